@@ -1,0 +1,159 @@
+/*
+ * sp.h -- C ABI of the MI355X (gfx950) K-student forward of Student Parallelism.
+ *
+ * The library runs the inference hot path of the paper's method: a group of K
+ * shallow BERT-like student encoders, all evaluated on the same padding-free
+ * batch of variable-length sequences, whose per-student classifier outputs are
+ * summed over the first k_active students (boosting ensemble, Section 3.1 Eq. 1;
+ * classifier on the ensembled representation, Section 3.2 Algorithm 2 lines 5-6;
+ * students are dropped from the tail at run time, Section 3.2 / Section 3.3.1).
+ *
+ * Conventions for every entry point
+ *   - return value 0 on success, a negative SP_E* code otherwise; no exception,
+ *     abort or global state crosses this boundary;
+ *   - "host" / "device" on a pointer says where the memory lives; the library
+ *     never takes ownership of caller memory and never frees it;
+ *   - all device memory (weight arena, workspace, inputs, outputs) is allocated
+ *     by the caller; sp_forward itself allocates nothing and does not
+ *     synchronise with the host: it enqueues kernels on the given stream and
+ *     returns.
+ */
+#ifndef SP_H_
+#define SP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    SP_OK = 0,
+    SP_EINVAL = -1,   /* null or misaligned pointer, malformed config */
+    SP_ESHAPE = -2,   /* batch < 1, total_tokens < batch, max_seqlen > max_pos, unsupported head width ... */
+    SP_EKACTIVE = -3, /* k_active outside 1..K */
+    SP_ENOMEM = -4,   /* weight blob, arena or workspace smaller than required */
+    SP_EHIP = -5      /* a HIP runtime call failed */
+};
+
+enum { SP_DTYPE_FP32 = 0, SP_DTYPE_BF16 = 1 };
+
+/* Shape of the student group.  All students share one architecture (Section 3.1:
+ * homogeneous students so that none is a straggler). */
+typedef struct {
+    int32_t K;        /* students in the group, index = training order */
+    int32_t layers;   /* transformer layers per student */
+    int32_t hidden;   /* H */
+    int32_t heads;    /* A; head width H/A must be 64 */
+    int32_t ffn;      /* F */
+    int32_t vocab;    /* V */
+    int32_t max_pos;  /* P: longest sequence a student can take */
+    int32_t classes;  /* C, 1..16 */
+    int32_t dtype;    /* SP_DTYPE_FP32: fp32 storage and arithmetic;
+                         SP_DTYPE_BF16: bf16 weights and activations, fp32 accumulation,
+                         LayerNorm statistics, softmax, GELU, pooling and logits */
+    float ln_eps;     /* LayerNorm epsilon (BERT: 1e-12) */
+} sp_config;
+
+typedef struct sp_model sp_model; /* opaque host-side handle */
+
+/* Canonical host weight blob: float32, per student m = 0..K-1 in this order
+ *   tok_emb[V][H] pos_emb[P][H] emb_ln_g[H] emb_ln_b[H]
+ *   per layer: Wq[H][H] bq[H] Wk[H][H] bk[H] Wv[H][H] bv[H] Wo[H][H] bo[H]
+ *              ln1_g[H] ln1_b[H] W1[H][F] b1[F] W2[F][H] b2[H] ln2_g[H] ln2_b[H]
+ *   Wp[H][H] bp[H] Wc[H][C] bc[C]
+ * every matrix [in][out] row-major.  The ensemble multipliers alpha of Eq. 1
+ * are expected folded into Wc (and the shared classifier bias placed in
+ * student 0's bc): a linear classifier on sum_m alpha_m p_m equals the sum of
+ * per-student heads alpha_m Wc.  Returns the number of floats in the blob, 0
+ * for a malformed config. */
+size_t sp_blob_floats(const sp_config* cfg);
+
+/* Device bytes needed for the repacked weights of the whole group. */
+size_t sp_arena_bytes(const sp_config* cfg);
+
+/* Device bytes of workspace sp_forward needs for a call with at most
+ * max_tokens packed tokens and max_batch sequences (monotone in both). */
+size_t sp_workspace_bytes(const sp_config* cfg, int32_t max_tokens, int32_t max_batch);
+
+/* Load the group (Algorithm 1 leaves the students in training order; that order
+ * is kept: student 0 is the one that survives every pruning).
+ *   host_weights  host, read-only, nfloats float32 values in blob order
+ *   device_arena  device, caller-allocated, >= sp_arena_bytes, 256-byte aligned;
+ *                 filled here (bf16 mode rounds to nearest even once) and
+ *                 referenced by the returned handle until sp_free
+ *   hip_stream    hipStream_t (or NULL for the default stream) the upload is
+ *                 ordered on; the call returns after the upload has completed
+ *   out           receives the handle
+ * Errors: SP_EINVAL, SP_ESHAPE (config the kernels do not support), SP_ENOMEM
+ * (nfloats or arena_bytes too small), SP_EHIP. */
+int sp_load_students(const sp_config* cfg, const float* host_weights, size_t nfloats,
+                     void* device_arena, size_t arena_bytes, void* hip_stream, sp_model** out);
+
+/* One forward pass (Section 3.3: one batch of individual samples and the current
+ * student number in, one prediction per sample out).
+ *   token_ids    device int32 [total_tokens]: the sequences back to back, no
+ *                padding; values in 0..V-1
+ *   cu_seqlens   device int32 [batch+1]: cu[0] = 0, cu[b+1] - cu[b] = length of
+ *                sequence b (>= 1), cu[batch] = total_tokens.  The first token
+ *                of a sequence is the one whose final state is pooled; a token's
+ *                position is its index inside its own sequence.
+ *   max_seqlen   upper bound on every sequence length in this call, <= P
+ *   k_active     1..K: only students 0..k_active-1 are evaluated and summed,
+ *                in that order, in fp32
+ *   workspace    device, 256-byte aligned, >= sp_workspace_bytes(cfg,
+ *                total_tokens, batch); contents undefined afterwards; calls
+ *                that may overlap in time need separate workspaces
+ *   logits_out   device float32 [batch][classes] row-major, overwritten
+ *   hip_stream   hipStream_t (or NULL); kernels are enqueued there
+ * Contents of token_ids / cu_seqlens are not inspected on the host (that
+ * would need a synchronisation): ids outside the vocabulary or inconsistent
+ * offsets are the caller's error; ids are clamped into the table and lengths
+ * into 1..max_seqlen on the device so that no access leaves its buffer.
+ * Errors: SP_EINVAL, SP_ESHAPE, SP_EKACTIVE, SP_ENOMEM, SP_EHIP (launch failure). */
+int sp_forward(const sp_model* model, const int32_t* token_ids, const int32_t* cu_seqlens,
+               int32_t batch, int32_t total_tokens, int32_t max_seqlen, int32_t k_active,
+               void* workspace, size_t workspace_bytes, float* logits_out, void* hip_stream);
+
+/* Releases the host handle only; the arena stays the caller's. */
+void sp_free(sp_model* model);
+
+/* Static description of an error code. */
+const char* sp_strerror(int code);
+
+/* Padding-free packing offsets on the host (Section 3.3.2 and Table 4 "with
+ * padding" motivate batches without padding): cu[0] = 0, cu[i+1] = cu[i] +
+ * lengths[i].  lengths_host [batch], cu_seqlens_host [batch+1].  SP_ESHAPE if a
+ * length is < 1 or the total exceeds INT32_MAX. */
+int sp_pack(const int32_t* lengths_host, int32_t batch, int32_t* cu_seqlens_host);
+
+/* Byte offsets, inside a workspace laid out for (total_tokens, batch), of the
+ * intermediate activations a forward leaves behind; for tests and profiling.
+ * Each activation tensor is [k_active][rows][width] with `rows` >= total_tokens
+ * (token-tile padded) in the model's activation type (float or bf16), row-major.
+ *   x    [rows][H]  hidden state entering the next layer (after the last layer:
+ *                   the final states)
+ *   qkv  [rows][3H] query | key | value projections of the last layer run
+ *   att  [rows][H]  attention output of the last layer run
+ *   x1   [rows][H]  state after the attention block's LayerNorm
+ *   g    [rows][F]  GELU(FFN up-projection)
+ *   z    float32 [K][batch][C] per-student classifier outputs before the sum */
+typedef struct {
+    size_t x, qkv, att, x1, g, z;
+    int32_t rows;      /* padded token rows per student */
+    int32_t act_bytes; /* 4 or 2 */
+} sp_ws_layout;
+int sp_workspace_layout(const sp_config* cfg, int32_t total_tokens, int32_t batch, sp_ws_layout* out);
+
+/* Same as sp_forward but stops after `stop_after_layers` transformer layers
+ * (0 = after the embedding LayerNorm) without computing logits; the
+ * intermediates can then be read through sp_workspace_layout.  For tests. */
+int sp_forward_partial(const sp_model* model, const int32_t* token_ids, const int32_t* cu_seqlens,
+                       int32_t batch, int32_t total_tokens, int32_t max_seqlen, int32_t k_active,
+                       int32_t stop_after_layers, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SP_H_ */

@@ -1,0 +1,342 @@
+// C ABI of libsp_mi355x.so: argument checks, weight upload, workspace carve-up
+// and the order in which the kernels of one forward pass are enqueued.
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <thread>
+#include <vector>
+
+#include "sp_internal.h"
+
+namespace sp {
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+static bool config_ok(const sp_config* c)
+{
+    if (!c) return false;
+    if (c->K < 1 || c->layers < 1 || c->hidden < 1 || c->heads < 1 || c->ffn < 1 || c->vocab < 1 || c->max_pos < 1 ||
+        c->classes < 1)
+        return false;
+    if (c->dtype != SP_DTYPE_FP32 && c->dtype != SP_DTYPE_BF16) return false;
+    if (!(c->ln_eps >= 0.f)) return false;
+    return true;
+}
+
+// what the kernels support
+static bool config_supported(const sp_config& c)
+{
+    if (c.hidden % c.heads || c.hidden / c.heads != 64) return false;
+    if (c.classes > 16 || c.hidden > 1024) return false;
+    if (c.dtype == SP_DTYPE_BF16) {
+        if (c.hidden % 64 || c.ffn % 64) return false;
+    } else {
+        if (c.hidden % 64 || c.ffn % 64) return false;
+    }
+    return true;
+}
+
+ArenaLayout make_arena_layout(const sp_config& c)
+{
+    const size_t H = c.hidden, F = c.ffn, C = c.classes;
+    const size_t wb = c.dtype == SP_DTYPE_BF16 ? 2 : 4;  // bytes per matrix / table element
+    ArenaLayout L{};
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    L.tok = take((size_t)c.vocab * H * wb);
+    L.pos = take((size_t)c.max_pos * H * wb);
+    L.emb_g = take(H * 4);
+    L.emb_b = take(H * 4);
+    L.layer0 = o;
+    {
+        size_t base = o;
+        L.wqkv = take(3 * H * H * wb) - base;
+        L.bqkv = take(3 * H * 4) - base;
+        L.wo = take(H * H * wb) - base;
+        L.bo = take(H * 4) - base;
+        L.ln1g = take(H * 4) - base;
+        L.ln1b = take(H * 4) - base;
+        L.w1 = take(F * H * wb) - base;
+        L.b1 = take(F * 4) - base;
+        L.w2 = take(H * F * wb) - base;
+        L.b2 = take(H * 4) - base;
+        L.ln2g = take(H * 4) - base;
+        L.ln2b = take(H * 4) - base;
+        L.layer_stride = o - base;
+        o = base + L.layer_stride * (size_t)c.layers;
+    }
+    L.wp = take(H * H * wb);
+    L.bp = take(H * 4);
+    L.wc = take(C * H * wb);
+    L.bc = take(C * 4);
+    L.student_stride = align_up(o, 4096);
+    return L;
+}
+
+WsLayout make_ws_layout(const sp_config& c, int total_tokens, int batch)
+{
+    WsLayout W{};
+    const size_t ab = c.dtype == SP_DTYPE_BF16 ? 2 : 4;
+    const size_t rows = align_up((size_t)total_tokens, kRowPad);
+    const size_t K = c.K, H = c.hidden, F = c.ffn;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    W.x = take(K * rows * H * ab);
+    W.qkv = take(K * rows * 3 * H * ab);
+    W.att = take(K * rows * H * ab);
+    W.u = take(K * rows * H * ab);
+    W.x1 = take(K * rows * H * ab);
+    W.g = take(K * rows * F * ab);
+    W.z = take(K * (size_t)batch * c.classes * 4);
+    W.zpart = take(K * (size_t)(H / 64) * batch * c.classes * 4);
+    W.end = o;
+    W.rows = (int)rows;
+    W.act_bytes = (int)ab;
+    return W;
+}
+
+static size_t student_blob_floats(const sp_config& c)
+{
+    const size_t H = c.hidden, F = c.ffn, C = c.classes;
+    const size_t layer = 4 * (H * H + H) + 2 * H + (H * F + F) + (F * H + H) + 2 * H;
+    return (size_t)c.vocab * H + (size_t)c.max_pos * H + 2 * H + (size_t)c.layers * layer + H * H + H + H * C + C;
+}
+
+// ---- host-side conversion into the arena image --------------------------------
+
+static inline uint16_t f32_to_bf16_rne(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);  // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+struct Writer {
+    bool bf16;
+    // copy n values as the arena's matrix element type
+    void copy(char* dst, const float* src, size_t n) const
+    {
+        if (bf16) {
+            uint16_t* d = (uint16_t*)dst;
+            for (size_t i = 0; i < n; ++i) d[i] = f32_to_bf16_rne(src[i]);
+        } else {
+            memcpy(dst, src, n * 4);
+        }
+    }
+    // dst[o][i] = src[i][o]; src is [n_in][n_out]; dst row stride n_in
+    void transpose(char* dst, const float* src, size_t n_in, size_t n_out) const
+    {
+        const size_t T = 32;
+        for (size_t i0 = 0; i0 < n_in; i0 += T)
+            for (size_t o0 = 0; o0 < n_out; o0 += T) {
+                const size_t i1 = i0 + T < n_in ? i0 + T : n_in, o1 = o0 + T < n_out ? o0 + T : n_out;
+                for (size_t o = o0; o < o1; ++o)
+                    for (size_t i = i0; i < i1; ++i) {
+                        const float v = src[i * n_out + o];
+                        if (bf16) ((uint16_t*)dst)[o * n_in + i] = f32_to_bf16_rne(v);
+                        else ((float*)dst)[o * n_in + i] = v;
+                    }
+            }
+    }
+};
+
+static void fill_student(const sp_config& c, const ArenaLayout& L, const float* src, char* dst)
+{
+    const size_t H = c.hidden, F = c.ffn, C = c.classes, wb = c.dtype == SP_DTYPE_BF16 ? 2 : 4;
+    Writer w{c.dtype == SP_DTYPE_BF16};
+    const float* p = src;
+    w.copy(dst + L.tok, p, (size_t)c.vocab * H); p += (size_t)c.vocab * H;
+    w.copy(dst + L.pos, p, (size_t)c.max_pos * H); p += (size_t)c.max_pos * H;
+    memcpy(dst + L.emb_g, p, H * 4); p += H;
+    memcpy(dst + L.emb_b, p, H * 4); p += H;
+    for (int l = 0; l < c.layers; ++l) {
+        char* lb = dst + L.layer0 + (size_t)l * L.layer_stride;
+        for (int part = 0; part < 3; ++part) {  // Wq bq Wk bk Wv bv -> rows [part*H, part*H+H) of the fused matrix
+            w.transpose(lb + L.wqkv + (size_t)part * H * H * wb, p, H, H); p += H * H;
+            memcpy(lb + L.bqkv + (size_t)part * H * 4, p, H * 4); p += H;
+        }
+        w.transpose(lb + L.wo, p, H, H); p += H * H;
+        memcpy(lb + L.bo, p, H * 4); p += H;
+        memcpy(lb + L.ln1g, p, H * 4); p += H;
+        memcpy(lb + L.ln1b, p, H * 4); p += H;
+        w.transpose(lb + L.w1, p, H, F); p += H * F;
+        memcpy(lb + L.b1, p, F * 4); p += F;
+        w.transpose(lb + L.w2, p, F, H); p += F * H;
+        memcpy(lb + L.b2, p, H * 4); p += H;
+        memcpy(lb + L.ln2g, p, H * 4); p += H;
+        memcpy(lb + L.ln2b, p, H * 4); p += H;
+    }
+    w.copy(dst + L.wp, p, H * H); p += H * H;
+    memcpy(dst + L.bp, p, H * 4); p += H;
+    w.copy(dst + L.wc, p, H * C); p += H * C;
+    memcpy(dst + L.bc, p, C * 4); p += C;
+}
+
+static int run_forward(const sp_model* M, const int32_t* ids, const int32_t* cu, int B, int T, int max_seqlen, int k,
+                       int stop_layers, bool with_head, void* ws, size_t ws_bytes, float* logits, hipStream_t s)
+{
+    if (!M || !ids || !cu || !ws || (with_head && !logits)) return SP_EINVAL;
+    if (((uintptr_t)ws & 255) || ((uintptr_t)ids & 3) || ((uintptr_t)cu & 3) || ((uintptr_t)logits & 3)) return SP_EINVAL;
+    const sp_config& c = M->cfg;
+    if (B < 1 || T < B || max_seqlen < 1 || max_seqlen > c.max_pos || (int64_t)B * max_seqlen < T) return SP_ESHAPE;
+    if (k < 1 || k > c.K) return SP_EKACTIVE;
+    if (stop_layers < 0 || stop_layers > c.layers) return SP_EINVAL;
+    const WsLayout W = make_ws_layout(c, T, B);
+    if (ws_bytes < W.end) return SP_ENOMEM;
+
+    char* w = (char*)ws;
+    const int H = c.hidden, F = c.ffn, rows = W.rows;
+    // rows actually computed: the packed tokens rounded up to the token tile the GEMMs will use
+    const int mtile = T > 256 ? 256 : (T > 64 ? 128 : 64);
+    const int mrows = (T + mtile - 1) / mtile * mtile;
+    const size_t ab = W.act_bytes;
+    void *x = w + W.x, *qkv = w + W.qkv, *att = w + W.att, *u = w + W.u, *x1 = w + W.x1, *g = w + W.g;
+    float* z = (float*)(w + W.z);
+    const size_t sH = (size_t)rows * H * ab, s3H = 3 * sH, sF = (size_t)rows * F * ab;
+    const ArenaLayout& L = M->L;
+
+#define SP_TRY(expr) do { if ((expr) != hipSuccess) return SP_EHIP; } while (0)
+    SP_TRY(launch_embed_ln(M, ids, cu, B, T, rows, mrows, k, x, s));
+    for (int l = 0; l < stop_layers; ++l) {
+        const size_t lo = L.layer0 + (size_t)l * L.layer_stride;
+        SP_TRY(launch_gemm(M, x, H, lo + L.wqkv, lo + L.bqkv, qkv, 3 * H, nullptr, 0, mrows, 3 * H, H, k, EPI_BIAS, sH,
+                           s3H, 0, s));
+        SP_TRY(launch_attention(M, qkv, att, cu, B, T, max_seqlen, rows, k, s));
+        SP_TRY(launch_gemm(M, att, H, lo + L.wo, lo + L.bo, u, H, x, H, mrows, H, H, k, EPI_BIAS_RESIDUAL, sH, sH, sH,
+                           s));
+        SP_TRY(launch_layernorm(M, u, x1, rows, mrows, k, lo + L.ln1g, lo + L.ln1b, s));
+        SP_TRY(launch_gemm(M, x1, H, lo + L.w1, lo + L.b1, g, F, nullptr, 0, mrows, F, H, k, EPI_BIAS_GELU, sH, sF, 0,
+                           s));
+        SP_TRY(launch_gemm(M, g, F, lo + L.w2, lo + L.b2, u, H, x1, H, mrows, H, F, k, EPI_BIAS_RESIDUAL, sF, sH, sH,
+                           s));
+        SP_TRY(launch_layernorm(M, u, x, rows, mrows, k, lo + L.ln2g, lo + L.ln2b, s));
+    }
+    if (with_head) SP_TRY(launch_head(M, x, cu, B, T, rows, k, z, (float*)(w + W.zpart), logits, s));
+#undef SP_TRY
+    return SP_OK;
+}
+
+}  // namespace sp
+
+using namespace sp;
+
+extern "C" {
+
+size_t sp_blob_floats(const sp_config* cfg)
+{
+    if (!config_ok(cfg)) return 0;
+    return (size_t)cfg->K * student_blob_floats(*cfg);
+}
+
+size_t sp_arena_bytes(const sp_config* cfg)
+{
+    if (!config_ok(cfg)) return 0;
+    return make_arena_layout(*cfg).student_stride * (size_t)cfg->K;
+}
+
+size_t sp_workspace_bytes(const sp_config* cfg, int32_t max_tokens, int32_t max_batch)
+{
+    if (!config_ok(cfg) || max_tokens < 1 || max_batch < 1) return 0;
+    return make_ws_layout(*cfg, max_tokens, max_batch).end;
+}
+
+int sp_workspace_layout(const sp_config* cfg, int32_t total_tokens, int32_t batch, sp_ws_layout* out)
+{
+    if (!config_ok(cfg) || !out) return SP_EINVAL;
+    if (total_tokens < 1 || batch < 1) return SP_ESHAPE;
+    const WsLayout W = make_ws_layout(*cfg, total_tokens, batch);
+    out->x = W.x; out->qkv = W.qkv; out->att = W.att; out->x1 = W.x1; out->g = W.g; out->z = W.z;
+    out->rows = W.rows; out->act_bytes = W.act_bytes;
+    return SP_OK;
+}
+
+int sp_load_students(const sp_config* cfg, const float* host_weights, size_t nfloats, void* device_arena,
+                     size_t arena_bytes, void* hip_stream, sp_model** out)
+{
+    if (!config_ok(cfg) || !host_weights || !device_arena || !out) return SP_EINVAL;
+    if ((uintptr_t)device_arena & 255) return SP_EINVAL;
+    if (!config_supported(*cfg)) return SP_ESHAPE;
+    const size_t per = student_blob_floats(*cfg);
+    if (nfloats < per * (size_t)cfg->K) return SP_ENOMEM;
+    const ArenaLayout L = make_arena_layout(*cfg);
+    if (arena_bytes < L.student_stride * (size_t)cfg->K) return SP_ENOMEM;
+
+    sp_model* m = new (std::nothrow) sp_model;
+    if (!m) return SP_ENOMEM;
+    m->cfg = *cfg; m->arena = (char*)device_arena; m->L = L;
+
+    // Build the arena image on the host, a few students at a time, then upload.
+    const int K = cfg->K;
+    const int group = K < 4 ? K : 4;
+    char* stage = (char*)calloc((size_t)group, L.student_stride);
+    if (!stage) { delete m; return SP_ENOMEM; }
+    hipStream_t s = (hipStream_t)hip_stream;
+    int rc = SP_OK;
+    for (int m0 = 0; m0 < K && rc == SP_OK; m0 += group) {
+        const int n = m0 + group <= K ? group : K - m0;
+        std::vector<std::thread> th;
+        for (int i = 0; i < n; ++i)
+            th.emplace_back(fill_student, std::cref(*cfg), std::cref(L), host_weights + (size_t)(m0 + i) * per,
+                            stage + (size_t)i * L.student_stride);
+        for (auto& t : th) t.join();
+        if (hipMemcpyAsync((char*)device_arena + (size_t)m0 * L.student_stride, stage, (size_t)n * L.student_stride,
+                           hipMemcpyHostToDevice, s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess)
+            rc = SP_EHIP;
+    }
+    free(stage);
+    if (rc != SP_OK) { delete m; return rc; }
+    *out = m;
+    return SP_OK;
+}
+
+int sp_forward(const sp_model* model, const int32_t* token_ids, const int32_t* cu_seqlens, int32_t batch,
+               int32_t total_tokens, int32_t max_seqlen, int32_t k_active, void* workspace, size_t workspace_bytes,
+               float* logits_out, void* hip_stream)
+{
+    if (!model) return SP_EINVAL;
+    return run_forward(model, token_ids, cu_seqlens, batch, total_tokens, max_seqlen, k_active, model->cfg.layers,
+                       true, workspace, workspace_bytes, logits_out, (hipStream_t)hip_stream);
+}
+
+int sp_forward_partial(const sp_model* model, const int32_t* token_ids, const int32_t* cu_seqlens, int32_t batch,
+                       int32_t total_tokens, int32_t max_seqlen, int32_t k_active, int32_t stop_after_layers,
+                       void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!model) return SP_EINVAL;
+    return run_forward(model, token_ids, cu_seqlens, batch, total_tokens, max_seqlen, k_active, stop_after_layers,
+                       false, workspace, workspace_bytes, nullptr, (hipStream_t)hip_stream);
+}
+
+void sp_free(sp_model* model) { delete model; }
+
+const char* sp_strerror(int code)
+{
+    switch (code) {
+        case SP_OK: return "ok";
+        case SP_EINVAL: return "invalid argument (null or misaligned pointer, malformed config)";
+        case SP_ESHAPE: return "unsupported or inconsistent shape";
+        case SP_EKACTIVE: return "k_active outside 1..K";
+        case SP_ENOMEM: return "buffer smaller than required";
+        case SP_EHIP: return "HIP runtime error";
+        default: return "unknown error code";
+    }
+}
+
+int sp_pack(const int32_t* lengths_host, int32_t batch, int32_t* cu_seqlens_host)
+{
+    if (!lengths_host || !cu_seqlens_host) return SP_EINVAL;
+    if (batch < 1) return SP_ESHAPE;
+    int64_t acc = 0;
+    cu_seqlens_host[0] = 0;
+    for (int32_t i = 0; i < batch; ++i) {
+        if (lengths_host[i] < 1) return SP_ESHAPE;
+        acc += lengths_host[i];
+        if (acc > INT32_MAX) return SP_ESHAPE;
+        cu_seqlens_host[i + 1] = (int32_t)acc;
+    }
+    return SP_OK;
+}
+
+}  // extern "C"

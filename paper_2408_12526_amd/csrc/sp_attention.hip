@@ -1,0 +1,236 @@
+// Multi-head self-attention over a packed batch: every sequence attends to itself only,
+// over exactly its own tokens (cu_seqlens gives the boundaries); head width is 64.
+#include "sp_internal.h"
+
+namespace sp {
+
+namespace {
+
+constexpr int kD = 64;          // head width
+constexpr int kQPerWg = 128;    // queries per workgroup: 4 waves x 32
+constexpr int kKeyTile = 64;    // keys staged in LDS per step
+constexpr int kKStride = kKeyTile + 1;   // 16-byte units per k-group of the key tile
+constexpr int kVStride = 68;    // bf16 elements per row of the transposed value tile (136 B)
+
+// -------------------------------------------------------------------------------------
+// bf16 kernel on the matrix cores.  One workgroup = (student, sequence, head, block of 128
+// queries); wave w owns queries q0 + 32w .. + 31.  Per 64-key tile:
+//   S^T = K Q^T      (A operand: key rows from LDS, B operand: the wave's queries, kept in
+//                     registers for the whole kernel)
+//   online softmax   per query = per lane column; a query's keys sit in 16 accumulator
+//                    registers of two lanes (l and l + 32)
+//   O^T += V^T P^T   (A operand: transposed value tile from LDS; B operand: the
+//                     probabilities, which already sit in the B-operand register layout
+//                     once the reduction slots of V^T are enumerated in the same key order)
+// -------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void attention_bf16_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ att,
+                                                             const int32_t* __restrict__ cu, int B, int Tn, int rows,
+                                                             int H, int heads, int max_seqlen, int nqc)
+{
+    __shared__ uint4 sK[8 * kKStride];             // [d-group of 8][key]
+    __shared__ __attribute__((aligned(16))) bf16 sVt[kD * kVStride];   // [d][key]
+
+    const int m = blockIdx.y;
+    int idx = blockIdx.x;
+    const int qc = idx % nqc; idx /= nqc;
+    const int h = idx % heads;
+    const int b = idx / heads;
+    int t0 = cu[b], t1 = cu[b + 1];
+    t0 = t0 < 0 ? 0 : (t0 > Tn - 1 ? Tn - 1 : t0);
+    int L = t1 - t0;
+    L = L < 1 ? 1 : L;
+    L = L > max_seqlen ? max_seqlen : L;
+    L = L > Tn - t0 ? Tn - t0 : L;
+    const int q0 = qc * kQPerWg;
+    if (q0 >= L) return;                            // whole workgroup leaves together
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int j = lane & 31, g = lane >> 5;
+    const size_t ld = (size_t)3 * H;
+    const bf16* base = qkv + ((size_t)m * rows + t0) * ld + h * kD;
+    const int q = q0 + wave * 32 + j;               // this lane's query
+    const bool wave_active = q0 + wave * 32 < L;
+
+    // queries: B operand of S^T = K Q^T, four k-steps of 16 over d
+    bf16x8 qf[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        uint4 t = {0, 0, 0, 0};
+        if (q < L) t = *(const uint4*)(base + (size_t)q * ld + 16 * s + 8 * g);
+        qf[s] = __builtin_bit_cast(bf16x8, t);
+    }
+
+    f32x16 o[2];
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o[db][e] = 0.f;
+    float mrun = -INFINITY, lrun = 0.f;
+    const float sl2 = 0.125f * 1.44269504088896341f;   // 1/sqrt(64) * log2(e)
+
+    const int lrow = tid >> 3, lc = tid & 7;
+    for (int kt0 = 0; kt0 < L; kt0 += kKeyTile) {
+        // stage the key tile and the transposed value tile (keys beyond L are zero)
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const int key = lrow + 32 * p;
+            uint4 kk = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
+            if (kt0 + key < L) {
+                const bf16* r = base + (size_t)(kt0 + key) * ld + lc * 8;
+                kk = *(const uint4*)(r + H);
+                vv = *(const uint4*)(r + 2 * H);
+            }
+            sK[lc * kKStride + key] = kk;
+            const bf16x8 v8 = __builtin_bit_cast(bf16x8, vv);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sVt[(lc * 8 + e) * kVStride + key] = v8[e];
+        }
+        __syncthreads();
+
+        if (wave_active) {
+            // scores of this wave's 32 queries against the 64 keys: two 32x32 blocks
+            f32x16 sc[2];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) sc[kb][e] = 0.f;
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const uint4 t = sK[(2 * s + g) * kKStride + kb * 32 + j];
+                    sc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, t), qf[s], sc[kb], 0, 0, 0);
+                }
+            }
+            // accumulator register v of this lane is key 8*(v/4) + 4*g + v%4 of its block
+            float mx = mrun;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int key = kt0 + kb * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+                    const float sv = key < L ? sc[kb][v] * sl2 : -INFINITY;
+                    sc[kb][v] = sv;
+                    mx = fmaxf(mx, sv);
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 32));          // the other half of the query's keys
+            const float alpha = exp2f(mrun - mx);        // first tile: exp2(-inf) = 0
+            mrun = mx;
+            float psum = 0.f;
+            bf16x8 pf[2][2];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const float p = exp2f(sc[kb][v] - mx);
+                    psum += p;
+                    pf[kb][v >> 3][v & 7] = (bf16)p;
+                }
+            lrun = lrun * alpha + psum;
+#pragma unroll
+            for (int db = 0; db < 2; ++db)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
+            // O^T += V^T P^T.  Reduction slot e of k-step s2 in block kb is key
+            // 32*kb + 16*s2 + 8*(e/4) + 4*g + e%4, the key held by register 8*s2 + e above.
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2) {
+                    const int kbase = kb * 32 + 16 * s2 + 4 * g;
+#pragma unroll
+                    for (int db = 0; db < 2; ++db) {
+                        const bf16* vr = sVt + (db * 32 + j) * kVStride + kbase;
+                        const bf16x4 lo = *(const bf16x4*)vr, hi = *(const bf16x4*)(vr + 8);
+                        const bf16x8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kb][s2], o[db], 0, 0, 0);
+                    }
+                }
+        }
+        __syncthreads();
+    }
+
+    if (wave_active) {
+        const float lsum = lrun + __shfl_xor(lrun, 32);
+        const float inv = 1.0f / lsum;
+        if (q < L) {
+            bf16* dst = att + ((size_t)m * rows + t0 + q) * H + h * kD;
+#pragma unroll
+            for (int db = 0; db < 2; ++db)
+#pragma unroll
+                for (int v4 = 0; v4 < 4; ++v4) {
+                    bf16x4 w;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) w[e] = (bf16)(o[db][4 * v4 + e] * inv);
+                    *(bf16x4*)(dst + db * 32 + 8 * v4 + 4 * g) = w;
+                }
+        }
+    }
+}
+
+// -------------------------------------------------------------------------------------
+// fp32 kernel: one thread per query, keys streamed from global memory (all threads of a
+// workgroup read the same key row), online softmax in registers, exact division.
+// -------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void attention_f32_kernel(const float* __restrict__ qkv, float* __restrict__ att,
+                                                           const int32_t* __restrict__ cu, int B, int Tn, int rows,
+                                                           int H, int heads, int max_seqlen, int nqc)
+{
+    const int m = blockIdx.y;
+    int idx = blockIdx.x;
+    const int qc = idx % nqc; idx /= nqc;
+    const int h = idx % heads;
+    const int b = idx / heads;
+    int t0 = cu[b], t1 = cu[b + 1];
+    t0 = t0 < 0 ? 0 : (t0 > Tn - 1 ? Tn - 1 : t0);
+    int L = t1 - t0;
+    L = L < 1 ? 1 : L;
+    L = L > max_seqlen ? max_seqlen : L;
+    L = L > Tn - t0 ? Tn - t0 : L;
+    const int q = qc * 64 + threadIdx.x;
+    if (q >= L) return;
+    const size_t ld = (size_t)3 * H;
+    const float* base = qkv + ((size_t)m * rows + t0) * ld + h * kD;
+    float qv[kD], o[kD];
+#pragma unroll
+    for (int e = 0; e < kD; ++e) { qv[e] = base[(size_t)q * ld + e]; o[e] = 0.f; }
+    float mrun = -INFINITY, lrun = 0.f;
+    for (int key = 0; key < L; ++key) {
+        const float* kr = base + (size_t)key * ld + H;
+        const float* vr = kr + H;
+        float sdot = 0.f;
+#pragma unroll
+        for (int e = 0; e < kD; ++e) sdot = fmaf(qv[e], kr[e], sdot);
+        sdot *= 0.125f;
+        const float mx = fmaxf(mrun, sdot);
+        const float alpha = expf(mrun - mx), p = expf(sdot - mx);
+        lrun = lrun * alpha + p;
+#pragma unroll
+        for (int e = 0; e < kD; ++e) o[e] = o[e] * alpha + p * vr[e];
+        mrun = mx;
+    }
+    float* dst = att + ((size_t)m * rows + t0 + q) * H + h * kD;
+#pragma unroll
+    for (int e = 0; e < kD; ++e) dst[e] = o[e] / lrun;
+}
+
+}  // namespace
+
+hipError_t launch_attention(const sp_model* M, const void* qkv, void* att, const int32_t* cu, int B, int T,
+                            int max_seqlen, int rows, int k, hipStream_t s)
+{
+    const sp_config& c = M->cfg;
+    if (c.hidden / c.heads != kD) return hipErrorInvalidValue;
+    if (c.dtype == SP_DTYPE_BF16) {
+        const int nqc = (max_seqlen + kQPerWg - 1) / kQPerWg;
+        dim3 grid((unsigned)(B * c.heads * nqc), k);
+        hipLaunchKernelGGL(attention_bf16_kernel, grid, dim3(256), 0, s, (const bf16*)qkv, (bf16*)att, cu, B, T, rows,
+                           c.hidden, c.heads, max_seqlen, nqc);
+    } else {
+        const int nqc = (max_seqlen + 63) / 64;
+        dim3 grid((unsigned)(B * c.heads * nqc), k);
+        hipLaunchKernelGGL(attention_f32_kernel, grid, dim3(64), 0, s, (const float*)qkv, (float*)att, cu, B, T, rows,
+                           c.hidden, c.heads, max_seqlen, nqc);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace sp

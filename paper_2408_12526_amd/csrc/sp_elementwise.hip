@@ -1,0 +1,270 @@
+// Bandwidth-bound kernels of the student forward: embedding gather + LayerNorm,
+// stand-alone LayerNorm, and the pooled head with the cross-student sum.
+#include "sp_internal.h"
+
+namespace sp {
+
+namespace {
+
+constexpr int kMaxChunks = 4;  // 8-element chunks per lane: hidden <= 64 * 8 * kMaxChunks
+
+__device__ inline float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+__device__ inline void load8(const float* p, float (&v)[8])
+{
+    const f32x4 a = *(const f32x4*)p, b = *(const f32x4*)(p + 4);
+    v[0] = a[0]; v[1] = a[1]; v[2] = a[2]; v[3] = a[3]; v[4] = b[0]; v[5] = b[1]; v[6] = b[2]; v[7] = b[3];
+}
+__device__ inline void load8(const bf16* p, float (&v)[8])
+{
+    const bf16x8 a = *(const bf16x8*)p;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = (float)a[i];
+}
+__device__ inline void store8(float* p, const float (&v)[8])
+{
+    *(f32x4*)p = f32x4{v[0], v[1], v[2], v[3]};
+    *(f32x4*)(p + 4) = f32x4{v[4], v[5], v[6], v[7]};
+}
+__device__ inline void store8(bf16* p, const float (&v)[8])
+{
+    bf16x8 a;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a[i] = (bf16)v[i];
+    *(bf16x8*)p = a;
+}
+
+// LayerNorm of one row held across a wave as v[chunk][8]; chunk c of lane l covers
+// elements 8*(l + 64c) .. +7.  Two passes over registers: mean, then centred variance.
+template <typename T>
+__device__ inline void ln_row_store(float (&v)[kMaxChunks][8], int nch, int lane, int H, const float* g,
+                                    const float* b, float eps, T* out)
+{
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < kMaxChunks; ++i)
+        if (lane + 64 * i < nch)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s += v[i][e];
+    const float mean = wave_sum(s) / (float)H;
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < kMaxChunks; ++i)
+        if (lane + 64 * i < nch)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { const float d = v[i][e] - mean; q += d * d; }
+    const float inv = 1.0f / sqrtf(wave_sum(q) / (float)H + eps);
+#pragma unroll
+    for (int i = 0; i < kMaxChunks; ++i) {
+        const int c = lane + 64 * i;
+        if (c < nch) {
+            float gg[8], bb[8], o[8];
+            load8(g + c * 8, gg);
+            load8(b + c * 8, bb);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = gg[e] * ((v[i][e] - mean) * inv) + bb[e];
+            store8(out + c * 8, o);
+        }
+    }
+}
+
+// One wave per packed token row, grid.y = student.
+template <typename T>
+__global__ __launch_bounds__(256) void embed_ln_kernel(const char* arena, size_t student_stride, size_t tok_off,
+                                                       size_t pos_off, size_t g_off, size_t b_off,
+                                                       const int32_t* __restrict__ ids,
+                                                       const int32_t* __restrict__ cu, int B, int Tn, int rows,
+                                                       int mrows, int H, int V, int P, float eps, T* __restrict__ x)
+{
+    const int m = blockIdx.y, lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= mrows) return;
+    const int nch = H >> 3;
+    T* out = x + ((size_t)m * rows + row) * H;
+    if (row >= Tn) {  // padding rows of the token tile: defined contents, never read by attention or the head
+        const float zero[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        for (int c = lane; c < nch; c += 64) store8(out + c * 8, zero);
+        return;
+    }
+    // sequence of this row: largest b with cu[b] <= row
+    int lo = 0, hi = B;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (cu[mid] <= row) lo = mid; else hi = mid;
+    }
+    int pos = row - cu[lo];
+    pos = pos < 0 ? 0 : (pos >= P ? P - 1 : pos);
+    int id = ids[row];
+    id = id < 0 ? 0 : (id >= V ? V - 1 : id);
+    const char* sb = arena + (size_t)m * student_stride;
+    const T* te = (const T*)(sb + tok_off) + (size_t)id * H;
+    const T* pe = (const T*)(sb + pos_off) + (size_t)pos * H;
+    float v[kMaxChunks][8];
+#pragma unroll
+    for (int i = 0; i < kMaxChunks; ++i) {
+        const int c = lane + 64 * i;
+        if (c < nch) {
+            float a[8], p8[8];
+            load8(te + c * 8, a);
+            load8(pe + c * 8, p8);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[i][e] = a[e] + p8[e];
+        }
+    }
+    ln_row_store<T>(v, nch, lane, H, (const float*)(sb + g_off), (const float*)(sb + b_off), eps, out);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void layernorm_kernel(const char* arena, size_t student_stride, size_t g_off,
+                                                        size_t b_off, const T* __restrict__ u, T* __restrict__ out,
+                                                        int rows, int mrows, int H, float eps)
+{
+    const int m = blockIdx.y, lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= mrows) return;
+    const int nch = H >> 3;
+    const T* in = u + ((size_t)m * rows + row) * H;
+    float v[kMaxChunks][8];
+#pragma unroll
+    for (int i = 0; i < kMaxChunks; ++i) {
+        const int c = lane + 64 * i;
+        if (c < nch) load8(in + c * 8, v[i]);
+    }
+    const char* sb = arena + (size_t)m * student_stride;
+    ln_row_store<T>(v, nch, lane, H, (const float*)(sb + g_off), (const float*)(sb + b_off), eps,
+                    out + ((size_t)m * rows + row) * H);
+}
+
+// ---- head -------------------------------------------------------------------------
+// Stage 1: one workgroup = (group of kSeqPerWg sequences, student, slice of 64 pooler outputs).
+// pooled[n] = tanh(bp[n] + sum_i cls[i] Wp[i][n]); the slice's share of the classifier,
+// sum_{n in slice} pooled[n] Wc[n][c], goes to zpart[m][slice][b][c].
+constexpr int kSeqPerWg = 8;
+
+template <typename T>
+__global__ __launch_bounds__(256) void head_pool_kernel(const char* arena, size_t student_stride, size_t wp_off,
+                                                        size_t bp_off, size_t wc_off, const T* __restrict__ x,
+                                                        const int32_t* __restrict__ cu, int B, int Tn, int rows, int H,
+                                                        int C, float* __restrict__ zpart)
+{
+    extern __shared__ float smem[];
+    float* xs = smem;                      // [kSeqPerWg][H]
+    float* red = smem + kSeqPerWg * H;     // [4][kSeqPerWg][64]
+    const int b0 = blockIdx.x * kSeqPerWg, m = blockIdx.y, slice = blockIdx.z, nslice = gridDim.z;
+    const int tid = threadIdx.x, lane = tid & 63, part = tid >> 6;
+    const int nseq = (B - b0) < kSeqPerWg ? (B - b0) : kSeqPerWg;
+    for (int s = 0; s < nseq; ++s) {
+        int r = cu[b0 + s];
+        r = r < 0 ? 0 : (r >= Tn ? Tn - 1 : r);
+        const T* src = x + ((size_t)m * rows + r) * H;
+        for (int i = tid; i < H; i += 256) xs[s * H + i] = (float)src[i];
+    }
+    __syncthreads();
+    const char* sb = arena + (size_t)m * student_stride;
+    const T* Wp = (const T*)(sb + wp_off);
+    const int n = slice * 64 + lane;
+    float acc[kSeqPerWg];
+#pragma unroll
+    for (int s = 0; s < kSeqPerWg; ++s) acc[s] = 0.f;
+    const int per = H / 4, i0 = part * per;   // this wave's share of the reduction index
+    for (int i = i0; i < i0 + per; ++i) {
+        const float w = (float)Wp[(size_t)i * H + n];
+#pragma unroll
+        for (int s = 0; s < kSeqPerWg; ++s) acc[s] += xs[s * H + i] * w;   // rows beyond nseq hold stale data: unused
+    }
+#pragma unroll
+    for (int s = 0; s < kSeqPerWg; ++s) red[(part * kSeqPerWg + s) * 64 + lane] = acc[s];
+    __syncthreads();
+    // wave `part` finishes sequences part, part+4: fixed order over the four shares
+    const float bpn = ((const float*)(sb + bp_off))[n];
+    const T* Wc = (const T*)(sb + wc_off);
+    for (int s = part; s < nseq; s += 4) {
+        float p = bpn;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) p += red[(q * kSeqPerWg + s) * 64 + lane];
+        p = tanhf(p);
+        for (int c = 0; c < C; ++c) {
+            const float t = wave_sum(p * (float)Wc[(size_t)n * C + c]);
+            if (lane == 0) zpart[(((size_t)m * nslice + slice) * B + (b0 + s)) * C + c] = t;
+        }
+    }
+}
+
+// Stage 2: z[m][b][c] = bc[m][c] + sum over slices (ascending); logits[b][c] = sum_m z (m ascending).
+__global__ void head_sum_kernel(const char* arena, size_t student_stride, size_t bc_off,
+                                const float* __restrict__ zpart, int B, int C, int k, int nslice,
+                                float* __restrict__ z, float* __restrict__ logits)
+{
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= B * C) return;
+    const int c = idx % C;
+    float total = 0.f;
+    for (int m = 0; m < k; ++m) {
+        float zm = 0.f;
+        for (int sl = 0; sl < nslice; ++sl) zm += zpart[((size_t)m * nslice + sl) * B * C + idx];
+        zm += ((const float*)(arena + (size_t)m * student_stride + bc_off))[c];
+        z[(size_t)m * B * C + idx] = zm;
+        total += zm;
+    }
+    logits[idx] = total;
+}
+
+}  // namespace
+
+hipError_t launch_embed_ln(const sp_model* M, const int32_t* ids, const int32_t* cu, int B, int T, int rows, int mrows,
+                           int k, void* x, hipStream_t s)
+{
+    const sp_config& c = M->cfg;
+    const ArenaLayout& L = M->L;
+    dim3 grid((mrows + 3) / 4, k);
+    if (c.dtype == SP_DTYPE_BF16)
+        hipLaunchKernelGGL(embed_ln_kernel<bf16>, grid, dim3(256), 0, s, M->arena, L.student_stride, L.tok, L.pos,
+                           L.emb_g, L.emb_b, ids, cu, B, T, rows, mrows, c.hidden, c.vocab, c.max_pos, c.ln_eps, (bf16*)x);
+    else
+        hipLaunchKernelGGL(embed_ln_kernel<float>, grid, dim3(256), 0, s, M->arena, L.student_stride, L.tok, L.pos,
+                           L.emb_g, L.emb_b, ids, cu, B, T, rows, mrows, c.hidden, c.vocab, c.max_pos, c.ln_eps, (float*)x);
+    return hipGetLastError();
+}
+
+hipError_t launch_layernorm(const sp_model* M, const void* u, void* out, int rows, int mrows, int k, size_t g_off,
+                            size_t b_off, hipStream_t s)
+{
+    const sp_config& c = M->cfg;
+    dim3 grid((mrows + 3) / 4, k);
+    if (c.dtype == SP_DTYPE_BF16)
+        hipLaunchKernelGGL(layernorm_kernel<bf16>, grid, dim3(256), 0, s, M->arena, M->L.student_stride, g_off, b_off,
+                           (const bf16*)u, (bf16*)out, rows, mrows, c.hidden, c.ln_eps);
+    else
+        hipLaunchKernelGGL(layernorm_kernel<float>, grid, dim3(256), 0, s, M->arena, M->L.student_stride, g_off, b_off,
+                           (const float*)u, (float*)out, rows, mrows, c.hidden, c.ln_eps);
+    return hipGetLastError();
+}
+
+hipError_t launch_head(const sp_model* M, const void* x, const int32_t* cu, int B, int T, int rows, int k, float* z,
+                       float* zpart, float* logits, hipStream_t s)
+{
+    const sp_config& c = M->cfg;
+    const ArenaLayout& L = M->L;
+    const int nslice = c.hidden / 64;
+    dim3 grid((B + kSeqPerWg - 1) / kSeqPerWg, k, nslice);
+    const size_t smem = (size_t)(kSeqPerWg * c.hidden + 4 * kSeqPerWg * 64) * sizeof(float);
+    if (c.dtype == SP_DTYPE_BF16)
+        hipLaunchKernelGGL(head_pool_kernel<bf16>, grid, dim3(256), smem, s, M->arena, L.student_stride, L.wp, L.bp,
+                           L.wc, (const bf16*)x, cu, B, T, rows, c.hidden, c.classes, zpart);
+    else
+        hipLaunchKernelGGL(head_pool_kernel<float>, grid, dim3(256), smem, s, M->arena, L.student_stride, L.wp, L.bp,
+                           L.wc, (const float*)x, cu, B, T, rows, c.hidden, c.classes, zpart);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int n = B * c.classes;
+    hipLaunchKernelGGL(head_sum_kernel, dim3((n + 255) / 256), dim3(256), 0, s, M->arena, L.student_stride, L.bc,
+                       zpart, B, c.classes, k, nslice, z, logits);
+    return hipGetLastError();
+}
+
+}  // namespace sp

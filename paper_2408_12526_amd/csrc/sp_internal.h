@@ -1,0 +1,81 @@
+// Internal declarations shared by the translation units of libsp_mi355x.so.
+// Nothing here is part of the C ABI (that is include/sp.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "sp.h"
+
+namespace sp {
+
+typedef __bf16 bf16;
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kRowPad = 256;  // activation rows per student are padded to a multiple of this
+
+// Byte offsets of every tensor inside one student's slab of the weight arena.
+// The encoder matrices are stored transposed with respect to the host blob,
+// [out][in], so that the reduction index is contiguous for both GEMM operands;
+// the pooler and classifier matrices keep the blob's [in][out] order.
+struct ArenaLayout {
+    size_t tok, pos, emb_g, emb_b;
+    size_t layer0, layer_stride;
+    // relative to the start of a layer
+    size_t wqkv, bqkv, wo, bo, ln1g, ln1b, w1, b1, w2, b2, ln2g, ln2b;
+    size_t wp, bp, wc, bc;
+    size_t student_stride;
+};
+
+ArenaLayout make_arena_layout(const sp_config& c);
+
+// Workspace carve-up for one call.
+struct WsLayout {
+    size_t x, qkv, att, u, x1, g, z, zpart, end;
+    int rows;
+    int act_bytes;
+};
+WsLayout make_ws_layout(const sp_config& c, int total_tokens, int batch);
+
+}  // namespace sp
+
+struct sp_model {
+    sp_config cfg;
+    char* arena;
+    sp::ArenaLayout L;
+};
+
+namespace sp {
+
+// ---- launchers (each returns the hipError_t of its launch) ------------------
+
+// X[m][row][:] = LN(tok[id[row]] + pos[row - cu[seq(row)]]) for row < T; zero rows up to `rows`.
+hipError_t launch_embed_ln(const sp_model* M, const int32_t* ids, const int32_t* cu, int B, int T, int rows,
+                           int mrows, int k, void* x, hipStream_t s);
+
+// out[m][row][:] = LN(u[m][row][:]; g, b); g/b are byte offsets into the student slab.
+hipError_t launch_layernorm(const sp_model* M, const void* u, void* out, int rows, int mrows, int k, size_t g_off,
+                            size_t b_off, hipStream_t s);
+
+enum Epilogue { EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_BIAS_RESIDUAL = 2 };
+
+// out[m][row][0..N) = epi(A[m][row][0..Kd) . W^T + bias), W stored [N][Kd] at w_off of each student.
+// lda / ldo / ldr are row strides in elements; residual may be null unless EPI_BIAS_RESIDUAL;
+// mrows (a multiple of 64, <= the padded row count) is how many rows are computed.
+hipError_t launch_gemm(const sp_model* M, const void* A, int lda, size_t w_off, size_t b_off, void* out, int ldo,
+                       const void* residual, int ldr, int mrows, int N, int Kd, int k, Epilogue epi,
+                       size_t a_student_stride, size_t o_student_stride, size_t r_student_stride, hipStream_t s);
+
+// att[m][t][h*64..] = softmax(q k^T / 8) v inside each sequence; qkv rows are [q | k | v] of width 3H.
+hipError_t launch_attention(const sp_model* M, const void* qkv, void* att, const int32_t* cu, int B, int T,
+                            int max_seqlen, int rows, int k, hipStream_t s);
+
+// z[m][b][c] = tanh(x[m][cu[b]] Wp + bp) Wc + bc ; logits[b][c] = sum_{m<k} z[m][b][c] (m ascending).
+hipError_t launch_head(const sp_model* M, const void* x, const int32_t* cu, int B, int T, int rows, int k, float* z,
+                       float* zpart, float* logits, hipStream_t s);
+
+}  // namespace sp

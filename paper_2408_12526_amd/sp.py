@@ -1,0 +1,185 @@
+"""Thin binding over libsp_mi355x.so (the C ABI declared in include/sp.h).
+
+Only argument marshalling happens here: torch supplies device memory and the
+current stream, every step of the forward runs in the library's HIP kernels.
+There is no fallback: importing this module without the built library, or
+calling it without a GPU, raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsp_mi355x.so")
+
+SP_DTYPE_FP32, SP_DTYPE_BF16 = 0, 1
+
+
+class sp_config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in
+                ("K", "layers", "hidden", "heads", "ffn", "vocab", "max_pos", "classes", "dtype")] + [
+        ("ln_eps", C.c_float)]
+
+
+class sp_ws_layout(C.Structure):
+    _fields_ = [(n, C.c_size_t) for n in ("x", "qkv", "att", "x1", "g", "z")] + [("rows", C.c_int32),
+                                                                                   ("act_bytes", C.c_int32)]
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2408_12526_amd.build` (there is no fallback path)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+    cfgp = C.POINTER(sp_config)
+    lib.sp_blob_floats.restype = sz; lib.sp_blob_floats.argtypes = [cfgp]
+    lib.sp_arena_bytes.restype = sz; lib.sp_arena_bytes.argtypes = [cfgp]
+    lib.sp_workspace_bytes.restype = sz; lib.sp_workspace_bytes.argtypes = [cfgp, i32, i32]
+    lib.sp_load_students.restype = C.c_int
+    lib.sp_load_students.argtypes = [cfgp, vp, sz, vp, sz, vp, C.POINTER(vp)]
+    lib.sp_forward.restype = C.c_int
+    lib.sp_forward.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, sz, vp, vp]
+    lib.sp_forward_partial.restype = C.c_int
+    lib.sp_forward_partial.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, sz, vp]
+    lib.sp_free.restype = None; lib.sp_free.argtypes = [vp]
+    lib.sp_strerror.restype = C.c_char_p; lib.sp_strerror.argtypes = [C.c_int]
+    lib.sp_pack.restype = C.c_int; lib.sp_pack.argtypes = [vp, i32, vp]
+    lib.sp_workspace_layout.restype = C.c_int
+    lib.sp_workspace_layout.argtypes = [cfgp, i32, i32, C.POINTER(sp_ws_layout)]
+    return lib
+
+
+_lib = _load()
+
+
+class SpError(RuntimeError):
+    def __init__(self, code: int):
+        self.code = code
+        super().__init__(f"sp error {code}: {_lib.sp_strerror(code).decode()}")
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        raise SpError(rc)
+
+
+def make_config(K, layers, hidden, heads, ffn, vocab, max_pos, classes, dtype="bf16", ln_eps=1e-12) -> sp_config:
+    return sp_config(K, layers, hidden, heads, ffn, vocab, max_pos, classes,
+                     SP_DTYPE_BF16 if dtype == "bf16" else SP_DTYPE_FP32, ln_eps)
+
+
+def config_from_shape(shape) -> sp_config:
+    """shape: any object with the StudentShape fields (see synth.py)."""
+    return make_config(shape.K, shape.layers, shape.hidden, shape.heads, shape.ffn, shape.vocab, shape.max_pos,
+                       shape.classes, shape.dtype, shape.ln_eps)
+
+
+def sp_blob_floats(cfg: sp_config) -> int:
+    return int(_lib.sp_blob_floats(C.byref(cfg)))
+
+
+def sp_arena_bytes(cfg: sp_config) -> int:
+    return int(_lib.sp_arena_bytes(C.byref(cfg)))
+
+
+def sp_workspace_bytes(cfg: sp_config, max_tokens: int, max_batch: int) -> int:
+    return int(_lib.sp_workspace_bytes(C.byref(cfg), max_tokens, max_batch))
+
+
+def sp_pack(lengths) -> np.ndarray:
+    lengths = np.ascontiguousarray(lengths, dtype=np.int32)
+    cu = np.zeros(lengths.size + 1, dtype=np.int32)
+    _check(_lib.sp_pack(lengths.ctypes.data, lengths.size, cu.ctypes.data))
+    return cu
+
+
+def sp_workspace_layout(cfg: sp_config, total_tokens: int, batch: int) -> sp_ws_layout:
+    out = sp_ws_layout()
+    _check(_lib.sp_workspace_layout(C.byref(cfg), total_tokens, batch, C.byref(out)))
+    return out
+
+
+def _stream_ptr(stream) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+class Students:
+    """A loaded student group: owns the device arena tensor and the library handle."""
+
+    def __init__(self, cfg: sp_config, blob: np.ndarray, device="cuda:0"):
+        if not torch.cuda.is_available():
+            raise RuntimeError("sp_load_students needs a GPU: there is no CPU path in this library")
+        blob = np.ascontiguousarray(blob, dtype=np.float32)
+        self.cfg = cfg
+        self.device = torch.device(device)
+        self.arena = torch.empty(sp_arena_bytes(cfg), dtype=torch.uint8, device=self.device)
+        handle = C.c_void_p()
+        with torch.cuda.device(self.device):
+            _check(_lib.sp_load_students(C.byref(cfg), blob.ctypes.data, blob.size, self.arena.data_ptr(),
+                                         self.arena.numel(), _stream_ptr(None), C.byref(handle)))
+        self.handle = handle
+        self._ws = None
+
+    def workspace(self, total_tokens: int, batch: int) -> torch.Tensor:
+        need = sp_workspace_bytes(self.cfg, total_tokens, batch)
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        return self._ws
+
+    def sp_forward(self, token_ids: torch.Tensor, cu_seqlens: torch.Tensor, max_seqlen: int, k_active: int,
+                   logits_out: torch.Tensor | None = None, workspace: torch.Tensor | None = None, stream=None):
+        """token_ids int32 [T], cu_seqlens int32 [B+1] (device).  Returns logits_out (float32 [B, C])."""
+        assert token_ids.dtype == torch.int32 and cu_seqlens.dtype == torch.int32
+        assert token_ids.is_cuda and cu_seqlens.is_cuda and token_ids.is_contiguous() and cu_seqlens.is_contiguous()
+        batch, total = cu_seqlens.numel() - 1, token_ids.numel()
+        if logits_out is None:
+            logits_out = torch.empty(batch, self.cfg.classes, dtype=torch.float32, device=self.device)
+        ws = workspace if workspace is not None else self.workspace(total, batch)
+        _check(_lib.sp_forward(self.handle, token_ids.data_ptr(), cu_seqlens.data_ptr(), batch, total, max_seqlen,
+                               k_active, ws.data_ptr(), ws.numel(), logits_out.data_ptr(), _stream_ptr(stream)))
+        return logits_out
+
+    def sp_forward_partial(self, token_ids, cu_seqlens, max_seqlen, k_active, stop_after_layers, workspace=None,
+                           stream=None):
+        batch, total = cu_seqlens.numel() - 1, token_ids.numel()
+        ws = workspace if workspace is not None else self.workspace(total, batch)
+        _check(_lib.sp_forward_partial(self.handle, token_ids.data_ptr(), cu_seqlens.data_ptr(), batch, total,
+                                       max_seqlen, k_active, stop_after_layers, ws.data_ptr(), ws.numel(),
+                                       _stream_ptr(stream)))
+        return ws
+
+    def read_activation(self, ws: torch.Tensor, name: str, total_tokens: int, batch: int, k_active: int) -> np.ndarray:
+        """Copy one intermediate tensor out of a workspace as float64 [k][T][width] (tests / profiling)."""
+        lay = sp_workspace_layout(self.cfg, total_tokens, batch)
+        H, F = self.cfg.hidden, self.cfg.ffn
+        if name == "z":
+            n = self.cfg.K * batch * self.cfg.classes
+            z = ws[lay.z:lay.z + 4 * n].view(torch.float32).view(self.cfg.K, batch, self.cfg.classes)
+            return z[:k_active].double().cpu().numpy()
+        width = {"x": H, "qkv": 3 * H, "att": H, "x1": H, "g": F}[name]
+        off = getattr(lay, name)
+        dt = torch.bfloat16 if lay.act_bytes == 2 else torch.float32
+        n = k_active * lay.rows * width
+        t = ws[off:off + n * lay.act_bytes].view(dt).view(k_active, lay.rows, width)
+        return t[:, :total_tokens].double().cpu().numpy()
+
+    def close(self):
+        if self.handle:
+            _lib.sp_free(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def raw_lib() -> C.CDLL:
+    """The ctypes handle itself, for tests of the error paths."""
+    return _lib

@@ -1,0 +1,258 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle.  Needs an MI355X."""
+import numpy as np
+import pytest
+import torch
+
+from oracle.sp_oracle import OracleConfig
+from paper_2408_12526_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+FP32_MAX_ABS = 1e-3        # fp32 path: max |gpu - oracle| over all logits
+BF16_REL = 3e-2            # bf16 path: max |gpu - oracle| / max(max |oracle|, 1e-3)
+
+
+def ocfg(s):
+    return OracleConfig(s.K, s.layers, s.hidden, s.heads, s.ffn, s.vocab, s.max_pos, s.classes, s.ln_eps)
+
+
+def oracle_weights(blob, shape):
+    """What the oracle consumes: in bf16 mode the weights rounded to bf16 once (library conversion), upcast."""
+    if shape.dtype == "bf16":
+        return torch.from_numpy(blob).to(torch.bfloat16).to(torch.float32).numpy()
+    return blob
+
+
+def rel_err(got, ref):
+    return np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-3)
+
+
+def check_logits(got, ref, shape, what=""):
+    assert np.isfinite(got).all(), what
+    if shape.dtype == "fp32":
+        err = np.abs(got - ref).max()
+        assert err <= FP32_MAX_ABS, f"{what}: max abs err {err:.3e}"
+    else:
+        err = rel_err(got, ref)
+        assert err <= BF16_REL, f"{what}: rel err {err:.3e}"
+    return err
+
+
+@pytest.fixture(scope="module")
+def sp():
+    from paper_2408_12526_amd import sp as binding
+    return binding
+
+
+def gpu_inputs(lengths, ids, sp):
+    cu = sp.sp_pack(lengths)
+    return (torch.from_numpy(ids).cuda(), torch.from_numpy(cu).cuda(), cu)
+
+
+# ---- kernel-by-kernel on small shapes ---------------------------------------------------------
+
+STAGE_SHAPES = {
+    "fp32": synth.StudentShape(K=2, layers=2, hidden=128, heads=2, ffn=256, vocab=100, max_pos=200, classes=3,
+                               dtype="fp32"),
+    "bf16": synth.StudentShape(K=3, layers=2, hidden=128, heads=2, ffn=256, vocab=100, max_pos=200, classes=3,
+                               dtype="bf16"),
+}
+STAGE_LENGTHS = (5, 1, 96, 33, 64, 200, 70, 129)   # spans several key tiles, query blocks and a ragged tail
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_every_stage_against_oracle_pieces(sp, oracle64, dtype):
+    """Each kernel in isolation: its output against the oracle's piece applied to the kernel's own input
+    (as the HIP path left it in the workspace), so that one kernel's rounding is not charged to the next."""
+    shape = STAGE_SHAPES[dtype]
+    rng = np.random.default_rng(21)
+    lengths = np.array(STAGE_LENGTHS, dtype=np.int32)
+    ids = synth.make_ids(rng, int(lengths.sum()), shape.vocab)
+    blob = synth.make_weights(rng, shape, std=0.08, ln_random=True, qk_std=0.25)
+    ow = oracle_weights(blob, shape)
+    st = sp.Students(sp.config_from_shape(shape), blob)
+    d_ids, d_cu, cu = gpu_inputs(lengths, ids, sp)
+    T, B, k, H = int(cu[-1]), len(lengths), shape.K, shape.hidden
+    mx = int(lengths.max())
+    # relative to the tensor's largest magnitude: fp32 reorders sums only; bf16 rounds each output once (2^-9)
+    # and, in attention, the probabilities as well
+    tol = 2e-5 if dtype == "fp32" else 1.2e-2
+
+    def per_seq(fn, *tensors):
+        return np.concatenate([fn(*[t[cu[b]:cu[b + 1]] for t in tensors]) for b in range(B)], axis=0)
+
+    def ln_rows(u, g, b):
+        return np.stack([oracle64.layernorm(r, g, b, shape.ln_eps) for r in u])
+
+    def gelu(u):
+        return torch.nn.functional.gelu(torch.from_numpy(u)).numpy()
+
+    ws = st.sp_forward_partial(d_ids, d_cu, mx, k, 0)
+    x_in = st.read_activation(ws, "x", T, B, k)
+    for m in range(k):
+        x0 = np.concatenate([oracle64.taps(ocfg(shape), ow, ids, cu, m, b)["x0"] for b in range(B)], axis=0)
+        assert rel_err(x_in[m], x0) < tol, f"embedding + LayerNorm, student {m}"
+    for layer in range(shape.layers):
+        ws = st.sp_forward_partial(d_ids, d_cu, mx, k, layer + 1)
+        got = {n: st.read_activation(ws, n, T, B, k) for n in ("qkv", "att", "x1", "g", "x")}
+        for m in range(k):
+            v = synth.student_views(ow, shape, m)
+            p = f"l{layer}."
+            Wqkv = np.concatenate([v[p + "Wq"], v[p + "Wk"], v[p + "Wv"]], axis=1)
+            bqkv = np.concatenate([v[p + "bq"], v[p + "bk"], v[p + "bv"]])
+            want = {
+                "qkv": oracle64.linear(x_in[m], Wqkv, bqkv),
+                "att": per_seq(lambda a: oracle64.attention(a[:, :H], a[:, H:2 * H], a[:, 2 * H:], shape.heads),
+                               got["qkv"][m]),
+                "x1": ln_rows(x_in[m] + oracle64.linear(got["att"][m], v[p + "Wo"], v[p + "bo"]), v[p + "ln1_g"],
+                              v[p + "ln1_b"]),
+                "g": gelu(oracle64.linear(got["x1"][m], v[p + "W1"], v[p + "b1"])),
+                "x": ln_rows(got["x1"][m] + oracle64.linear(got["g"][m], v[p + "W2"], v[p + "b2"]), v[p + "ln2_g"],
+                             v[p + "ln2_b"]),
+            }
+            for name in ("qkv", "att", "x1", "g", "x"):
+                e = rel_err(got[name][m], want[name])
+                assert e < tol, f"layer {layer} student {m} stage {name}: rel err {e:.3e}"
+        x_in = got["x"]
+    logits = st.sp_forward(d_ids, d_cu, mx, k).cpu().numpy().astype(np.float64)
+    z = st.read_activation(st.workspace(T, B), "z", T, B, k)
+    for m in range(k):     # head in isolation: pooled first-token state through the oracle's linear pieces
+        v = synth.student_views(ow, shape, m)
+        pooled = np.tanh(oracle64.linear(x_in[m][cu[:-1]], v["Wp"], v["bp"]))
+        assert rel_err(z[m], oracle64.linear(pooled, v["Wc"], v["bc"])) < (2e-5 if dtype == "fp32" else 2e-3)
+    np.testing.assert_allclose(logits, z.sum(0), atol=1e-5)
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_small_shape_end_to_end(sp, oracle64, dtype):
+    """Whole forward on the small shape with non-trivial LayerNorm parameters and sharpened attention."""
+    shape = STAGE_SHAPES[dtype]
+    rng = np.random.default_rng(22)
+    lengths = np.array(STAGE_LENGTHS, dtype=np.int32)
+    ids = synth.make_ids(rng, int(lengths.sum()), shape.vocab)
+    blob = synth.make_weights(rng, shape, std=0.05, ln_random=True, qk_std=0.12)
+    st = sp.Students(sp.config_from_shape(shape), blob)
+    d_ids, d_cu, cu = gpu_inputs(lengths, ids, sp)
+    for k in range(1, shape.K + 1):
+        got = st.sp_forward(d_ids, d_cu, int(lengths.max()), k).cpu().numpy().astype(np.float64)
+        want = oracle64.forward(ocfg(shape), oracle_weights(blob, shape), ids, cu, k)
+        assert np.abs(want).max() > 5e-2
+        check_logits(got, want, shape, f"small shape {dtype} k_active={k}")
+
+
+# ---- the five workloads ----------------------------------------------------------------------------
+
+_cache = {}
+
+
+def loaded(sp, n):
+    """Students + inputs of workload n, kept for the module (weights are large)."""
+    if n not in _cache:
+        _cache.clear()
+        w = synth.WORKLOADS[n]
+        batch, blob = synth.make_workload(w)
+        st = sp.Students(sp.config_from_shape(w.shape), blob)
+        _cache[n] = (w, batch, oracle_weights(blob, w.shape), st)
+    return _cache[n]
+
+
+def run_workload(sp, oracle, n, sample=None):
+    w, batch, ow, st = loaded(sp, n)
+    d_ids, d_cu, cu = gpu_inputs(batch.lengths, batch.ids, sp)
+    B = len(batch.lengths)
+    pick = np.arange(B) if sample is None or sample >= B else np.sort(
+        np.random.default_rng(5).choice(B, size=sample, replace=False))
+    # the oracle runs the sampled sequences as a batch of their own (samples are independent)
+    sub_ids = np.concatenate([batch.ids[cu[b]:cu[b + 1]] for b in pick])
+    sub_cu = np.concatenate([[0], np.cumsum(batch.lengths[pick])]).astype(np.int32)
+    errs = {}
+    prev = None
+    for k in sorted(w.k_actives):
+        got = st.sp_forward(d_ids, d_cu, int(batch.lengths.max()), k).cpu().numpy().astype(np.float64)
+        want = oracle.forward(ocfg(w.shape), ow, sub_ids, sub_cu, k)
+        errs[k] = check_logits(got[pick], want, w.shape, f"{w.name} k_active={k}")
+        assert np.abs(want).max() > 1e-2
+        prev = got
+    return errs
+
+
+def test_config1_tiny_fp32(sp, oracle64, oracle32):
+    errs = run_workload(sp, oracle64, 1)
+    run_workload(sp, oracle32, 1)       # the fp32 build the benchmark spec names, same bound
+    assert max(errs.values()) < 1e-4    # fp32 arithmetic does far better than the 1e-3 gate
+
+
+def test_config2_base_width_b32(sp, oracle64):
+    run_workload(sp, oracle64, 2, sample=6)
+
+
+def test_config3_latency_b1(sp, oracle64):
+    run_workload(sp, oracle64, 3)
+
+
+def test_config4_burst_b256_sampled(sp, oracle64):
+    run_workload(sp, oracle64, 4, sample=6)
+
+
+def test_config5_large_width_b64_sampled(sp, oracle64):
+    run_workload(sp, oracle64, 5, sample=2)
+
+
+# ---- properties that hold at any size ----------------------------------------------------------------
+
+def test_prefix_property_and_determinism_at_full_size(sp):
+    """logits(k) - logits(k-1) is student k-1's term exactly, and two runs agree bit for bit."""
+    w, batch, _, st = loaded(sp, 4)
+    d_ids, d_cu, cu = gpu_inputs(batch.lengths, batch.ids, sp)
+    T, B = int(cu[-1]), len(batch.lengths)
+    mx = int(batch.lengths.max())
+    full = st.sp_forward(d_ids, d_cu, mx, 8).clone()
+    z = torch.from_numpy(st.read_activation(st.workspace(T, B), "z", T, B, 8)).float()
+    again = st.sp_forward(d_ids, d_cu, mx, 8)
+    assert torch.equal(full, again)
+    acc = torch.zeros(B, w.shape.classes)
+    for k in range(1, 9):
+        acc = acc + z[k - 1]
+        if k in (2, 4, 8):
+            got = st.sp_forward(d_ids, d_cu, mx, k).cpu()
+            assert torch.equal(got, acc), f"k_active={k} is not the fixed-order prefix sum"
+
+
+def test_sample_is_independent_of_batch_mates(sp):
+    """A sequence's logits do not depend on where it sits in the packed batch (bitwise in the fp32 path)."""
+    w = synth.WORKLOADS[1]
+    batch, blob = synth.make_workload(w)
+    st = sp.Students(sp.config_from_shape(w.shape), blob)
+    d_ids, d_cu, cu = gpu_inputs(batch.lengths, batch.ids, sp)
+    full = st.sp_forward(d_ids, d_cu, int(batch.lengths.max()), 2).cpu().numpy()
+    order = [2, 0, 3, 1]
+    p_ids = np.concatenate([batch.ids[cu[b]:cu[b + 1]] for b in order])
+    dp_ids, dp_cu, _ = gpu_inputs(batch.lengths[order], p_ids, sp)
+    perm = st.sp_forward(dp_ids, dp_cu, int(batch.lengths.max()), 2).cpu().numpy()
+    assert np.array_equal(perm, full[order])
+
+
+# ---- boundary behaviour --------------------------------------------------------------------------------
+
+def test_error_codes(sp):
+    w = synth.WORKLOADS[1]
+    batch, blob = synth.make_workload(w)
+    cfg = sp.config_from_shape(w.shape)
+    st = sp.Students(cfg, blob)
+    d_ids, d_cu, cu = gpu_inputs(batch.lengths, batch.ids, sp)
+    mx = int(batch.lengths.max())
+    for k in (0, 3):
+        with pytest.raises(sp.SpError) as e:
+            st.sp_forward(d_ids, d_cu, mx, k)
+        assert e.value.code == -3
+    with pytest.raises(sp.SpError) as e:
+        st.sp_forward(d_ids, d_cu, w.shape.max_pos + 1, 2)
+    assert e.value.code == -2
+    small = torch.empty(1024, dtype=torch.uint8, device="cuda")
+    with pytest.raises(sp.SpError) as e:
+        st.sp_forward(d_ids, d_cu, mx, 2, workspace=small)
+    assert e.value.code == -4
+    bad = sp.make_config(2, 2, 96, 2, 256, 100, 64, 2, "bf16")     # head width 48: unsupported
+    with pytest.raises(sp.SpError) as e:
+        sp.Students(bad, np.zeros(sp.sp_blob_floats(bad), np.float32))
+    assert e.value.code == -2
