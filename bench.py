@@ -1,0 +1,198 @@
+#!/usr/bin/env python3
+"""Benchmark of the K-student forward on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+A step is one sp_forward over one synthetic batch of the burst workload (256
+sequences, lognormal lengths, K = 8 students, k_active = 8) with inputs already
+on the device.  The JSON line also carries the batch-1 latency workload (p50 and
+p95 per k_active), the burst workload at k_active 4 and 2, a per-phase breakdown
+with roofline fractions (HIP events on the launch stream), and the CPU oracle
+timed on a bounded sample of the same batch.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# published MI355X peaks used for the roofline fractions
+PEAK_BF16_TFLOPS = 2500.0
+PEAK_HBM_GBS = 8000.0
+
+
+def percentile(xs, q):
+    return float(np.percentile(np.asarray(xs), q))
+
+
+def gemm_flops(shape, tokens, k):
+    H, F = shape.hidden, shape.ffn
+    per_layer = {"qkv": 2 * tokens * H * 3 * H, "oproj": 2 * tokens * H * H, "ffn_up": 2 * tokens * H * F,
+                 "ffn_down": 2 * tokens * F * H}
+    return {n: v * k * shape.layers for n, v in per_layer.items()}
+
+
+def attention_flops(shape, lengths, k):
+    return 4 * shape.hidden * int((lengths.astype(np.int64) ** 2).sum()) * k * shape.layers
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--latency-calls", type=int, default=300)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only", choices=["burst", "latency"], default=None,
+                    help="run one workload only (for profiling a single launch configuration)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2408_12526_amd import sp, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs an MI355X; there is no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    out = {}
+
+    # ------------------------------------------------------------------ burst workload (batch 256)
+    w4 = synth.WORKLOADS[4]
+    batch4, blob4 = synth.make_workload(w4)
+    cu4 = sp.sp_pack(batch4.lengths)
+    T4, B4, mx4 = int(cu4[-1]), len(batch4.lengths), int(batch4.lengths.max())
+    st4 = sp.Students(sp.config_from_shape(w4.shape), blob4)
+    d_ids4, d_cu4 = torch.from_numpy(batch4.ids).to(dev), torch.from_numpy(cu4).to(dev)
+    logits4 = torch.empty(B4, w4.shape.classes, dtype=torch.float32, device=dev)
+    ws4 = st4.workspace(T4, B4)
+
+    def timed_steps(st, ids, cu, mx, k, logits, ws, steps, warmup):
+        for _ in range(warmup):
+            st.sp_forward(ids, cu, mx, k, logits, ws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            st.sp_forward(ids, cu, mx, k, logits, ws)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    burst = {}
+    phases = {}
+    if args.only in (None, "burst"):
+        for k in w4.k_actives:
+            sec = timed_steps(st4, d_ids4, d_cu4, mx4, k, logits4, ws4, args.steps, args.warmup)
+            burst[k] = {"ms_per_step": sec * 1e3, "sequences_per_s": B4 / sec, "tokens_per_s": T4 / sec}
+        # per-phase device time at k_active = 8 (events after every launch, on the launch stream)
+        acc = {n: 0.0 for n in sp.PHASES}
+        for _ in range(args.steps):
+            ms = st4.sp_forward_profiled(d_ids4, d_cu4, mx4, 8, logits4, ws4)
+            for n, v in ms.items():
+                acc[n] += v / args.steps
+        gf = gemm_flops(w4.shape, T4, 8)
+        H, F, Ly = w4.shape.hidden, w4.shape.ffn, w4.shape.layers
+        for n in ("qkv", "oproj", "ffn_up", "ffn_down"):
+            phases[n] = {"ms": acc[n], "bound": "mfma", "tflops": gf[n] / acc[n] / 1e9,
+                         "frac": gf[n] / acc[n] / 1e9 / PEAK_BF16_TFLOPS}
+        af = attention_flops(w4.shape, batch4.lengths, 8)
+        phases["attention"] = {"ms": acc["attention"], "bound": "mfma", "tflops": af / acc["attention"] / 1e9,
+                               "frac": af / acc["attention"] / 1e9 / PEAK_BF16_TFLOPS}
+        emb_bytes = 8 * T4 * (6 * H + 4)                      # two table rows read, one row written, bf16, + id
+        ln_bytes = 8 * T4 * 2 * Ly * (4 * H)                  # every LayerNorm reads a row and writes a row, bf16
+        head_bytes = 8 * (B4 * H * 2 + (H * H + H * w4.shape.classes) * 2)
+        for n, b in (("embed", emb_bytes), ("layernorm", ln_bytes), ("head", head_bytes)):
+            phases[n] = {"ms": acc[n], "bound": "hbm", "gbs": b / acc[n] / 1e6, "frac": b / acc[n] / 1e6 / PEAK_HBM_GBS}
+        gemm_ms = sum(acc[n] for n in ("qkv", "oproj", "ffn_up", "ffn_down"))
+        phases["gemm_phase_total"] = {"ms": gemm_ms, "bound": "mfma", "tflops": sum(gf.values()) / gemm_ms / 1e9,
+                                      "frac": sum(gf.values()) / gemm_ms / 1e9 / PEAK_BF16_TFLOPS}
+        phases["sum_ms"] = sum(acc.values())
+
+    # ------------------------------------------------------------------ latency workload (batch 1)
+    latency = {}
+    if args.only in (None, "latency"):
+        del st4
+        torch.cuda.empty_cache()
+        w3 = synth.WORKLOADS[3]
+        batch3, blob3 = synth.make_workload(w3)
+        cu3 = sp.sp_pack(batch3.lengths)
+        T3, mx3 = int(cu3[-1]), int(batch3.lengths.max())
+        st3 = sp.Students(sp.config_from_shape(w3.shape), blob3)
+        d_ids3, d_cu3 = torch.from_numpy(batch3.ids).to(dev), torch.from_numpy(cu3).to(dev)
+        logits3 = torch.empty(1, w3.shape.classes, dtype=torch.float32, device=dev)
+        ws3 = st3.workspace(T3, 1)
+        for k in sorted(w3.k_actives):
+            for _ in range(50):
+                st3.sp_forward(d_ids3, d_cu3, mx3, k, logits3, ws3)
+            torch.cuda.synchronize()
+            wall = []
+            for _ in range(args.latency_calls):
+                t0 = time.perf_counter()
+                st3.sp_forward(d_ids3, d_cu3, mx3, k, logits3, ws3)
+                torch.cuda.synchronize()
+                wall.append((time.perf_counter() - t0) * 1e6)
+            # device-side time of back-to-back calls (no host gap between launches)
+            back = timed_steps(st3, d_ids3, d_cu3, mx3, k, logits3, ws3, args.latency_calls, 10) * 1e6
+            weight_bytes = k * w3.shape.layers * 12 * w3.shape.hidden ** 2 * 2
+            latency[k] = {"p50_us": percentile(wall, 50), "p95_us": percentile(wall, 95),
+                          "back_to_back_us": back, "weight_stream_gbs": weight_bytes / back / 1e3}
+
+    # ------------------------------------------------------------------ CPU oracle on a bounded sample
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle.sp_oracle import Oracle, OracleConfig
+        orc = Oracle("f32")
+        s = w4.shape
+        oc = OracleConfig(s.K, s.layers, s.hidden, s.heads, s.ffn, s.vocab, s.max_pos, s.classes, s.ln_eps)
+        cores = len(os.sched_getaffinity(0))
+        cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
+        def run(n):
+            sub_cu = np.concatenate([[0], np.cumsum(batch4.lengths[:n])]).astype(np.int32)
+            t0 = time.perf_counter()
+            orc.forward(oc, blob4, batch4.ids[:sub_cu[-1]], sub_cu, 8)
+            return time.perf_counter() - t0, int(sub_cu[-1])
+
+        probe, _ = run(8)                                      # calibrate, then time about 15 s of oracle work
+        n = int(min(B4, max(8, 8 * 15.0 / probe)))
+        dt, ntok = run(n)
+        cpu = {"value": n / dt, "unit": "sequences/s", "cores": cores, "kind": "oracle",
+               "sample": f"first {n} sequences ({ntok} tokens) of the burst batch, all 8 students, fp32 build of the "
+                         f"oracle, {dt:.1f} s"}
+
+    main_k = 8
+    rec = {
+        "metric": "sequences/sec at batch 256, K-student forward (with p50 latency in us at batch 1 alongside)",
+        "value": burst[main_k]["sequences_per_s"] if burst else None,
+        "unit": "sequences/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": burst[main_k]["ms_per_step"] if burst else None,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "c4_burst_b256: K=8 students x 2 layers, hidden 768, 12 heads, FFN 3072, vocab 30522, "
+                               "batch 256, lognormal lengths (median 48, sigma 0.6, clipped to [8,256]), k_active=8",
+                   "total_tokens": T4, "batch": B4, "k_active": main_k, "variant": "all-token last layer"},
+        "burst_by_k_active": {str(k): v for k, v in burst.items()},
+        "latency_batch1_by_k_active": {str(k): v for k, v in latency.items()},
+        "latency_workload": "c3_latency_b1: K=8 students, one sequence of 64 tokens, 3 classes; wall time from call "
+                            "to stream sync, inputs resident",
+        "phases_k8": phases,
+    }
+    if phases:
+        d = phases["ffn_up"]
+        rec["roofline"] = {"kernel": "gemm_bf16_kernel (FFN up-projection + GELU)", "bound": "mfma",
+                           "achieved": d["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": d["frac"],
+                           "traffic": None}
+    rec["cpu_baseline"] = cpu
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()

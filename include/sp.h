@@ -153,6 +153,29 @@ int sp_forward_partial(const sp_model* model, const int32_t* token_ids, const in
                        int32_t batch, int32_t total_tokens, int32_t max_seqlen, int32_t k_active,
                        int32_t stop_after_layers, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Phases of one forward, in the order of the encoder layer (Section 2.1: the serial depth
+ * of attention layers is what the students shorten; each layer is these steps). */
+enum {
+    SP_PHASE_EMBED = 0,   /* embedding gather + LayerNorm */
+    SP_PHASE_QKV,         /* query/key/value projection */
+    SP_PHASE_ATTENTION,   /* softmax(q k^T / sqrt(d)) v inside each sequence */
+    SP_PHASE_OPROJ,       /* attention output projection + residual */
+    SP_PHASE_LAYERNORM,   /* both LayerNorms of every layer */
+    SP_PHASE_FFN_UP,      /* feed-forward up-projection + GELU */
+    SP_PHASE_FFN_DOWN,    /* feed-forward down-projection + residual */
+    SP_PHASE_HEAD,        /* pooling, per-student head, cross-student sum */
+    SP_PHASE_COUNT
+};
+
+/* sp_forward with HIP events recorded on hip_stream after every kernel launch; waits for
+ * the stream and adds each phase's device time, in milliseconds and summed over layers,
+ * into phase_ms_host[SP_PHASE_COUNT] (host).  A measurement aid: it creates and destroys
+ * events and synchronises, so it is not for latency-critical callers. */
+int sp_forward_profiled(const sp_model* model, const int32_t* token_ids, const int32_t* cu_seqlens,
+                        int32_t batch, int32_t total_tokens, int32_t max_seqlen, int32_t k_active,
+                        void* workspace, size_t workspace_bytes, float* logits_out, void* hip_stream,
+                        float* phase_ms_host);
+
 #ifdef __cplusplus
 }
 #endif

@@ -174,8 +174,26 @@ static void fill_student(const sp_config& c, const ArenaLayout& L, const float* 
     memcpy(dst + L.bc, p, C * 4); p += C;
 }
 
+// Optional per-phase timing: an event is recorded after every launch and tagged with its phase.
+struct PhaseTimer {
+    hipEvent_t ev[64];
+    int phase[64];
+    int n = 0;
+    bool ok = true;
+    void mark(int ph, hipStream_t s)
+    {
+        if (n >= 64) { ok = false; return; }
+        if (hipEventCreate(&ev[n]) != hipSuccess) { ok = false; return; }
+        phase[n] = ph;
+        if (hipEventRecord(ev[n], s) != hipSuccess) ok = false;
+        ++n;
+    }
+    void release() { for (int i = 0; i < n; ++i) (void)hipEventDestroy(ev[i]); n = 0; }
+};
+
 static int run_forward(const sp_model* M, const int32_t* ids, const int32_t* cu, int B, int T, int max_seqlen, int k,
-                       int stop_layers, bool with_head, void* ws, size_t ws_bytes, float* logits, hipStream_t s)
+                       int stop_layers, bool with_head, void* ws, size_t ws_bytes, float* logits, hipStream_t s,
+                       PhaseTimer* pt = nullptr)
 {
     if (!M || !ids || !cu || !ws || (with_head && !logits)) return SP_EINVAL;
     if (((uintptr_t)ws & 255) || ((uintptr_t)ids & 3) || ((uintptr_t)cu & 3) || ((uintptr_t)logits & 3)) return SP_EINVAL;
@@ -198,22 +216,36 @@ static int run_forward(const sp_model* M, const int32_t* ids, const int32_t* cu,
     const ArenaLayout& L = M->L;
 
 #define SP_TRY(expr) do { if ((expr) != hipSuccess) return SP_EHIP; } while (0)
+#define SP_MARK(ph) do { if (pt) pt->mark(ph, s); } while (0)
+    SP_MARK(-1);
     SP_TRY(launch_embed_ln(M, ids, cu, B, T, rows, mrows, k, x, s));
+    SP_MARK(SP_PHASE_EMBED);
     for (int l = 0; l < stop_layers; ++l) {
         const size_t lo = L.layer0 + (size_t)l * L.layer_stride;
         SP_TRY(launch_gemm(M, x, H, lo + L.wqkv, lo + L.bqkv, qkv, 3 * H, nullptr, 0, mrows, 3 * H, H, k, EPI_BIAS, sH,
                            s3H, 0, s));
+        SP_MARK(SP_PHASE_QKV);
         SP_TRY(launch_attention(M, qkv, att, cu, B, T, max_seqlen, rows, k, s));
+        SP_MARK(SP_PHASE_ATTENTION);
         SP_TRY(launch_gemm(M, att, H, lo + L.wo, lo + L.bo, u, H, x, H, mrows, H, H, k, EPI_BIAS_RESIDUAL, sH, sH, sH,
                            s));
+        SP_MARK(SP_PHASE_OPROJ);
         SP_TRY(launch_layernorm(M, u, x1, rows, mrows, k, lo + L.ln1g, lo + L.ln1b, s));
+        SP_MARK(SP_PHASE_LAYERNORM);
         SP_TRY(launch_gemm(M, x1, H, lo + L.w1, lo + L.b1, g, F, nullptr, 0, mrows, F, H, k, EPI_BIAS_GELU, sH, sF, 0,
                            s));
+        SP_MARK(SP_PHASE_FFN_UP);
         SP_TRY(launch_gemm(M, g, F, lo + L.w2, lo + L.b2, u, H, x1, H, mrows, H, F, k, EPI_BIAS_RESIDUAL, sF, sH, sH,
                            s));
+        SP_MARK(SP_PHASE_FFN_DOWN);
         SP_TRY(launch_layernorm(M, u, x, rows, mrows, k, lo + L.ln2g, lo + L.ln2b, s));
+        SP_MARK(SP_PHASE_LAYERNORM);
     }
-    if (with_head) SP_TRY(launch_head(M, x, cu, B, T, rows, k, z, (float*)(w + W.zpart), logits, s));
+    if (with_head) {
+        SP_TRY(launch_head(M, x, cu, B, T, rows, k, z, (float*)(w + W.zpart), logits, s));
+        SP_MARK(SP_PHASE_HEAD);
+    }
+#undef SP_MARK
 #undef SP_TRY
     return SP_OK;
 }
@@ -307,6 +339,27 @@ int sp_forward_partial(const sp_model* model, const int32_t* token_ids, const in
     if (!model) return SP_EINVAL;
     return run_forward(model, token_ids, cu_seqlens, batch, total_tokens, max_seqlen, k_active, stop_after_layers,
                        false, workspace, workspace_bytes, nullptr, (hipStream_t)hip_stream);
+}
+
+int sp_forward_profiled(const sp_model* model, const int32_t* token_ids, const int32_t* cu_seqlens, int32_t batch,
+                        int32_t total_tokens, int32_t max_seqlen, int32_t k_active, void* workspace,
+                        size_t workspace_bytes, float* logits_out, void* hip_stream, float* phase_ms_host)
+{
+    if (!model || !phase_ms_host) return SP_EINVAL;
+    PhaseTimer pt;
+    hipStream_t s = (hipStream_t)hip_stream;
+    int rc = run_forward(model, token_ids, cu_seqlens, batch, total_tokens, max_seqlen, k_active, model->cfg.layers,
+                         true, workspace, workspace_bytes, logits_out, s, &pt);
+    if (hipStreamSynchronize(s) != hipSuccess || !pt.ok) rc = rc == SP_OK ? SP_EHIP : rc;
+    for (int i = 0; i < SP_PHASE_COUNT; ++i) phase_ms_host[i] = 0.f;
+    if (rc == SP_OK)
+        for (int i = 1; i < pt.n; ++i) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, pt.ev[i - 1], pt.ev[i]) != hipSuccess) { rc = SP_EHIP; break; }
+            phase_ms_host[pt.phase[i]] += ms;
+        }
+    pt.release();
+    return rc;
 }
 
 void sp_free(sp_model* model) { delete model; }

@@ -17,6 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsp_mi355x.so")
 
 SP_DTYPE_FP32, SP_DTYPE_BF16 = 0, 1
+PHASES = ("embed", "qkv", "attention", "oproj", "layernorm", "ffn_up", "ffn_down", "head")
 
 
 class sp_config(C.Structure):
@@ -45,6 +46,8 @@ def _load() -> C.CDLL:
     lib.sp_forward.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, sz, vp, vp]
     lib.sp_forward_partial.restype = C.c_int
     lib.sp_forward_partial.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, sz, vp]
+    lib.sp_forward_profiled.restype = C.c_int
+    lib.sp_forward_profiled.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, sz, vp, vp, vp]
     lib.sp_free.restype = None; lib.sp_free.argtypes = [vp]
     lib.sp_strerror.restype = C.c_char_p; lib.sp_strerror.argtypes = [C.c_int]
     lib.sp_pack.restype = C.c_int; lib.sp_pack.argtypes = [vp, i32, vp]
@@ -143,6 +146,19 @@ class Students:
         _check(_lib.sp_forward(self.handle, token_ids.data_ptr(), cu_seqlens.data_ptr(), batch, total, max_seqlen,
                                k_active, ws.data_ptr(), ws.numel(), logits_out.data_ptr(), _stream_ptr(stream)))
         return logits_out
+
+    def sp_forward_profiled(self, token_ids, cu_seqlens, max_seqlen, k_active, logits_out=None, workspace=None,
+                            stream=None) -> dict:
+        """One forward with per-phase device times (ms), as {phase name: ms}."""
+        batch, total = cu_seqlens.numel() - 1, token_ids.numel()
+        if logits_out is None:
+            logits_out = torch.empty(batch, self.cfg.classes, dtype=torch.float32, device=self.device)
+        ws = workspace if workspace is not None else self.workspace(total, batch)
+        ms = (C.c_float * len(PHASES))()
+        _check(_lib.sp_forward_profiled(self.handle, token_ids.data_ptr(), cu_seqlens.data_ptr(), batch, total,
+                                        max_seqlen, k_active, ws.data_ptr(), ws.numel(), logits_out.data_ptr(),
+                                        _stream_ptr(stream), C.cast(ms, C.c_void_p)))
+        return {n: float(ms[i]) for i, n in enumerate(PHASES)}
 
     def sp_forward_partial(self, token_ids, cu_seqlens, max_seqlen, k_active, stop_after_layers, workspace=None,
                            stream=None):
