@@ -25,7 +25,7 @@ constexpr int kVStride = 68;    // bf16 elements per row of the transposed value
 // -------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void attention_bf16_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ att,
                                                              const int32_t* __restrict__ cu, int B, int Tn, int rows,
-                                                             int H, int heads, int max_seqlen, int nqc)
+                                                             int H, int heads, int max_seqlen, int nqc, int min_len)
 {
     __shared__ uint4 sK[8 * kKStride];             // [d-group of 8][key]
     __shared__ __attribute__((aligned(16))) bf16 sVt[kD * kVStride];   // [d][key]
@@ -42,7 +42,7 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(const bf16* __restr
     L = L > max_seqlen ? max_seqlen : L;
     L = L > Tn - t0 ? Tn - t0 : L;
     const int q0 = qc * kQPerWg;
-    if (q0 >= L) return;                            // whole workgroup leaves together
+    if (q0 >= L || L <= min_len) return;            // whole workgroup leaves together
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int j = lane & 31, g = lane >> 5;
@@ -166,6 +166,153 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(const bf16* __restr
     }
 }
 
+
+// -------------------------------------------------------------------------------------
+// bf16 kernel for short sequences (the common case of the serving workloads: tens of tokens).  One wave = one
+// (student, sequence, head); the four waves of a workgroup take four heads of the same sequence and never
+// synchronise with each other: each wave stages its 32-key tiles in a private slice of LDS.  Same arithmetic as
+// the kernel above (S^T = K Q^T, online softmax per lane column, O^T += V^T P^T), 32 queries per pass; the next
+// key tile is fetched into registers while the current one is multiplied.
+// -------------------------------------------------------------------------------------
+constexpr int kSKey = 32;                 // keys per tile
+constexpr int kSKStride = kSKey + 1;      // 16-byte units per d-group of the key tile
+constexpr int kSVStride = 36;             // bf16 elements per row of the transposed value tile (72 B)
+
+__global__ __launch_bounds__(256, 3) void attention_bf16_short_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ att,
+                                                                   const int32_t* __restrict__ cu, int B, int Tn,
+                                                                   int rows, int H, int heads, int max_seqlen,
+                                                                   int ngroups, int max_len)
+{
+    __shared__ uint4 sK_all[4][8 * kSKStride];
+    __shared__ __attribute__((aligned(16))) bf16 sVt_all[4][kD * kSVStride];
+
+    const int m = blockIdx.y;
+    const int b = blockIdx.x / ngroups, hg = blockIdx.x % ngroups;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int h = hg * 4 + wave;
+    int t0 = cu[b], t1 = cu[b + 1];
+    t0 = t0 < 0 ? 0 : (t0 > Tn - 1 ? Tn - 1 : t0);
+    int L = t1 - t0;
+    L = L < 1 ? 1 : L;
+    L = L > max_seqlen ? max_seqlen : L;
+    L = L > Tn - t0 ? Tn - t0 : L;
+    if (L > max_len || h >= heads) return;         // long sequences belong to the cooperative kernel
+    uint4* sK = sK_all[wave];
+    bf16* sVt = sVt_all[wave];
+
+    const int j = lane & 31, g = lane >> 5;
+    const size_t ld = (size_t)3 * H;
+    const bf16* base = qkv + ((size_t)m * rows + t0) * ld + h * kD;
+    const float sl2 = 0.125f * 1.44269504088896341f;
+    const int lkey = lane >> 3, lc = lane & 7;      // tile loader: 8 keys x 8 sixteen-byte chunks per instruction
+
+    for (int q0 = 0; q0 < L; q0 += 32) {
+        const int q = q0 + j;
+        bf16x8 qf[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            uint4 t = {0, 0, 0, 0};
+            if (q < L) t = *(const uint4*)(base + (size_t)q * ld + 16 * s + 8 * g);
+            qf[s] = __builtin_bit_cast(bf16x8, t);
+        }
+        f32x16 o[2];
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) o[db][e] = 0.f;
+        float mrun = -INFINITY, lrun = 0.f;
+
+        uint4 kreg[4], vreg[4];
+        auto fetch = [&](int kt0) {
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const int key = kt0 + p * 8 + lkey;
+                kreg[p] = uint4{0, 0, 0, 0};
+                vreg[p] = uint4{0, 0, 0, 0};
+                if (key < L) {
+                    const bf16* r = base + (size_t)key * ld + lc * 8;
+                    kreg[p] = *(const uint4*)(r + H);
+                    vreg[p] = *(const uint4*)(r + 2 * H);
+                }
+            }
+        };
+        fetch(0);
+        for (int kt0 = 0; kt0 < L; kt0 += kSKey) {
+            // registers -> this wave's LDS slice (keys beyond L were fetched as zeros)
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const int key = p * 8 + lkey;
+                sK[lc * kSKStride + key] = kreg[p];
+                const bf16x8 v8 = __builtin_bit_cast(bf16x8, vreg[p]);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) sVt[(lc * 8 + e) * kSVStride + key] = v8[e];
+            }
+            if (kt0 + kSKey < L) fetch(kt0 + kSKey);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+
+            f32x16 sc;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) sc[e] = 0.f;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const uint4 t = sK[(2 * s + g) * kSKStride + j];
+                sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, t), qf[s], sc, 0, 0, 0);
+            }
+            float mx = mrun;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int key = kt0 + 8 * (v >> 2) + 4 * g + (v & 3);
+                const float sv = key < L ? sc[v] * sl2 : -INFINITY;
+                sc[v] = sv;
+                mx = fmaxf(mx, sv);
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float alpha = exp2f(mrun - mx);
+            mrun = mx;
+            float psum = 0.f;
+            bf16x8 pf[2];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const float p = exp2f(sc[v] - mx);
+                psum += p;
+                pf[v >> 3][v & 7] = (bf16)p;
+            }
+            lrun = lrun * alpha + psum;
+#pragma unroll
+            for (int db = 0; db < 2; ++db)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                const int kbase = 16 * s2 + 4 * g;
+#pragma unroll
+                for (int db = 0; db < 2; ++db) {
+                    const bf16* vr = sVt + (db * 32 + j) * kSVStride + kbase;
+                    const bf16x4 lo = *(const bf16x4*)vr, hi = *(const bf16x4*)(vr + 8);
+                    const bf16x8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[s2], o[db], 0, 0, 0);
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();       // the slice is rewritten at the top of the next iteration
+        }
+        const float inv = 1.0f / (lrun + __shfl_xor(lrun, 32));
+        if (q < L) {
+            bf16* dst = att + ((size_t)m * rows + t0 + q) * H + h * kD;
+#pragma unroll
+            for (int db = 0; db < 2; ++db)
+#pragma unroll
+                for (int v4 = 0; v4 < 4; ++v4) {
+                    bf16x4 w;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) w[e] = (bf16)(o[db][4 * v4 + e] * inv);
+                    *(bf16x4*)(dst + db * 32 + 8 * v4 + 4 * g) = w;
+                }
+        }
+    }
+}
+
 // -------------------------------------------------------------------------------------
 // fp32 kernel: one thread per query, keys streamed from global memory (all threads of a
 // workgroup read the same key row), online softmax in registers, exact division.
@@ -220,10 +367,21 @@ hipError_t launch_attention(const sp_model* M, const void* qkv, void* att, const
     const sp_config& c = M->cfg;
     if (c.hidden / c.heads != kD) return hipErrorInvalidValue;
     if (c.dtype == SP_DTYPE_BF16) {
-        const int nqc = (max_seqlen + kQPerWg - 1) / kQPerWg;
-        dim3 grid((unsigned)(B * c.heads * nqc), k);
-        hipLaunchKernelGGL(attention_bf16_kernel, grid, dim3(256), 0, s, (const bf16*)qkv, (bf16*)att, cu, B, T, rows,
-                           c.hidden, c.heads, max_seqlen, nqc);
+        // sequences of up to kShortLen tokens: one wave per (sequence, head); longer ones: one workgroup per
+        // (sequence, head, 128 queries) sharing the key/value tiles.  Each kernel skips the other's sequences.
+        constexpr int kShortLen = 128;
+        const int ngroups = (c.heads + 3) / 4;
+        hipLaunchKernelGGL(attention_bf16_short_kernel, dim3((unsigned)(B * ngroups), k), dim3(256), 0, s,
+                           (const bf16*)qkv, (bf16*)att, cu, B, T, rows, c.hidden, c.heads, max_seqlen, ngroups,
+                           kShortLen);
+        if (max_seqlen > kShortLen) {
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            const int nqc = (max_seqlen + kQPerWg - 1) / kQPerWg;
+            dim3 grid((unsigned)(B * c.heads * nqc), k);
+            hipLaunchKernelGGL(attention_bf16_kernel, grid, dim3(256), 0, s, (const bf16*)qkv, (bf16*)att, cu, B, T,
+                               rows, c.hidden, c.heads, max_seqlen, nqc, kShortLen);
+        }
     } else {
         const int nqc = (max_seqlen + 63) / 64;
         dim3 grid((unsigned)(B * c.heads * nqc), k);

@@ -171,11 +171,16 @@ __global__ __launch_bounds__(256) void head_pool_kernel(const char* arena, size_
     float acc[kSeqPerWg];
 #pragma unroll
     for (int s = 0; s < kSeqPerWg; ++s) acc[s] = 0.f;
-    const int per = H / 4, i0 = part * per;   // this wave's share of the reduction index
-    for (int i = i0; i < i0 + per; ++i) {
-        const float w = (float)Wp[(size_t)i * H + n];
+    const int per = H / 4, i0 = part * per;   // this wave's share of the reduction index (a multiple of 16)
+    for (int i = i0; i < i0 + per; i += 4) {
+        float w[4];
 #pragma unroll
-        for (int s = 0; s < kSeqPerWg; ++s) acc[s] += xs[s * H + i] * w;   // rows beyond nseq hold stale data: unused
+        for (int e = 0; e < 4; ++e) w[e] = (float)Wp[(size_t)(i + e) * H + n];
+#pragma unroll
+        for (int s = 0; s < kSeqPerWg; ++s) {    // rows beyond nseq hold stale data: their sums are never used
+            const f32x4 xv = *(const f32x4*)&xs[s * H + i];
+            acc[s] += xv[0] * w[0] + xv[1] * w[1] + xv[2] * w[2] + xv[3] * w[3];
+        }
     }
 #pragma unroll
     for (int s = 0; s < kSeqPerWg; ++s) red[(part * kSeqPerWg + s) * 64 + lane] = acc[s];

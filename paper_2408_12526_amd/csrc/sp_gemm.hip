@@ -2,6 +2,8 @@
 // student m.  The bf16 kernel runs on the matrix cores (v_mfma_f32_32x32x16_bf16, fp32
 // accumulate) with both operands staged through LDS; the fp32 kernel is a plain FMA tile
 // kernel used by the fp32 path.
+#include <type_traits>
+
 #include "sp_internal.h"
 
 namespace sp {
@@ -10,63 +12,104 @@ namespace {
 
 __device__ inline float gelu_erf(float u) { return 0.5f * u * (1.0f + erff(u * 0.70710678118654752f)); }
 
-// -------------------------------------------------------------------------------------
-// bf16 MFMA kernel.
-//
-// Operand roles are swapped with respect to the textbook picture: the weight tile is the
-// MFMA "A" operand (rows = output features) and the activation tile the "B" operand
-// (columns = tokens).  In the 32x32 accumulator a lane then owns one token and runs of four
-// consecutive features, so the epilogue writes 8-byte pieces of row-major [token][feature]
-// output without a transpose.
-//
-// LDS holds a tile as [k-group of 8][row] 16-byte units (row = token or feature), so the 32
-// lanes of a fragment read 32 consecutive units; the +1 unit of padding per k-group spreads
-// the global->LDS stores (8 k-groups of one row at a time) over distinct banks.
-// -------------------------------------------------------------------------------------
-template <int BM, int BN, int BK, int EPI>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16* __restrict__ A, int lda, size_t a_ss,
-                                                        const char* __restrict__ arena, size_t student_stride,
-                                                        size_t w_off, size_t b_off, bf16* __restrict__ out, int ldo,
-                                                        size_t o_ss, const bf16* __restrict__ res, int ldr,
-                                                        size_t r_ss, int Kd, int mtiles, int ntiles, int total)
+// GELU (erf form) for outputs that are rounded to bf16 afterwards.  erf by the rational-exponential
+// formula 7.1.26 of Abramowitz & Stegun (absolute error < 1.5e-7, far below half a bf16 ulp):
+//   erf(z) = 1 - (a1 t + ... + a5 t^5) exp(-z^2),  t = 1 / (1 + p z),  z >= 0
+// and gelu(x) = (x + |x| erf(|x| / sqrt 2)) / 2.  Hardware reciprocal and exp2 instead of libm's erff,
+// which costs several times more VALU cycles in an epilogue that the matrix cores wait for.
+__device__ inline float gelu_erf_fast(float x)
 {
-    constexpr int KG = BK / 8;            // k-groups per tile
-    constexpr int SA = BM + 1, SW = BN + 1;
-    constexpr int TM = BM / 64, TN = BN / 64;  // 32x32 blocks per wave along tokens / features (2x2 waves)
-    constexpr int PA = BM / 32, PW = BN / 32;  // 16-byte loads per thread per tile (256 threads, 8 per row)
-    static_assert(BK == 64, "loader assumes 8 sixteen-byte chunks per row");
+    const float ax = __builtin_fabsf(x);
+    const float z = ax * 0.70710678118654752f;
+    const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(0.3275911f, z, 1.0f));
+    float p = __builtin_fmaf(1.061405429f, t, -1.453152027f);
+    p = __builtin_fmaf(p, t, 1.421413741f);
+    p = __builtin_fmaf(p, t, -0.284496736f);
+    p = __builtin_fmaf(p, t, 0.254829592f);
+    p *= t;
+    const float ex = __builtin_amdgcn_exp2f(z * z * -1.44269504088896341f);
+    const float erfz = __builtin_fmaf(-p, ex, 1.0f);
+    return 0.5f * __builtin_fmaf(ax, erfz, x);
+}
 
+// -------------------------------------------------------------------------------------
+// bf16 MFMA kernel (v_mfma_f32_32x32x16_bf16), 256 threads = 2 x 2 waves, tile BM tokens x BN features.
+//
+// Operand roles are swapped with respect to the textbook picture: the weight tile is the MFMA "A" operand
+// (rows = output features) and the activation tile the "B" operand (columns = tokens), so a lane of the
+// 32x32 accumulator owns one token and runs of four consecutive features.
+//
+// Data movement
+//   * global -> LDS with direct-to-LDS loads (no register staging).  A wave-load moves 8 rows x 128 bytes
+//     (64 reduction elements) and lands as 1 KB of contiguous LDS.
+//   * LDS tile = [row][8 slots of 16 B]; slot s of row r holds k-chunk s ^ ((r >> 1) & 7).  The 16 lanes that
+//     a ds_read_b128 serves per cycle then hit 16 distinct 16-byte bank groups (no bank conflicts), and the
+//     global side still reads whole 128-byte rows.
+//   * two-stage ring over the reduction dimension.  The loads that refill a stage are spread over the MFMAs of
+//     two k-steps (a burst of loads stalls the issuing wave behind the address unit's queue), and the
+//     fragments of k-step s + 1 are read while step s multiplies.  One barrier per 64-wide k-tile, placed where
+//     every wave already holds its last fragments of the tile in registers.
+//   * epilogue through LDS: each wave stages its sub-tile (and the residual rows it needs) in its own slice of
+//     the ring, so that global reads and writes are whole 16-byte-per-lane row segments.
+// -------------------------------------------------------------------------------------
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void gbl_void;
+
+template <int N>
+__device__ inline void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
+template <int BM, int BN>
+struct GemmTile {
+    static constexpr int BK = 64, NS = 2, STEPS = 4, LSPREAD = 2;
+    static constexpr int WTM = BM / 2, WTN = BN / 2;        // wave tile
+    static constexpr int PITCH = WTN * 2 + 16;              // bytes per staged epilogue row
+    static constexpr size_t ring_bytes = (size_t)NS * (BM + BN) * 8 * 16;
+    static constexpr size_t stage_bytes = (size_t)4 * WTM * PITCH;
+    static constexpr size_t smem_bytes = ring_bytes > stage_bytes ? ring_bytes : stage_bytes;
+};
+
+template <int BM, int BN, int EPI>
+__global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restrict__ A, int lda, size_t a_ss,
+                                                           const char* __restrict__ arena, size_t student_stride,
+                                                           size_t w_off, size_t b_off, bf16* __restrict__ out, int ldo,
+                                                           size_t o_ss, const bf16* __restrict__ res, int ldr,
+                                                           size_t r_ss, int Kd, int mtiles, int ntiles, int total)
+{
+    using G = GemmTile<BM, BN>;
+    constexpr int BK = G::BK, NS = G::NS, STEPS = G::STEPS, LSPREAD = G::LSPREAD;
+    constexpr int LA = BM / 32, LW = BN / 32;               // wave-loads (8 rows each) per wave per stage
+    constexpr int LPW = LA + LW, LPS = LPW / LSPREAD;
+    constexpr int TM = BM / 64, TN = BN / 64;               // 32x32 blocks per wave: tokens, features
+    constexpr int STAGE = (BM + BN) * 8;                    // 16-byte units per stage
+    static_assert(LPW % LSPREAD == 0, "loads must split evenly over the steps that carry them");
     extern __shared__ uint4 smem[];
-    uint4* sA = smem;                      // [2][KG][SA]
-    uint4* sW = smem + 2 * KG * SA;        // [2][KG][SW]
 
-    // XCD-aware tile order: consecutive workgroup ids go to different XCDs, so give each XCD a
-    // contiguous run of (student, token tile, feature tile) triples; neighbours in a run share
-    // the activation tile and the student's weights in that XCD's L2.
+    // XCD-aware tile order: consecutive workgroup ids go to different XCDs, so each XCD gets a contiguous run of
+    // (student, token tile, feature tile) triples; neighbours share the activation tile and the student's
+    // weights in that XCD's L2.
     const int chunk = (total + 7) >> 3;
     const int lin = (int)(blockIdx.x & 7) * chunk + (int)(blockIdx.x >> 3);
     if (lin >= total) return;
     const int nt = lin % ntiles, mt = (lin / ntiles) % mtiles, m = lin / (ntiles * mtiles);
     const int m0 = mt * BM, n0 = nt * BN;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave & 1, wn = wave >> 1;
     const bf16* Ag = A + (size_t)m * a_ss + (size_t)m0 * lda;
     const bf16* Wg = (const bf16*)(arena + (size_t)m * student_stride + w_off) + (size_t)n0 * Kd;
 
-    const int lrow = tid >> 3, lc = tid & 7;  // loader: row within a 32-row pass, 16-byte chunk within the row
-    uint4 ra[PA], rw[PW];
-    auto gload = [&](int k0) {
-#pragma unroll
-        for (int p = 0; p < PA; ++p) ra[p] = *(const uint4*)(Ag + (size_t)(lrow + 32 * p) * lda + k0 + lc * 8);
-#pragma unroll
-        for (int p = 0; p < PW; ++p) rw[p] = *(const uint4*)(Wg + (size_t)(lrow + 32 * p) * Kd + k0 + lc * 8);
-    };
-    auto sstore = [&](int buf) {
-#pragma unroll
-        for (int p = 0; p < PA; ++p) sA[(buf * KG + lc) * SA + lrow + 32 * p] = ra[p];
-#pragma unroll
-        for (int p = 0; p < PW; ++p) sW[(buf * KG + lc) * SW + lrow + 32 * p] = rw[p];
+    // loader: lane -> (row lane / 8 of the wave-load, LDS slot lane % 8); it fetches k-chunk slot ^ key(row)
+    const int lrow = lane >> 3, lslot = lane & 7;
+    const int lchunk = lslot ^ ((4 * wave + (lrow >> 1)) & 7);
+    const bf16* a_src = Ag + (size_t)(wave * 8 + lrow) * lda + lchunk * 8;
+    const bf16* w_src = Wg + (size_t)(wave * 8 + lrow) * Kd + lchunk * 8;
+    auto issue1 = [&](int i, int k0, int stage) {           // i-th wave-load of a stage (activation rows first)
+        if (i < LA)
+            __builtin_amdgcn_global_load_lds((gbl_void*)(a_src + (size_t)i * 32 * lda + k0),
+                                             (lds_void*)(smem + stage * STAGE + (wave + i * 4) * 64), 16, 0, 0);
+        else
+            __builtin_amdgcn_global_load_lds((gbl_void*)(w_src + (size_t)(i - LA) * 32 * Kd + k0),
+                                             (lds_void*)(smem + stage * STAGE + BM * 8 + (wave + (i - LA) * 4) * 64),
+                                             16, 0, 0);
     };
 
     f32x16 acc[TN][TM];
@@ -77,69 +120,132 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16* __restrict__
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    const int nk = Kd / BK;
-    gload(0);
-    sstore(0);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nk) gload((kt + 1) * BK);
+    const int j31 = lane & 31, g = lane >> 5;
+    int woff[TN], xoff[TM], wkey[TN], xkey[TM];
 #pragma unroll
-        for (int s = 0; s < BK / 16; ++s) {
-            const int kg = 2 * s + (lane >> 5);
-            bf16x8 wf[TN], xf[TM];
+    for (int i = 0; i < TN; ++i) { const int r = wn * G::WTN + i * 32 + j31; woff[i] = BM * 8 + r * 8; wkey[i] = (r >> 1) & 7; }
 #pragma unroll
-            for (int i = 0; i < TN; ++i) {
-                const uint4 t = sW[(buf * KG + kg) * SW + wn * (BN / 2) + i * 32 + (lane & 31)];
-                wf[i] = __builtin_bit_cast(bf16x8, t);
-            }
-#pragma unroll
-            for (int j = 0; j < TM; ++j) {
-                const uint4 t = sA[(buf * KG + kg) * SA + wm * (BM / 2) + j * 32 + (lane & 31)];
-                xf[j] = __builtin_bit_cast(bf16x8, t);
-            }
-#pragma unroll
-            for (int i = 0; i < TN; ++i)
-#pragma unroll
-                for (int j = 0; j < TM; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[j], acc[i][j], 0, 0, 0);
-        }
-        if (kt + 1 < nk) sstore(buf ^ 1);
-        __syncthreads();
-    }
+    for (int j = 0; j < TM; ++j) { const int r = wm * G::WTM + j * 32 + j31; xoff[j] = r * 8; xkey[j] = (r >> 1) & 7; }
+    bf16x8 fw[2][TN], fx[2][TM];
 
-    // Epilogue.  Accumulator element v of lane l in block (i, j): token = l % 32,
+    const int nk = Kd / BK;
+#pragma unroll
+    for (int t = 0; t < NS; ++t)
+        if (t < nk)
+#pragma unroll
+            for (int i = 0; i < LPW; ++i) issue1(i, t * BK, t);
+    if (nk >= NS) wait_vmcnt<(NS - 1) * LPW>(); else wait_vmcnt<0>();
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < TN; ++i) fw[0][i] = __builtin_bit_cast(bf16x8, smem[woff[i] + (g ^ wkey[i])]);
+#pragma unroll
+    for (int j = 0; j < TM; ++j) fx[0][j] = __builtin_bit_cast(bf16x8, smem[xoff[j] + (g ^ xkey[j])]);
+
+    int stage = 0, pstage = NS - 1;                         // stage of k-tile j, of k-tile j - 1
+    // One k-tile.  STEADY: every load / prefetch condition is known to hold, so the body has no branches and
+    // the scheduling fences below fix the interleaving of loads, LDS reads and MFMAs.
+    auto ktile = [&](int j, auto steady_c) {
+        constexpr bool STEADY = decltype(steady_c)::value;
+        const int nstage = stage + 1 == NS ? 0 : stage + 1;
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s) {
+            if (s == STEPS - 1) {
+                // every wave holds (or has requested) its last fragments of k-tile j: after the barrier nobody reads
+                // this stage any more, and k-tile j + 1 (waited for here) is visible to all
+                if (STEADY || j + NS <= nk) wait_vmcnt<(NS - 2) * LPW>(); else wait_vmcnt<0>();
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __syncthreads();
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // refill: k-tile j + NS -> this stage (from the last step on), k-tile j - 1 + NS -> previous stage
+            const int lt = s == STEPS - 1 ? j + NS : j - 1 + NS;
+            const int lstage = s == STEPS - 1 ? stage : pstage;
+            const bool do_loads = ((s + 1) % STEPS) < LSPREAD && (STEADY || ((s == STEPS - 1 || j >= 1) && lt < nk));
+            const bool do_frags = s + 1 < STEPS || STEADY || j + 1 < nk;
+            const int fstage = s + 1 < STEPS ? stage : nstage, fstep = s + 1 < STEPS ? s + 1 : 0;
+            const int kg = 2 * fstep + g;
+            constexpr int NF = TM + TN, NM = TM * TN;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {                   // quarter-steps: a share of loads, fragment reads, MFMAs
+                if (do_loads) {
+#pragma unroll
+                    for (int i = q * LPS / 4; i < (q + 1) * LPS / 4; ++i)
+                        issue1(((s + 1) % STEPS) * LPS + i, lt * BK, lstage);
+                }
+                if (do_frags) {
+#pragma unroll
+                    for (int f = q * NF / 4; f < (q + 1) * NF / 4; ++f) {
+                        if (f < TN)
+                            fw[(s + 1) & 1][f] = __builtin_bit_cast(bf16x8, smem[fstage * STAGE + woff[f] + (kg ^ wkey[f])]);
+                        else
+                            fx[(s + 1) & 1][f - TN] =
+                                __builtin_bit_cast(bf16x8, smem[fstage * STAGE + xoff[f - TN] + (kg ^ xkey[f - TN])]);
+                    }
+                }
+#pragma unroll
+                for (int idx = q * NM / 4; idx < (q + 1) * NM / 4; ++idx) {
+                    const int i = idx / TM, jj = idx % TM;
+                    acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[s & 1][i], fx[s & 1][jj], acc[i][jj], 0, 0, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        pstage = stage;
+        stage = nstage;
+    };
+    int jt = 0;
+    ktile(jt++, std::false_type{});
+    for (; jt < nk - NS; ++jt) ktile(jt, std::true_type{});
+    for (; jt < nk; ++jt) ktile(jt, std::false_type{});
+
+    // ---- epilogue.  Accumulator element v of lane l in block (i, j): token = l % 32,
     // feature = 8 * (v / 4) + 4 * (l / 32) + v % 4 inside the 32x32 block.
-    const float* bias = (const float*)(arena + (size_t)m * student_stride + b_off);
-    bf16* og = out + (size_t)m * o_ss;
-    const bf16* rg = EPI == EPI_BIAS_RESIDUAL ? res + (size_t)m * r_ss : nullptr;
+    constexpr int WTM = G::WTM, WTN = G::WTN, PITCH = G::PITCH;
+    constexpr int CPR = WTN / 8;                            // 16-byte chunks per staged row
+    constexpr int RPI = 64 / CPR;                           // rows per row-wise instruction
+    __syncthreads();                                        // all fragment reads are done: the ring is free
+    char* stg = (char*)smem + (size_t)wave * WTM * PITCH;   // this wave's private staging slice
+    const int rr = lane / CPR, cc = lane % CPR;
+    const size_t row0 = (size_t)m0 + wm * WTM;
+    const int col0 = n0 + wn * WTN;
+    if (EPI == EPI_BIAS_RESIDUAL) {                         // residual rows -> staging, whole row segments
+        const bf16* rsrc = res + (size_t)m * r_ss + row0 * ldr + col0 + cc * 8;
+#pragma unroll 4
+        for (int r0 = 0; r0 < WTM; r0 += RPI)
+            *(uint4*)(stg + (r0 + rr) * PITCH + cc * 16) = *(const uint4*)(rsrc + (size_t)(r0 + rr) * ldr);
+    }
+    const float* bias = (const float*)(arena + (size_t)m * student_stride + b_off) + col0;
 #pragma unroll
     for (int i = 0; i < TN; ++i)
 #pragma unroll
-        for (int j = 0; j < TM; ++j) {
-            const int token = m0 + wm * (BM / 2) + j * 32 + (lane & 31);
+        for (int v4 = 0; v4 < 4; ++v4) {
+            const int f = i * 32 + 8 * v4 + 4 * g;
+            const f32x4 b4 = *(const f32x4*)(bias + f);
 #pragma unroll
-            for (int v4 = 0; v4 < 4; ++v4) {
-                const int f = n0 + wn * (BN / 2) + i * 32 + 8 * v4 + 4 * (lane >> 5);
-                const f32x4 b4 = *(const f32x4*)(bias + f);
+            for (int jj = 0; jj < TM; ++jj) {
+                char* cell = stg + (jj * 32 + j31) * PITCH + f * 2;
                 float r[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) r[e] = acc[i][j][4 * v4 + e] + b4[e];
+                for (int e = 0; e < 4; ++e) r[e] = acc[i][jj][4 * v4 + e] + b4[e];
                 if (EPI == EPI_BIAS_GELU) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) r[e] = gelu_erf(r[e]);
+                    for (int e = 0; e < 4; ++e) r[e] = gelu_erf_fast(r[e]);
                 }
                 if (EPI == EPI_BIAS_RESIDUAL) {
-                    const bf16x4 x4 = *(const bf16x4*)(rg + (size_t)token * ldr + f);
+                    const bf16x4 x4 = *(const bf16x4*)cell;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) r[e] += (float)x4[e];
                 }
                 bf16x4 o4;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) o4[e] = (bf16)r[e];
-                *(bf16x4*)(og + (size_t)token * ldo + f) = o4;
+                *(bf16x4*)cell = o4;
             }
         }
+    bf16* dst = out + (size_t)m * o_ss + row0 * ldo + col0 + cc * 8;
+#pragma unroll 4
+    for (int r0 = 0; r0 < WTM; r0 += RPI)
+        *(uint4*)(dst + (size_t)(r0 + rr) * ldo) = *(const uint4*)(stg + (r0 + rr) * PITCH + cc * 16);
 }
 
 // -------------------------------------------------------------------------------------
@@ -201,9 +307,8 @@ hipError_t launch_bf16_tile(const sp_model* M, const void* A, int lda, size_t w_
                             const void* residual, int ldr, int mrows, int N, int Kd, int k, size_t a_ss, size_t o_ss,
                             size_t r_ss, hipStream_t s)
 {
-    constexpr int BK = 64;
-    constexpr size_t smem = (size_t)2 * (BK / 8) * ((BM + 1) + (BN + 1)) * sizeof(uint4);
-    auto kern = gemm_bf16_kernel<BM, BN, BK, EPI>;
+    constexpr size_t smem = GemmTile<BM, BN>::smem_bytes;
+    auto kern = gemm_bf16_kernel<BM, BN, EPI>;
     if (smem > 48 * 1024) {
         static bool raised = false;   // per instantiation; the attribute is sticky for the process
         if (!raised) {
