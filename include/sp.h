@@ -134,13 +134,16 @@ int sp_pack(const int32_t* lengths_host, int32_t batch, int32_t* cu_seqlens_host
  * (token-tile padded) in the model's activation type (float or bf16), row-major.
  *   x    [rows][H]  hidden state entering the next layer (after the last layer:
  *                   the final states)
- *   qkv  [rows][3H] query | key | value projections of the last layer run
+ *   qkv  [rows][3H] query | key | value projections of the last layer run; in bf16
+ *                   mode the value slice is not written: the values are kept
+ *                   transposed for the attention kernel, in
+ *   vt   [H][rows]  value projection, feature-major (bf16 mode only)
  *   att  [rows][H]  attention output of the last layer run
  *   x1   [rows][H]  state after the attention block's LayerNorm
  *   g    [rows][F]  GELU(FFN up-projection)
  *   z    float32 [K][batch][C] per-student classifier outputs before the sum */
 typedef struct {
-    size_t x, qkv, att, x1, g, z;
+    size_t x, qkv, vt, att, x1, g, z;
     int32_t rows;      /* padded token rows per student */
     int32_t act_bytes; /* 4 or 2 */
 } sp_ws_layout;

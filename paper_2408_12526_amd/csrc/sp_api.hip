@@ -28,11 +28,7 @@ static bool config_supported(const sp_config& c)
 {
     if (c.hidden % c.heads || c.hidden / c.heads != 64) return false;
     if (c.classes > 16 || c.hidden > 1024) return false;
-    if (c.dtype == SP_DTYPE_BF16) {
-        if (c.hidden % 64 || c.ffn % 64) return false;
-    } else {
-        if (c.hidden % 64 || c.ffn % 64) return false;
-    }
+    if (c.hidden % 128 || c.ffn % 128) return false;   // reduction depth of every projection: whole 64-wide k-tiles, at least two
     return true;
 }
 
@@ -83,6 +79,7 @@ WsLayout make_ws_layout(const sp_config& c, int total_tokens, int batch)
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
     W.x = take(K * rows * H * ab);
     W.qkv = take(K * rows * 3 * H * ab);
+    W.vt = take(K * rows * H * ab);
     W.att = take(K * rows * H * ab);
     W.u = take(K * rows * H * ab);
     W.x1 = take(K * rows * H * ab);
@@ -210,7 +207,7 @@ static int run_forward(const sp_model* M, const int32_t* ids, const int32_t* cu,
     const int mtile = T > 256 ? 256 : (T > 64 ? 128 : 64);
     const int mrows = (T + mtile - 1) / mtile * mtile;
     const size_t ab = W.act_bytes;
-    void *x = w + W.x, *qkv = w + W.qkv, *att = w + W.att, *u = w + W.u, *x1 = w + W.x1, *g = w + W.g;
+    void *x = w + W.x, *qkv = w + W.qkv, *vt = w + W.vt, *att = w + W.att, *u = w + W.u, *x1 = w + W.x1, *g = w + W.g;
     float* z = (float*)(w + W.z);
     const size_t sH = (size_t)rows * H * ab, s3H = 3 * sH, sF = (size_t)rows * F * ab;
     const ArenaLayout& L = M->L;
@@ -218,14 +215,18 @@ static int run_forward(const sp_model* M, const int32_t* ids, const int32_t* cu,
 #define SP_TRY(expr) do { if ((expr) != hipSuccess) return SP_EHIP; } while (0)
 #define SP_MARK(ph) do { if (pt) pt->mark(ph, s); } while (0)
     SP_MARK(-1);
-    SP_TRY(launch_embed_ln(M, ids, cu, B, T, rows, mrows, k, x, s));
+    SP_TRY(launch_embed_ln(M, ids, cu, B, T, rows, mrows, k, x, att, s));
     SP_MARK(SP_PHASE_EMBED);
     for (int l = 0; l < stop_layers; ++l) {
         const size_t lo = L.layer0 + (size_t)l * L.layer_stride;
-        SP_TRY(launch_gemm(M, x, H, lo + L.wqkv, lo + L.bqkv, qkv, 3 * H, nullptr, 0, mrows, 3 * H, H, k, EPI_BIAS, sH,
-                           s3H, 0, s));
+        if (c.dtype == SP_DTYPE_BF16)
+            SP_TRY(launch_gemm(M, x, H, lo + L.wqkv, lo + L.bqkv, qkv, 3 * H, nullptr, 0, mrows, 3 * H, H, k, EPI_QKV,
+                               sH, s3H, 0, s, vt, 2 * H, rows, sH));
+        else
+            SP_TRY(launch_gemm(M, x, H, lo + L.wqkv, lo + L.bqkv, qkv, 3 * H, nullptr, 0, mrows, 3 * H, H, k, EPI_BIAS,
+                               sH, s3H, 0, s));
         SP_MARK(SP_PHASE_QKV);
-        SP_TRY(launch_attention(M, qkv, att, cu, B, T, max_seqlen, rows, k, s));
+        SP_TRY(launch_attention(M, qkv, vt, att, cu, B, T, max_seqlen, rows, k, s));
         SP_MARK(SP_PHASE_ATTENTION);
         SP_TRY(launch_gemm(M, att, H, lo + L.wo, lo + L.bo, u, H, x, H, mrows, H, H, k, EPI_BIAS_RESIDUAL, sH, sH, sH,
                            s));
@@ -279,7 +280,7 @@ int sp_workspace_layout(const sp_config* cfg, int32_t total_tokens, int32_t batc
     if (!config_ok(cfg) || !out) return SP_EINVAL;
     if (total_tokens < 1 || batch < 1) return SP_ESHAPE;
     const WsLayout W = make_ws_layout(*cfg, total_tokens, batch);
-    out->x = W.x; out->qkv = W.qkv; out->att = W.att; out->x1 = W.x1; out->g = W.g; out->z = W.z;
+    out->x = W.x; out->qkv = W.qkv; out->vt = W.vt; out->att = W.att; out->x1 = W.x1; out->g = W.g; out->z = W.z;
     out->rows = W.rows; out->act_bytes = W.act_bytes;
     return SP_OK;
 }

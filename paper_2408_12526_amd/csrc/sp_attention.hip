@@ -23,7 +23,8 @@ constexpr int kVStride = 68;    // bf16 elements per row of the transposed value
 //                     probabilities, which already sit in the B-operand register layout
 //                     once the reduction slots of V^T are enumerated in the same key order)
 // -------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void attention_bf16_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ att,
+__global__ __launch_bounds__(256) void attention_bf16_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ vt,
+                                                             bf16* __restrict__ att,
                                                              const int32_t* __restrict__ cu, int B, int Tn, int rows,
                                                              int H, int heads, int max_seqlen, int nqc, int min_len)
 {
@@ -68,22 +69,24 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(const bf16* __restr
     float mrun = -INFINITY, lrun = 0.f;
     const float sl2 = 0.125f * 1.44269504088896341f;   // 1/sqrt(64) * log2(e)
 
+    // Key tiles start at a token index that is a multiple of 8, so that the transposed values (token-contiguous
+    // rows) can be fetched 16 bytes at a time; tokens in front of the sequence are masked below.
+    const int lead = t0 & 7;
+    const bf16* vbase = vt + ((size_t)m * H + h * kD) * rows + (t0 - lead);
     const int lrow = tid >> 3, lc = tid & 7;
-    for (int kt0 = 0; kt0 < L; kt0 += kKeyTile) {
-        // stage the key tile and the transposed value tile (keys beyond L are zero)
+    for (int kt0 = -lead; kt0 < L; kt0 += kKeyTile) {
+        // stage the key tile (rows = keys) and the value tile (rows = head dimensions); what lies beyond the
+        // sequence is zero-filled
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
-            const int key = lrow + 32 * p;
+            const int r = lrow + 32 * p;                      // key of the tile, or head dimension
             uint4 kk = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
-            if (kt0 + key < L) {
-                const bf16* r = base + (size_t)(kt0 + key) * ld + lc * 8;
-                kk = *(const uint4*)(r + H);
-                vv = *(const uint4*)(r + 2 * H);
-            }
-            sK[lc * kKStride + key] = kk;
-            const bf16x8 v8 = __builtin_bit_cast(bf16x8, vv);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) sVt[(lc * 8 + e) * kVStride + key] = v8[e];
+            if (kt0 + r >= 0 && kt0 + r < L) kk = *(const uint4*)(base + (ptrdiff_t)(kt0 + r) * (ptrdiff_t)ld + H + lc * 8);
+            if (kt0 + lc * 8 < L) vv = *(const uint4*)(vbase + (size_t)r * rows + (kt0 + lead) + lc * 8);
+            sK[lc * kKStride + r] = kk;
+            uint2* vd = (uint2*)(sVt + r * kVStride + lc * 8);
+            vd[0] = uint2{vv.x, vv.y};
+            vd[1] = uint2{vv.z, vv.w};
         }
         __syncthreads();
 
@@ -107,7 +110,7 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(const bf16* __restr
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int key = kt0 + kb * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-                    const float sv = key < L ? sc[kb][v] * sl2 : -INFINITY;
+                    const float sv = key >= 0 && key < L ? sc[kb][v] * sl2 : -INFINITY;
                     sc[kb][v] = sv;
                     mx = fmaxf(mx, sv);
                 }
@@ -178,8 +181,9 @@ constexpr int kSKey = 32;                 // keys per tile
 constexpr int kSKStride = kSKey + 1;      // 16-byte units per d-group of the key tile
 constexpr int kSVStride = 36;             // bf16 elements per row of the transposed value tile (72 B)
 
-__global__ __launch_bounds__(256, 3) void attention_bf16_short_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ att,
-                                                                   const int32_t* __restrict__ cu, int B, int Tn,
+__global__ __launch_bounds__(256, 3) void attention_bf16_short_kernel(const bf16* __restrict__ qkv,
+                                                                      const bf16* __restrict__ vt, bf16* __restrict__ att,
+                                                                      const int32_t* __restrict__ cu, int B, int Tn,
                                                                    int rows, int H, int heads, int max_seqlen,
                                                                    int ngroups, int max_len)
 {
@@ -204,7 +208,12 @@ __global__ __launch_bounds__(256, 3) void attention_bf16_short_kernel(const bf16
     const size_t ld = (size_t)3 * H;
     const bf16* base = qkv + ((size_t)m * rows + t0) * ld + h * kD;
     const float sl2 = 0.125f * 1.44269504088896341f;
-    const int lkey = lane >> 3, lc = lane & 7;      // tile loader: 8 keys x 8 sixteen-byte chunks per instruction
+    const int lkey = lane >> 3, lc = lane & 7;      // key loader: 8 keys x 8 sixteen-byte chunks per instruction
+    const int vrow = lane >> 2, vc = lane & 3;      // value loader: 16 head dimensions x 4 chunks of 8 keys
+    // key tiles start at a token index that is a multiple of 8 (16-byte fetches of the token-contiguous values);
+    // tokens in front of the sequence are masked
+    const int lead = t0 & 7;
+    const bf16* vbase = vt + ((size_t)m * H + h * kD) * rows + (t0 - lead);
 
     for (int q0 = 0; q0 < L; q0 += 32) {
         const int q = q0 + j;
@@ -223,29 +232,25 @@ __global__ __launch_bounds__(256, 3) void attention_bf16_short_kernel(const bf16
         float mrun = -INFINITY, lrun = 0.f;
 
         uint4 kreg[4], vreg[4];
-        auto fetch = [&](int kt0) {
+        auto fetch = [&](int kt0) {                  // kt0: first key of the tile relative to the sequence start
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
                 const int key = kt0 + p * 8 + lkey;
                 kreg[p] = uint4{0, 0, 0, 0};
                 vreg[p] = uint4{0, 0, 0, 0};
-                if (key < L) {
-                    const bf16* r = base + (size_t)key * ld + lc * 8;
-                    kreg[p] = *(const uint4*)(r + H);
-                    vreg[p] = *(const uint4*)(r + 2 * H);
-                }
+                if (key >= 0 && key < L) kreg[p] = *(const uint4*)(base + (ptrdiff_t)key * (ptrdiff_t)ld + H + lc * 8);
+                if (kt0 + vc * 8 < L) vreg[p] = *(const uint4*)(vbase + (size_t)(p * 16 + vrow) * rows + (kt0 + lead) + vc * 8);
             }
         };
-        fetch(0);
-        for (int kt0 = 0; kt0 < L; kt0 += kSKey) {
-            // registers -> this wave's LDS slice (keys beyond L were fetched as zeros)
+        fetch(-lead);
+        for (int kt0 = -lead; kt0 < L; kt0 += kSKey) {
+            // registers -> this wave's LDS slice (what lies beyond the sequence was fetched as zeros)
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
-                const int key = p * 8 + lkey;
-                sK[lc * kSKStride + key] = kreg[p];
-                const bf16x8 v8 = __builtin_bit_cast(bf16x8, vreg[p]);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) sVt[(lc * 8 + e) * kSVStride + key] = v8[e];
+                sK[lc * kSKStride + p * 8 + lkey] = kreg[p];
+                uint2* vd = (uint2*)(sVt + (p * 16 + vrow) * kSVStride + vc * 8);
+                vd[0] = uint2{vreg[p].x, vreg[p].y};
+                vd[1] = uint2{vreg[p].z, vreg[p].w};
             }
             if (kt0 + kSKey < L) fetch(kt0 + kSKey);
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -263,7 +268,7 @@ __global__ __launch_bounds__(256, 3) void attention_bf16_short_kernel(const bf16
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int key = kt0 + 8 * (v >> 2) + 4 * g + (v & 3);
-                const float sv = key < L ? sc[v] * sl2 : -INFINITY;
+                const float sv = key >= 0 && key < L ? sc[v] * sl2 : -INFINITY;
                 sc[v] = sv;
                 mx = fmaxf(mx, sv);
             }
@@ -361,8 +366,8 @@ __global__ __launch_bounds__(64) void attention_f32_kernel(const float* __restri
 
 }  // namespace
 
-hipError_t launch_attention(const sp_model* M, const void* qkv, void* att, const int32_t* cu, int B, int T,
-                            int max_seqlen, int rows, int k, hipStream_t s)
+hipError_t launch_attention(const sp_model* M, const void* qkv, const void* vt, void* att, const int32_t* cu, int B,
+                            int T, int max_seqlen, int rows, int k, hipStream_t s)
 {
     const sp_config& c = M->cfg;
     if (c.hidden / c.heads != kD) return hipErrorInvalidValue;
@@ -372,15 +377,15 @@ hipError_t launch_attention(const sp_model* M, const void* qkv, void* att, const
         constexpr int kShortLen = 128;
         const int ngroups = (c.heads + 3) / 4;
         hipLaunchKernelGGL(attention_bf16_short_kernel, dim3((unsigned)(B * ngroups), k), dim3(256), 0, s,
-                           (const bf16*)qkv, (bf16*)att, cu, B, T, rows, c.hidden, c.heads, max_seqlen, ngroups,
-                           kShortLen);
+                           (const bf16*)qkv, (const bf16*)vt, (bf16*)att, cu, B, T, rows, c.hidden, c.heads, max_seqlen,
+                           ngroups, kShortLen);
         if (max_seqlen > kShortLen) {
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
             const int nqc = (max_seqlen + kQPerWg - 1) / kQPerWg;
             dim3 grid((unsigned)(B * c.heads * nqc), k);
-            hipLaunchKernelGGL(attention_bf16_kernel, grid, dim3(256), 0, s, (const bf16*)qkv, (bf16*)att, cu, B, T,
-                               rows, c.hidden, c.heads, max_seqlen, nqc, kShortLen);
+            hipLaunchKernelGGL(attention_bf16_kernel, grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)vt,
+                               (bf16*)att, cu, B, T, rows, c.hidden, c.heads, max_seqlen, nqc, kShortLen);
         }
     } else {
         const int nqc = (max_seqlen + 63) / 64;

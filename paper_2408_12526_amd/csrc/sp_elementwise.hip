@@ -79,16 +79,21 @@ __global__ __launch_bounds__(256) void embed_ln_kernel(const char* arena, size_t
                                                        size_t pos_off, size_t g_off, size_t b_off,
                                                        const int32_t* __restrict__ ids,
                                                        const int32_t* __restrict__ cu, int B, int Tn, int rows,
-                                                       int mrows, int H, int V, int P, float eps, T* __restrict__ x)
+                                                       int mrows, int H, int V, int P, float eps, T* __restrict__ x,
+                                                       T* __restrict__ att)
 {
     const int m = blockIdx.y, lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= mrows) return;
     const int nch = H >> 3;
     T* out = x + ((size_t)m * rows + row) * H;
-    if (row >= Tn) {  // padding rows of the token tile: defined contents, never read by attention or the head
-        const float zero[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        for (int c = lane; c < nch; c += 64) store8(out + c * 8, zero);
+    if (row >= Tn) {
+        // Padding rows of the token tile.  They never reach a result, but the projections compute them and the
+        // attention kernels fetch values in chunks of eight tokens, so they must hold finite numbers: zero the
+        // hidden state here and, once per call, the attention output rows that no kernel writes.
+        const float zero8[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        T* arow = att + ((size_t)m * rows + row) * H;
+        for (int c = lane; c < nch; c += 64) { store8(out + c * 8, zero8); store8(arow + c * 8, zero8); }
         return;
     }
     // sequence of this row: largest b with cu[b] <= row
@@ -172,7 +177,8 @@ __global__ __launch_bounds__(256) void head_pool_kernel(const char* arena, size_
 #pragma unroll
     for (int s = 0; s < kSeqPerWg; ++s) acc[s] = 0.f;
     const int per = H / 4, i0 = part * per;   // this wave's share of the reduction index (a multiple of 16)
-    for (int i = i0; i < i0 + per; i += 4) {
+#pragma unroll 4
+    for (int i = i0; i < i0 + per; i += 4) {     // unrolled: sixteen weight loads in flight per lane
         float w[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) w[e] = (float)Wp[(size_t)(i + e) * H + n];
@@ -222,17 +228,17 @@ __global__ void head_sum_kernel(const char* arena, size_t student_stride, size_t
 }  // namespace
 
 hipError_t launch_embed_ln(const sp_model* M, const int32_t* ids, const int32_t* cu, int B, int T, int rows, int mrows,
-                           int k, void* x, hipStream_t s)
+                           int k, void* x, void* att, hipStream_t s)
 {
     const sp_config& c = M->cfg;
     const ArenaLayout& L = M->L;
     dim3 grid((mrows + 3) / 4, k);
     if (c.dtype == SP_DTYPE_BF16)
         hipLaunchKernelGGL(embed_ln_kernel<bf16>, grid, dim3(256), 0, s, M->arena, L.student_stride, L.tok, L.pos,
-                           L.emb_g, L.emb_b, ids, cu, B, T, rows, mrows, c.hidden, c.vocab, c.max_pos, c.ln_eps, (bf16*)x);
+                           L.emb_g, L.emb_b, ids, cu, B, T, rows, mrows, c.hidden, c.vocab, c.max_pos, c.ln_eps, (bf16*)x, (bf16*)att);
     else
         hipLaunchKernelGGL(embed_ln_kernel<float>, grid, dim3(256), 0, s, M->arena, L.student_stride, L.tok, L.pos,
-                           L.emb_g, L.emb_b, ids, cu, B, T, rows, mrows, c.hidden, c.vocab, c.max_pos, c.ln_eps, (float*)x);
+                           L.emb_g, L.emb_b, ids, cu, B, T, rows, mrows, c.hidden, c.vocab, c.max_pos, c.ln_eps, (float*)x, (float*)att);
     return hipGetLastError();
 }
 

@@ -73,7 +73,8 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
                                                            const char* __restrict__ arena, size_t student_stride,
                                                            size_t w_off, size_t b_off, bf16* __restrict__ out, int ldo,
                                                            size_t o_ss, const bf16* __restrict__ res, int ldr,
-                                                           size_t r_ss, int Kd, int mtiles, int ntiles, int total)
+                                                           size_t r_ss, int Kd, int mtiles, int ntiles, int total,
+                                                           bf16* __restrict__ out2, int n_split, int ld2, size_t o2_ss)
 {
     using G = GemmTile<BM, BN>;
     constexpr int BK = G::BK, NS = G::NS, STEPS = G::STEPS, LSPREAD = G::LSPREAD;
@@ -215,6 +216,9 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
             *(uint4*)(stg + (r0 + rr) * PITCH + cc * 16) = *(const uint4*)(rsrc + (size_t)(r0 + rr) * ldr);
     }
     const float* bias = (const float*)(arena + (size_t)m * student_stride + b_off) + col0;
+    // EPI_QKV: feature tiles at or beyond n_split (the value projection) are staged feature-major and written
+    // transposed, out2[feature - n_split][token]; the choice is uniform over the workgroup.
+    const bool transposed = EPI == EPI_QKV && n0 >= n_split;
 #pragma unroll
     for (int i = 0; i < TN; ++i)
 #pragma unroll
@@ -236,16 +240,25 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
 #pragma unroll
                     for (int e = 0; e < 4; ++e) r[e] += (float)x4[e];
                 }
-                bf16x4 o4;
+                if (EPI == EPI_QKV && transposed) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) o4[e] = (bf16)r[e];
-                *(bf16x4*)cell = o4;
+                    for (int e = 0; e < 4; ++e) *(bf16*)(stg + (f + e) * PITCH + (jj * 32 + j31) * 2) = (bf16)r[e];
+                } else {
+                    bf16x4 o4;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o4[e] = (bf16)r[e];
+                    *(bf16x4*)cell = o4;
+                }
             }
         }
-    bf16* dst = out + (size_t)m * o_ss + row0 * ldo + col0 + cc * 8;
+    // staged rows -> global memory, 16 bytes per lane, whole row segments (rows are tokens, or features if transposed)
+    bf16* dst = EPI == EPI_QKV && transposed
+                    ? out2 + (size_t)m * o2_ss + (size_t)(col0 - n_split) * ld2 + row0 + cc * 8
+                    : out + (size_t)m * o_ss + row0 * ldo + col0 + cc * 8;
+    const size_t dpitch = EPI == EPI_QKV && transposed ? (size_t)ld2 : (size_t)ldo;
 #pragma unroll 4
     for (int r0 = 0; r0 < WTM; r0 += RPI)
-        *(uint4*)(dst + (size_t)(r0 + rr) * ldo) = *(const uint4*)(stg + (r0 + rr) * PITCH + cc * 16);
+        *(uint4*)(dst + (size_t)(r0 + rr) * dpitch) = *(const uint4*)(stg + (r0 + rr) * PITCH + cc * 16);
 }
 
 // -------------------------------------------------------------------------------------
@@ -305,8 +318,9 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
 template <int BM, int BN, int EPI>
 hipError_t launch_bf16_tile(const sp_model* M, const void* A, int lda, size_t w_off, size_t b_off, void* out, int ldo,
                             const void* residual, int ldr, int mrows, int N, int Kd, int k, size_t a_ss, size_t o_ss,
-                            size_t r_ss, hipStream_t s)
+                            size_t r_ss, hipStream_t s, void* out2, int n_split, int ld2, size_t o2_ss)
 {
+    static_assert(BM == BN, "the transposed epilogue assumes a square wave tile");
     constexpr size_t smem = GemmTile<BM, BN>::smem_bytes;
     auto kern = gemm_bf16_kernel<BM, BN, EPI>;
     if (smem > 48 * 1024) {
@@ -321,18 +335,20 @@ hipError_t launch_bf16_tile(const sp_model* M, const void* A, int lda, size_t w_
     const int grid = ((total + 7) / 8) * 8;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), smem, s, (const bf16*)A, lda, a_ss / 2, M->arena,
                        M->L.student_stride, w_off, b_off, (bf16*)out, ldo, o_ss / 2, (const bf16*)residual, ldr,
-                       r_ss / 2, Kd, mtiles, ntiles, total);
+                       r_ss / 2, Kd, mtiles, ntiles, total, (bf16*)out2, n_split, ld2, o2_ss / 2);
     return hipGetLastError();
 }
 
 template <int EPI>
 hipError_t launch_bf16(const sp_model* M, const void* A, int lda, size_t w_off, size_t b_off, void* out, int ldo,
                        const void* residual, int ldr, int mrows, int N, int Kd, int k, size_t a_ss, size_t o_ss,
-                       size_t r_ss, hipStream_t s)
+                       size_t r_ss, hipStream_t s, void* out2, int n_split, int ld2, size_t o2_ss)
 {
-#define SP_ARGS M, A, lda, w_off, b_off, out, ldo, residual, ldr, mrows, N, Kd, k, a_ss, o_ss, r_ss, s
-    if (mrows % 256 == 0 && mrows >= 2048 && N % 256 == 0) return launch_bf16_tile<256, 256, EPI>(SP_ARGS);
-    if (mrows % 128 == 0 && N % 128 == 0) return launch_bf16_tile<128, 128, EPI>(SP_ARGS);
+#define SP_ARGS M, A, lda, w_off, b_off, out, ldo, residual, ldr, mrows, N, Kd, k, a_ss, o_ss, r_ss, s, out2, n_split, ld2, o2_ss
+    // a feature tile must lie entirely on one side of n_split
+    if (mrows % 256 == 0 && mrows >= 2048 && N % 256 == 0 && n_split % 256 == 0)
+        return launch_bf16_tile<256, 256, EPI>(SP_ARGS);
+    if (mrows % 128 == 0 && N % 128 == 0 && n_split % 128 == 0) return launch_bf16_tile<128, 128, EPI>(SP_ARGS);
     return launch_bf16_tile<64, 64, EPI>(SP_ARGS);
 #undef SP_ARGS
 }
@@ -353,17 +369,20 @@ hipError_t launch_f32(const sp_model* M, const void* A, int lda, size_t w_off, s
 
 hipError_t launch_gemm(const sp_model* M, const void* A, int lda, size_t w_off, size_t b_off, void* out, int ldo,
                        const void* residual, int ldr, int mrows, int N, int Kd, int k, Epilogue epi,
-                       size_t a_student_stride, size_t o_student_stride, size_t r_student_stride, hipStream_t s)
+                       size_t a_student_stride, size_t o_student_stride, size_t r_student_stride, hipStream_t s,
+                       void* out2, int n_split, int ld2, size_t o2_student_stride)
 {
     // shapes the kernels assume; config_supported() guarantees them for every model that loads
-    if (mrows % 64 || N % 64 || Kd % 64 || (epi == EPI_BIAS_RESIDUAL && !residual)) return hipErrorInvalidValue;
+    if (mrows % 64 || N % 64 || Kd % 128 || (epi == EPI_BIAS_RESIDUAL && !residual)) return hipErrorInvalidValue;
+    if (epi == EPI_QKV && (M->cfg.dtype != SP_DTYPE_BF16 || !out2 || n_split % 64 || ld2 % 8)) return hipErrorInvalidValue;
 #define SP_ARGS M, A, lda, w_off, b_off, out, ldo, residual, ldr, mrows, N, Kd, k, a_student_stride, \
                 o_student_stride, r_student_stride, s
     if (M->cfg.dtype == SP_DTYPE_BF16) {
         switch (epi) {
-            case EPI_BIAS: return launch_bf16<EPI_BIAS>(SP_ARGS);
-            case EPI_BIAS_GELU: return launch_bf16<EPI_BIAS_GELU>(SP_ARGS);
-            default: return launch_bf16<EPI_BIAS_RESIDUAL>(SP_ARGS);
+            case EPI_BIAS: return launch_bf16<EPI_BIAS>(SP_ARGS, nullptr, 0, 0, 0);
+            case EPI_BIAS_GELU: return launch_bf16<EPI_BIAS_GELU>(SP_ARGS, nullptr, 0, 0, 0);
+            case EPI_QKV: return launch_bf16<EPI_QKV>(SP_ARGS, out2, n_split, ld2, o2_student_stride);
+            default: return launch_bf16<EPI_BIAS_RESIDUAL>(SP_ARGS, nullptr, 0, 0, 0);
         }
     }
     switch (epi) {

@@ -35,7 +35,7 @@ ArenaLayout make_arena_layout(const sp_config& c);
 
 // Workspace carve-up for one call.
 struct WsLayout {
-    size_t x, qkv, att, u, x1, g, z, zpart, end;
+    size_t x, qkv, vt, att, u, x1, g, z, zpart, end;
     int rows;
     int act_bytes;
 };
@@ -54,25 +54,30 @@ namespace sp {
 // ---- launchers (each returns the hipError_t of its launch) ------------------
 
 // X[m][row][:] = LN(tok[id[row]] + pos[row - cu[seq(row)]]) for row < T; zero rows up to `rows`.
+// Rows T..mrows of x and of att are zeroed.
 hipError_t launch_embed_ln(const sp_model* M, const int32_t* ids, const int32_t* cu, int B, int T, int rows,
-                           int mrows, int k, void* x, hipStream_t s);
+                           int mrows, int k, void* x, void* att, hipStream_t s);
 
 // out[m][row][:] = LN(u[m][row][:]; g, b); g/b are byte offsets into the student slab.
 hipError_t launch_layernorm(const sp_model* M, const void* u, void* out, int rows, int mrows, int k, size_t g_off,
                             size_t b_off, hipStream_t s);
 
-enum Epilogue { EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_BIAS_RESIDUAL = 2 };
+// EPI_QKV (bf16 path only): bias; output columns >= n_split (the value projection) are written transposed,
+// out2[m][column - n_split][row], so that attention reads key-contiguous value tiles.
+enum Epilogue { EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_BIAS_RESIDUAL = 2, EPI_QKV = 3 };
 
 // out[m][row][0..N) = epi(A[m][row][0..Kd) . W^T + bias), W stored [N][Kd] at w_off of each student.
 // lda / ldo / ldr are row strides in elements; residual may be null unless EPI_BIAS_RESIDUAL;
 // mrows (a multiple of 64, <= the padded row count) is how many rows are computed.
 hipError_t launch_gemm(const sp_model* M, const void* A, int lda, size_t w_off, size_t b_off, void* out, int ldo,
                        const void* residual, int ldr, int mrows, int N, int Kd, int k, Epilogue epi,
-                       size_t a_student_stride, size_t o_student_stride, size_t r_student_stride, hipStream_t s);
+                       size_t a_student_stride, size_t o_student_stride, size_t r_student_stride, hipStream_t s,
+                       void* out2 = nullptr, int n_split = 0, int ld2 = 0, size_t o2_student_stride = 0);
 
 // att[m][t][h*64..] = softmax(q k^T / 8) v inside each sequence; qkv rows are [q | k | v] of width 3H.
-hipError_t launch_attention(const sp_model* M, const void* qkv, void* att, const int32_t* cu, int B, int T,
-                            int max_seqlen, int rows, int k, hipStream_t s);
+// bf16 path: the values are read from vt[m][H][rows] (transposed) instead of the third slice of qkv.
+hipError_t launch_attention(const sp_model* M, const void* qkv, const void* vt, void* att, const int32_t* cu, int B,
+                            int T, int max_seqlen, int rows, int k, hipStream_t s);
 
 // z[m][b][c] = tanh(x[m][cu[b]] Wp + bp) Wc + bc ; logits[b][c] = sum_{m<k} z[m][b][c] (m ascending).
 hipError_t launch_head(const sp_model* M, const void* x, const int32_t* cu, int B, int T, int rows, int k, float* z,

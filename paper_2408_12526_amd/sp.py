@@ -27,7 +27,7 @@ class sp_config(C.Structure):
 
 
 class sp_ws_layout(C.Structure):
-    _fields_ = [(n, C.c_size_t) for n in ("x", "qkv", "att", "x1", "g", "z")] + [("rows", C.c_int32),
+    _fields_ = [(n, C.c_size_t) for n in ("x", "qkv", "vt", "att", "x1", "g", "z")] + [("rows", C.c_int32),
                                                                                    ("act_bytes", C.c_int32)]
 
 
@@ -182,7 +182,13 @@ class Students:
         dt = torch.bfloat16 if lay.act_bytes == 2 else torch.float32
         n = k_active * lay.rows * width
         t = ws[off:off + n * lay.act_bytes].view(dt).view(k_active, lay.rows, width)
-        return t[:, :total_tokens].double().cpu().numpy()
+        t = t[:, :total_tokens].double()
+        if name == "qkv" and lay.act_bytes == 2:      # bf16 mode keeps the values feature-major in `vt`
+            nv = k_active * H * lay.rows
+            vt = ws[lay.vt:lay.vt + nv * 2].view(dt).view(k_active, H, lay.rows)
+            t = t.clone()
+            t[:, :, 2 * H:] = vt[:, :, :total_tokens].double().transpose(1, 2)
+        return t.cpu().numpy()
 
     def close(self):
         if self.handle:

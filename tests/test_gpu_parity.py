@@ -58,15 +58,17 @@ STAGE_SHAPES = {
                                dtype="bf16"),
 }
 STAGE_LENGTHS = (5, 1, 96, 33, 64, 200, 70, 129)   # spans several key tiles, query blocks and a ragged tail
+SINGLE_TILE_LENGTHS = (7, 1, 30, 19)                # 57 tokens: the single-tile (latency) code path of the bf16 mode
 
 
-@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
-def test_every_stage_against_oracle_pieces(sp, oracle64, dtype):
+@pytest.mark.parametrize("dtype,lens", [("fp32", STAGE_LENGTHS), ("bf16", STAGE_LENGTHS),
+                                        ("bf16", SINGLE_TILE_LENGTHS), ("bf16", (64,))])
+def test_every_stage_against_oracle_pieces(sp, oracle64, dtype, lens):
     """Each kernel in isolation: its output against the oracle's piece applied to the kernel's own input
     (as the HIP path left it in the workspace), so that one kernel's rounding is not charged to the next."""
     shape = STAGE_SHAPES[dtype]
     rng = np.random.default_rng(21)
-    lengths = np.array(STAGE_LENGTHS, dtype=np.int32)
+    lengths = np.array(lens, dtype=np.int32)
     ids = synth.make_ids(rng, int(lengths.sum()), shape.vocab)
     blob = synth.make_weights(rng, shape, std=0.08, ln_random=True, qk_std=0.25)
     ow = oracle_weights(blob, shape)
