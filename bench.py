@@ -52,6 +52,11 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", choices=["burst", "latency"], default=None,
                     help="run one workload only (for profiling a single launch configuration)")
+    ap.add_argument("--burst-k", default=None,
+                    help="comma-separated k_active values for the burst workload (default: 8,4,2); profiles of one "
+                         "launch configuration use --burst-k 8")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a plain 1 GiB device-to-device copy a few times (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
@@ -64,7 +69,15 @@ def main():
         print("bench.py needs an MI355X; there is no CPU fallback", file=sys.stderr)
         sys.exit(2)
     dev = torch.device("cuda:0")
-    out = {}
+    if args.calibrate_copy:
+        n = 1 << 30
+        a = torch.empty(n, dtype=torch.uint8, device=dev).fill_(1)
+        b = torch.empty(n, dtype=torch.uint8, device=dev)
+        for _ in range(5):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "device copy", "bytes_read_per_copy": n, "bytes_written_per_copy": n}))
+        return
 
     # ------------------------------------------------------------------ burst workload (batch 256)
     w4 = synth.WORKLOADS[4]
@@ -89,7 +102,10 @@ def main():
     burst = {}
     phases = {}
     if args.only in (None, "burst"):
-        for k in w4.k_actives:
+        burst_ks = [int(v) for v in args.burst_k.split(",")] if args.burst_k else list(w4.k_actives)
+        if 8 not in burst_ks:
+            burst_ks.insert(0, 8)
+        for k in burst_ks:
             sec = timed_steps(st4, d_ids4, d_cu4, mx4, k, logits4, ws4, args.steps, args.warmup)
             burst[k] = {"ms_per_step": sec * 1e3, "sequences_per_s": B4 / sec, "tokens_per_s": T4 / sec}
         # per-phase device time at k_active = 8 (events after every launch, on the launch stream)
@@ -160,8 +176,8 @@ def main():
             orc.forward(oc, blob4, batch4.ids[:sub_cu[-1]], sub_cu, 8)
             return time.perf_counter() - t0, int(sub_cu[-1])
 
-        probe, _ = run(8)                                      # calibrate, then time about 15 s of oracle work
-        n = int(min(B4, max(8, 8 * 15.0 / probe)))
+        probe, _ = run(8)                                      # calibrate, then time up to about 20 s of oracle work
+        n = int(min(B4, max(8, 8 * 20.0 / probe)))
         dt, ntok = run(n)
         cpu = {"value": n / dt, "unit": "sequences/s", "cores": cores, "kind": "oracle",
                "sample": f"first {n} sequences ({ntok} tokens) of the burst batch, all 8 students, fp32 build of the "
