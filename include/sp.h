@@ -54,6 +54,13 @@ typedef struct {
                          SP_DTYPE_BF16: bf16 weights and activations, fp32 accumulation,
                          LayerNorm statistics, softmax, GELU, pooling and logits */
     float ln_eps;     /* LayerNorm epsilon (BERT: 1e-12) */
+    int32_t last_layer_all_tokens;
+                      /* Only the first token of each sequence feeds the head, so after the last layer's
+                         key/value projections every other row is dead work.  0 (default): bf16 calls with
+                         >= 1024 tokens run the last layer's attention queries, output projection, FFN and
+                         LayerNorms on the first-token rows only (same results up to rounding order in
+                         attention).  1: every token goes through the whole last layer (what a stock BERT
+                         does; the fp32 path always does). */
 } sp_config;
 
 typedef struct sp_model sp_model; /* opaque host-side handle */

@@ -86,6 +86,15 @@ WsLayout make_ws_layout(const sp_config& c, int total_tokens, int batch)
     W.g = take(K * rows * F * ab);
     W.z = take(K * (size_t)batch * c.classes * 4);
     W.zpart = take(K * (size_t)(H / 64) * batch * c.classes * 4);
+    // compact buffers for the first-token rows of the last layer
+    const size_t crows = align_up((size_t)batch, kRowPad);
+    W.cx = take(K * crows * H * ab);
+    W.cq = take(K * crows * H * ab);
+    W.catt = take(K * crows * H * ab);
+    W.cu_ = take(K * crows * H * ab);
+    W.cx1 = take(K * crows * H * ab);
+    W.cg = take(K * crows * F * ab);
+    W.crows = (int)crows;
     W.end = o;
     W.rows = (int)rows;
     W.act_bytes = (int)ab;
@@ -217,8 +226,45 @@ static int run_forward(const sp_model* M, const int32_t* ids, const int32_t* cu,
     SP_MARK(-1);
     SP_TRY(launch_embed_ln(M, ids, cu, B, T, rows, mrows, k, x, att, s));
     SP_MARK(SP_PHASE_EMBED);
+    // Last layer on the first-token rows only (see sp_config.last_layer_all_tokens).  Not used by the partial
+    // forwards of the tests unless they stop before the last layer.
+    const bool first_only = c.dtype == SP_DTYPE_BF16 && !c.last_layer_all_tokens && with_head && T >= 1024 &&
+                            max_seqlen <= 512;
+    const int crows = W.crows;
+    const int ctile = B > 256 ? 256 : (B > 64 ? 128 : 64);
+    const int cmrows = (B + ctile - 1) / ctile * ctile;
+    void *cx = w + W.cx, *cq = w + W.cq, *catt = w + W.catt, *cu2 = w + W.cu_, *cx1 = w + W.cx1, *cg = w + W.cg;
+    const size_t cH = (size_t)crows * H * ab, cF = (size_t)crows * F * ab;
+    bool compact_final = false;
     for (int l = 0; l < stop_layers; ++l) {
         const size_t lo = L.layer0 + (size_t)l * L.layer_stride;
+        if (first_only && l == c.layers - 1) {
+            SP_TRY(launch_gather_first(M, x, cu, B, T, rows, cx, catt, crows, cmrows, k, s));
+            SP_MARK(SP_PHASE_EMBED);
+            // keys and values of every token (columns H..3H of the fused projection), queries of the first tokens
+            SP_TRY(launch_gemm(M, x, H, lo + L.wqkv + (size_t)H * H * ab, lo + L.bqkv + (size_t)H * 4, (char*)qkv + H * ab,
+                               3 * H, nullptr, 0, mrows, 2 * H, H, k, EPI_QKV, sH, s3H, 0, s, vt, H, rows, sH));
+            SP_TRY(launch_gemm(M, cx, H, lo + L.wqkv, lo + L.bqkv, cq, H, nullptr, 0, cmrows, H, H, k, EPI_BIAS, cH, cH, 0,
+                               s));
+            SP_MARK(SP_PHASE_QKV);
+            SP_TRY(launch_attention_first(M, cq, qkv, vt, catt, cu, B, T, max_seqlen, rows, crows, k, s));
+            SP_MARK(SP_PHASE_ATTENTION);
+            SP_TRY(launch_gemm(M, catt, H, lo + L.wo, lo + L.bo, cu2, H, cx, H, cmrows, H, H, k, EPI_BIAS_RESIDUAL, cH, cH,
+                               cH, s));
+            SP_MARK(SP_PHASE_OPROJ);
+            SP_TRY(launch_layernorm(M, cu2, cx1, crows, cmrows, k, lo + L.ln1g, lo + L.ln1b, s));
+            SP_MARK(SP_PHASE_LAYERNORM);
+            SP_TRY(launch_gemm(M, cx1, H, lo + L.w1, lo + L.b1, cg, F, nullptr, 0, cmrows, F, H, k, EPI_BIAS_GELU, cH, cF, 0,
+                               s));
+            SP_MARK(SP_PHASE_FFN_UP);
+            SP_TRY(launch_gemm(M, cg, F, lo + L.w2, lo + L.b2, cu2, H, cx1, H, cmrows, H, F, k, EPI_BIAS_RESIDUAL, cF, cH,
+                               cH, s));
+            SP_MARK(SP_PHASE_FFN_DOWN);
+            SP_TRY(launch_layernorm(M, cu2, cx, crows, cmrows, k, lo + L.ln2g, lo + L.ln2b, s));
+            SP_MARK(SP_PHASE_LAYERNORM);
+            compact_final = true;
+            continue;
+        }
         if (c.dtype == SP_DTYPE_BF16)
             SP_TRY(launch_gemm(M, x, H, lo + L.wqkv, lo + L.bqkv, qkv, 3 * H, nullptr, 0, mrows, 3 * H, H, k, EPI_QKV,
                                sH, s3H, 0, s, vt, 2 * H, rows, sH));
@@ -243,7 +289,10 @@ static int run_forward(const sp_model* M, const int32_t* ids, const int32_t* cu,
         SP_MARK(SP_PHASE_LAYERNORM);
     }
     if (with_head) {
-        SP_TRY(launch_head(M, x, cu, B, T, rows, k, z, (float*)(w + W.zpart), logits, s));
+        if (compact_final)
+            SP_TRY(launch_head(M, cx, nullptr, B, B, crows, k, z, (float*)(w + W.zpart), logits, s));
+        else
+            SP_TRY(launch_head(M, x, cu, B, T, rows, k, z, (float*)(w + W.zpart), logits, s));
         SP_MARK(SP_PHASE_HEAD);
     }
 #undef SP_MARK

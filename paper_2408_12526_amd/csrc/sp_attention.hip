@@ -319,6 +319,84 @@ __global__ __launch_bounds__(256, 3) void attention_bf16_short_kernel(const bf16
 }
 
 // -------------------------------------------------------------------------------------
+// Attention of one query per sequence (its first token), used when only the first-token rows of the last layer are
+// needed.  One wave per (student, sequence, head): lanes own keys for the scores and softmax, then head dimensions
+// for the weighted sum of the values (which are stored feature-major, so a lane walks contiguous tokens).
+// -------------------------------------------------------------------------------------
+constexpr int kFirstMaxKeysPerLane = 8;   // sequences of up to 512 tokens
+
+__global__ __launch_bounds__(256) void attention_first_kernel(const bf16* __restrict__ qc, const bf16* __restrict__ qkv,
+                                                              const bf16* __restrict__ vt, bf16* __restrict__ attc,
+                                                              const int32_t* __restrict__ cu, int B, int Tn, int rows,
+                                                              int crows, int H, int heads, int max_seqlen)
+{
+    __shared__ float sp_all[4][64 * kFirstMaxKeysPerLane];
+    const int m = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int item = blockIdx.x * 4 + wave;             // (sequence, head)
+    if (item >= B * heads) return;
+    const int b = item / heads, h = item % heads;
+    float* sp = sp_all[wave];
+    int t0 = cu[b], t1 = cu[b + 1];
+    t0 = t0 < 0 ? 0 : (t0 > Tn - 1 ? Tn - 1 : t0);
+    int L = t1 - t0;
+    L = L < 1 ? 1 : L;
+    L = L > max_seqlen ? max_seqlen : L;
+    L = L > Tn - t0 ? Tn - t0 : L;
+    L = L > 64 * kFirstMaxKeysPerLane ? 64 * kFirstMaxKeysPerLane : L;
+
+    float q[kD];
+    {
+        const bf16* qr = qc + ((size_t)m * crows + b) * H + h * kD;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            const bf16x8 t = *(const bf16x8*)(qr + c * 8);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) q[c * 8 + e] = (float)t[e];
+        }
+    }
+    const size_t ld = (size_t)3 * H;
+    const bf16* kbase = qkv + ((size_t)m * rows + t0) * ld + H + h * kD;
+    float sc[kFirstMaxKeysPerLane];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < kFirstMaxKeysPerLane; ++i) {
+        const int key = lane + 64 * i;
+        sc[i] = -INFINITY;
+        if (key < L) {
+            const bf16* kr = kbase + (size_t)key * ld;
+            float d = 0.f;
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                const bf16x8 t = *(const bf16x8*)(kr + c * 8);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) d = fmaf(q[c * 8 + e], (float)t[e], d);
+            }
+            sc[i] = d * (0.125f * 1.44269504088896341f);
+            mx = fmaxf(mx, sc[i]);
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < kFirstMaxKeysPerLane; ++i) {
+        const int key = lane + 64 * i;
+        const float p = key < L ? exp2f(sc[i] - mx) : 0.f;
+        sum += p;
+        if (key < L) sp[key] = p;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    // lane = head dimension: walk the sequence's tokens in the feature-major values
+    const bf16* vr = vt + ((size_t)m * H + h * kD + lane) * rows + t0;
+    float o = 0.f;
+    for (int key = 0; key < L; ++key) o = fmaf(sp[key], (float)vr[key], o);
+    attc[((size_t)m * crows + b) * H + h * kD + lane] = (bf16)(o / sum);
+}
+
+// -------------------------------------------------------------------------------------
 // fp32 kernel: one thread per query, keys streamed from global memory (all threads of a
 // workgroup read the same key row), online softmax in registers, exact division.
 // -------------------------------------------------------------------------------------
@@ -393,6 +471,19 @@ hipError_t launch_attention(const sp_model* M, const void* qkv, const void* vt, 
         hipLaunchKernelGGL(attention_f32_kernel, grid, dim3(64), 0, s, (const float*)qkv, (float*)att, cu, B, T, rows,
                            c.hidden, c.heads, max_seqlen, nqc);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_attention_first(const sp_model* M, const void* qc, const void* qkv, const void* vt, void* attc,
+                                  const int32_t* cu, int B, int T, int max_seqlen, int rows, int crows, int k,
+                                  hipStream_t s)
+{
+    const sp_config& c = M->cfg;
+    if (c.dtype != SP_DTYPE_BF16 || c.hidden / c.heads != kD || max_seqlen > 64 * kFirstMaxKeysPerLane)
+        return hipErrorInvalidValue;
+    dim3 grid((unsigned)((B * c.heads + 3) / 4), k);
+    hipLaunchKernelGGL(attention_first_kernel, grid, dim3(256), 0, s, (const bf16*)qc, (const bf16*)qkv, (const bf16*)vt,
+                       (bf16*)attc, cu, B, T, rows, crows, c.hidden, c.heads, max_seqlen);
     return hipGetLastError();
 }
 

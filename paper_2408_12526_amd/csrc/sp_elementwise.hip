@@ -145,6 +145,33 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const char* arena, size_
                     out + ((size_t)m * rows + row) * H);
 }
 
+// First-token rows: one wave per (student, sequence).
+template <typename T>
+__global__ __launch_bounds__(256) void gather_first_kernel(const T* __restrict__ x, const int32_t* __restrict__ cu, int B,
+                                                           int Tn, int rows, int H, T* __restrict__ xc,
+                                                           T* __restrict__ attc, int crows, int cmrows)
+{
+    const int m = blockIdx.y, lane = threadIdx.x & 63;
+    const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (b >= cmrows) return;
+    const int nch = H >> 3;
+    T* dst = xc + ((size_t)m * crows + b) * H;
+    if (b >= B) {                                  // padding rows of the compact tile: finite contents
+        const float zero8[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        T* arow = attc + ((size_t)m * crows + b) * H;
+        for (int c = lane; c < nch; c += 64) { store8(dst + c * 8, zero8); store8(arow + c * 8, zero8); }
+        return;
+    }
+    int r = cu[b];
+    r = r < 0 ? 0 : (r >= Tn ? Tn - 1 : r);
+    const T* src = x + ((size_t)m * rows + r) * H;
+    for (int c = lane; c < nch; c += 64) {
+        float v[8];
+        load8(src + c * 8, v);
+        store8(dst + c * 8, v);
+    }
+}
+
 // ---- head -------------------------------------------------------------------------
 // Stage 1: one workgroup = (group of kSeqPerWg sequences, student, slice of 64 pooler outputs).
 // pooled[n] = tanh(bp[n] + sum_i cls[i] Wp[i][n]); the slice's share of the classifier,
@@ -164,7 +191,7 @@ __global__ __launch_bounds__(256) void head_pool_kernel(const char* arena, size_
     const int tid = threadIdx.x, lane = tid & 63, part = tid >> 6;
     const int nseq = (B - b0) < kSeqPerWg ? (B - b0) : kSeqPerWg;
     for (int s = 0; s < nseq; ++s) {
-        int r = cu[b0 + s];
+        int r = cu ? cu[b0 + s] : b0 + s;    // packed layout: first token of the sequence; compact layout: row b
         r = r < 0 ? 0 : (r >= Tn ? Tn - 1 : r);
         const T* src = x + ((size_t)m * rows + r) * H;
         for (int i = tid; i < H; i += 256) xs[s * H + i] = (float)src[i];
@@ -253,6 +280,20 @@ hipError_t launch_layernorm(const sp_model* M, const void* u, void* out, int row
     else
         hipLaunchKernelGGL(layernorm_kernel<float>, grid, dim3(256), 0, s, M->arena, M->L.student_stride, g_off, b_off,
                            (const float*)u, (float*)out, rows, mrows, c.hidden, c.ln_eps);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_first(const sp_model* M, const void* x, const int32_t* cu, int B, int T, int rows, void* xc,
+                               void* attc, int crows, int cmrows, int k, hipStream_t s)
+{
+    const sp_config& c = M->cfg;
+    dim3 grid((cmrows + 3) / 4, k);
+    if (c.dtype == SP_DTYPE_BF16)
+        hipLaunchKernelGGL(gather_first_kernel<bf16>, grid, dim3(256), 0, s, (const bf16*)x, cu, B, T, rows, c.hidden,
+                           (bf16*)xc, (bf16*)attc, crows, cmrows);
+    else
+        hipLaunchKernelGGL(gather_first_kernel<float>, grid, dim3(256), 0, s, (const float*)x, cu, B, T, rows, c.hidden,
+                           (float*)xc, (float*)attc, crows, cmrows);
     return hipGetLastError();
 }
 

@@ -36,7 +36,8 @@ ArenaLayout make_arena_layout(const sp_config& c);
 // Workspace carve-up for one call.
 struct WsLayout {
     size_t x, qkv, vt, att, u, x1, g, z, zpart, end;
-    int rows;
+    size_t cx, cq, catt, cu_, cx1, cg;   // first-token rows only: [K][crows][H] (cg: [F]), last layer
+    int rows, crows;
     int act_bytes;
 };
 WsLayout make_ws_layout(const sp_config& c, int total_tokens, int batch);
@@ -79,7 +80,18 @@ hipError_t launch_gemm(const sp_model* M, const void* A, int lda, size_t w_off, 
 hipError_t launch_attention(const sp_model* M, const void* qkv, const void* vt, void* att, const int32_t* cu, int B,
                             int T, int max_seqlen, int rows, int k, hipStream_t s);
 
-// z[m][b][c] = tanh(x[m][cu[b]] Wp + bp) Wc + bc ; logits[b][c] = sum_{m<k} z[m][b][c] (m ascending).
+// First-token rows of every sequence: xc[m][b][:] = x[m][cu[b]][:] (b < B), zero rows up to cmrows; the same
+// rows of attc are zeroed.
+hipError_t launch_gather_first(const sp_model* M, const void* x, const int32_t* cu, int B, int T, int rows, void* xc,
+                               void* attc, int crows, int cmrows, int k, hipStream_t s);
+
+// Attention of the first token of each sequence only: attc[m][b][h*64..] = softmax(qc[m][b] k^T / 8) v, keys and
+// values of sequence b taken from qkv (key slice) and vt.
+hipError_t launch_attention_first(const sp_model* M, const void* qc, const void* qkv, const void* vt, void* attc,
+                                  const int32_t* cu, int B, int T, int max_seqlen, int rows, int crows, int k,
+                                  hipStream_t s);
+
+// z[m][b][c] = tanh(x[m][cu[b]] Wp + bp) Wc + bc (row b itself if cu is null) ; logits[b][c] = sum_{m<k} z[m][b][c] (m ascending).
 hipError_t launch_head(const sp_model* M, const void* x, const int32_t* cu, int B, int T, int rows, int k, float* z,
                        float* zpart, float* logits, hipStream_t s);
 

@@ -142,6 +142,26 @@ def test_small_shape_end_to_end(sp, oracle64, dtype):
         check_logits(got, want, shape, f"small shape {dtype} k_active={k}")
 
 
+def test_first_token_last_layer_matches_all_tokens(sp, oracle64):
+    """Calls with >= 1024 tokens run the last layer on the first-token rows only; a stock all-token last layer must
+    give the same logits (up to attention's rounding order), and both must match the oracle."""
+    shape = STAGE_SHAPES["bf16"]
+    rng = np.random.default_rng(23)
+    lengths = rng.integers(1, 130, size=37).astype(np.int32)
+    lengths[:3] = (200, 1, 129)
+    assert lengths.sum() >= 1024
+    ids = synth.make_ids(rng, int(lengths.sum()), shape.vocab)
+    blob = synth.make_weights(rng, shape, std=0.05, ln_random=True, qk_std=0.12)
+    d_ids, d_cu, cu = gpu_inputs(lengths, ids, sp)
+    want = oracle64.forward(ocfg(shape), oracle_weights(blob, shape), ids, cu, shape.K)
+    got = {}
+    for all_tokens in (False, True):
+        st = sp.Students(sp.config_from_shape(shape, last_layer_all_tokens=all_tokens), blob)
+        got[all_tokens] = st.sp_forward(d_ids, d_cu, int(lengths.max()), shape.K).cpu().numpy().astype(np.float64)
+        check_logits(got[all_tokens], want, shape, f"all_tokens={all_tokens}")
+    assert rel_err(got[False], got[True]) < 1e-2
+
+
 # ---- the five workloads ----------------------------------------------------------------------------
 
 _cache = {}
