@@ -27,7 +27,7 @@ static bool config_ok(const sp_config* c)
 static bool config_supported(const sp_config& c)
 {
     if (c.hidden % c.heads || c.hidden / c.heads != 64) return false;
-    if (c.classes > 16 || c.hidden > 1024) return false;
+    if (c.classes > 16 || c.hidden > 1024 || c.K > 64) return false;
     if (c.hidden % 128 || c.ffn % 128) return false;   // reduction depth of every projection: whole 64-wide k-tiles, at least two
     return true;
 }
@@ -62,6 +62,7 @@ ArenaLayout make_arena_layout(const sp_config& c)
         o = base + L.layer_stride * (size_t)c.layers;
     }
     L.wp = take(H * H * wb);
+    L.wp_t = take(H * H * wb);
     L.bp = take(H * 4);
     L.wc = take(C * H * wb);
     L.bc = take(C * 4);
@@ -174,7 +175,8 @@ static void fill_student(const sp_config& c, const ArenaLayout& L, const float* 
         memcpy(lb + L.ln2g, p, H * 4); p += H;
         memcpy(lb + L.ln2b, p, H * 4); p += H;
     }
-    w.copy(dst + L.wp, p, H * H); p += H * H;
+    w.copy(dst + L.wp, p, H * H);
+    w.transpose(dst + L.wp_t, p, H, H); p += H * H;
     memcpy(dst + L.bp, p, H * 4); p += H;
     w.copy(dst + L.wc, p, H * C); p += H * C;
     memcpy(dst + L.bc, p, C * 4); p += C;
@@ -289,9 +291,11 @@ static int run_forward(const sp_model* M, const int32_t* ids, const int32_t* cu,
         SP_MARK(SP_PHASE_LAYERNORM);
     }
     if (with_head) {
-        if (compact_final)
-            SP_TRY(launch_head(M, cx, nullptr, B, B, crows, k, z, (float*)(w + W.zpart), logits, s));
-        else
+        if (compact_final) {
+            // pooler as one more student-grouped projection (tanh epilogue) on the first-token rows, then the classifier
+            SP_TRY(launch_gemm(M, cx, H, L.wp_t, L.bp, cq, H, nullptr, 0, cmrows, H, H, k, EPI_BIAS_TANH, cH, cH, 0, s));
+            SP_TRY(launch_head_classify(M, cq, B, crows, k, z, logits, s));
+        } else
             SP_TRY(launch_head(M, x, cu, B, T, rows, k, z, (float*)(w + W.zpart), logits, s));
         SP_MARK(SP_PHASE_HEAD);
     }

@@ -391,8 +391,17 @@ __global__ __launch_bounds__(256) void attention_first_kernel(const bf16* __rest
     __builtin_amdgcn_wave_barrier();
     // lane = head dimension: walk the sequence's tokens in the feature-major values
     const bf16* vr = vt + ((size_t)m * H + h * kD + lane) * rows + t0;
-    float o = 0.f;
-    for (int key = 0; key < L; ++key) o = fmaf(sp[key], (float)vr[key], o);
+    float o4[4] = {0.f, 0.f, 0.f, 0.f};             // four independent chains, sixteen loads in flight
+    int key = 0;
+    for (; key + 16 <= L; key += 16) {
+        float v[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) v[e] = (float)vr[key + e];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o4[e & 3] = fmaf(sp[key + e], v[e], o4[e & 3]);
+    }
+    for (; key < L; ++key) o4[0] = fmaf(sp[key], (float)vr[key], o4[0]);
+    const float o = (o4[0] + o4[1]) + (o4[2] + o4[3]);
     attc[((size_t)m * crows + b) * H + h * kD + lane] = (bf16)(o / sum);
 }
 
@@ -450,9 +459,11 @@ hipError_t launch_attention(const sp_model* M, const void* qkv, const void* vt, 
     const sp_config& c = M->cfg;
     if (c.hidden / c.heads != kD) return hipErrorInvalidValue;
     if (c.dtype == SP_DTYPE_BF16) {
-        // sequences of up to kShortLen tokens: one wave per (sequence, head); longer ones: one workgroup per
-        // (sequence, head, 128 queries) sharing the key/value tiles.  Each kernel skips the other's sequences.
-        constexpr int kShortLen = 128;
+        // Short sequences: one wave per (sequence, head); long ones: one workgroup per (sequence, head, 128 queries)
+        // sharing the key/value tiles.  Each kernel skips the other's sequences.  When nothing in the call is longer
+        // than 256 tokens the per-wave kernel takes everything (the few long sequences of a serving batch re-read
+        // their keys per 32 queries from L2, which costs less than a second, mostly idle launch).
+        const int kShortLen = max_seqlen <= 256 ? 256 : 128;
         const int ngroups = (c.heads + 3) / 4;
         hipLaunchKernelGGL(attention_bf16_short_kernel, dim3((unsigned)(B * ngroups), k), dim3(256), 0, s,
                            (const bf16*)qkv, (const bf16*)vt, (bf16*)att, cu, B, T, rows, c.hidden, c.heads, max_seqlen,

@@ -252,7 +252,46 @@ __global__ void head_sum_kernel(const char* arena, size_t student_stride, size_t
     logits[idx] = total;
 }
 
+// Classifier on pooled rows and the cross-student sum: one workgroup per sequence, wave w takes students w, w + 4, ...
+template <typename T>
+__global__ __launch_bounds__(256) void head_classify_kernel(const char* arena, size_t student_stride, size_t wc_off,
+                                                            size_t bc_off, const T* __restrict__ pooled, int B, int crows,
+                                                            int H, int C, int k, float* __restrict__ z,
+                                                            float* __restrict__ logits)
+{
+    __shared__ float zs[64][16];                 // [student][class]
+    const int b = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int m = wave; m < k; m += 4) {
+        const char* sb = arena + (size_t)m * student_stride;
+        const T* Wc = (const T*)(sb + wc_off);
+        const float* bc = (const float*)(sb + bc_off);
+        const T* p = pooled + ((size_t)m * crows + b) * H;
+        for (int c = 0; c < C; ++c) {
+            float acc = 0.f;
+            for (int n = lane; n < H; n += 64) acc += (float)p[n] * (float)Wc[(size_t)n * C + c];
+            acc = wave_sum(acc);
+            if (lane == 0) { const float v = acc + bc[c]; zs[m][c] = v; z[((size_t)m * B + b) * C + c] = v; }
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x < C) {
+        float total = 0.f;
+        for (int m = 0; m < k; ++m) total += zs[m][threadIdx.x];   // students in training order
+        logits[(size_t)b * C + threadIdx.x] = total;
+    }
+}
+
 }  // namespace
+
+hipError_t launch_head_classify(const sp_model* M, const void* pooled, int B, int crows, int k, float* z, float* logits,
+                                hipStream_t s)
+{
+    const sp_config& c = M->cfg;
+    if (c.dtype != SP_DTYPE_BF16 || k > 64) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(head_classify_kernel<bf16>, dim3(B), dim3(256), 0, s, M->arena, M->L.student_stride, M->L.wc,
+                       M->L.bc, (const bf16*)pooled, B, crows, c.hidden, c.classes, k, z, logits);
+    return hipGetLastError();
+}
 
 hipError_t launch_embed_ln(const sp_model* M, const int32_t* ids, const int32_t* cu, int B, int T, int rows, int mrows,
                            int k, void* x, void* att, hipStream_t s)

@@ -235,6 +235,10 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
 #pragma unroll
                     for (int e = 0; e < 4; ++e) r[e] = gelu_erf_fast(r[e]);
                 }
+                if (EPI == EPI_BIAS_TANH) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) r[e] = tanhf(r[e]);
+                }
                 if (EPI == EPI_BIAS_RESIDUAL) {
                     const bf16x4 x4 = *(const bf16x4*)cell;
 #pragma unroll
@@ -382,9 +386,11 @@ hipError_t launch_gemm(const sp_model* M, const void* A, int lda, size_t w_off, 
             case EPI_BIAS: return launch_bf16<EPI_BIAS>(SP_ARGS, nullptr, 0, 0, 0);
             case EPI_BIAS_GELU: return launch_bf16<EPI_BIAS_GELU>(SP_ARGS, nullptr, 0, 0, 0);
             case EPI_QKV: return launch_bf16<EPI_QKV>(SP_ARGS, out2, n_split, ld2, o2_student_stride);
+            case EPI_BIAS_TANH: return launch_bf16<EPI_BIAS_TANH>(SP_ARGS, nullptr, 0, 0, 0);
             default: return launch_bf16<EPI_BIAS_RESIDUAL>(SP_ARGS, nullptr, 0, 0, 0);
         }
     }
+    if (epi == EPI_QKV || epi == EPI_BIAS_TANH) return hipErrorInvalidValue;   // bf16 path only
     switch (epi) {
         case EPI_BIAS: return launch_f32<EPI_BIAS>(SP_ARGS);
         case EPI_BIAS_GELU: return launch_f32<EPI_BIAS_GELU>(SP_ARGS);

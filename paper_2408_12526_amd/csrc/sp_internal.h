@@ -27,7 +27,7 @@ struct ArenaLayout {
     size_t layer0, layer_stride;
     // relative to the start of a layer
     size_t wqkv, bqkv, wo, bo, ln1g, ln1b, w1, b1, w2, b2, ln2g, ln2b;
-    size_t wp, bp, wc, bc;
+    size_t wp, wp_t, bp, wc, bc;   // wp: [in][out] (column-parallel head kernel); wp_t: [out][in] (GEMM operand)
     size_t student_stride;
 };
 
@@ -65,7 +65,7 @@ hipError_t launch_layernorm(const sp_model* M, const void* u, void* out, int row
 
 // EPI_QKV (bf16 path only): bias; output columns >= n_split (the value projection) are written transposed,
 // out2[m][column - n_split][row], so that attention reads key-contiguous value tiles.
-enum Epilogue { EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_BIAS_RESIDUAL = 2, EPI_QKV = 3 };
+enum Epilogue { EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_BIAS_RESIDUAL = 2, EPI_QKV = 3, EPI_BIAS_TANH = 4 };
 
 // out[m][row][0..N) = epi(A[m][row][0..Kd) . W^T + bias), W stored [N][Kd] at w_off of each student.
 // lda / ldo / ldr are row strides in elements; residual may be null unless EPI_BIAS_RESIDUAL;
@@ -90,6 +90,10 @@ hipError_t launch_gather_first(const sp_model* M, const void* x, const int32_t* 
 hipError_t launch_attention_first(const sp_model* M, const void* qc, const void* qkv, const void* vt, void* attc,
                                   const int32_t* cu, int B, int T, int max_seqlen, int rows, int crows, int k,
                                   hipStream_t s);
+
+// Head on pooled rows: z[m][b][c] = pooled[m][b] . Wc + bc; logits[b][c] = sum_{m<k} z[m][b][c] (m ascending).
+hipError_t launch_head_classify(const sp_model* M, const void* pooled, int B, int crows, int k, float* z, float* logits,
+                                hipStream_t s);
 
 // z[m][b][c] = tanh(x[m][cu[b]] Wp + bp) Wc + bc (row b itself if cu is null) ; logits[b][c] = sum_{m<k} z[m][b][c] (m ascending).
 hipError_t launch_head(const sp_model* M, const void* x, const int32_t* cu, int B, int T, int rows, int k, float* z,

@@ -52,9 +52,9 @@ def gpu_inputs(lengths, ids, sp):
 # ---- kernel-by-kernel on small shapes ---------------------------------------------------------
 
 STAGE_SHAPES = {
-    "fp32": synth.StudentShape(K=2, layers=2, hidden=128, heads=2, ffn=256, vocab=100, max_pos=200, classes=3,
+    "fp32": synth.StudentShape(K=2, layers=2, hidden=128, heads=2, ffn=256, vocab=100, max_pos=320, classes=3,
                                dtype="fp32"),
-    "bf16": synth.StudentShape(K=3, layers=2, hidden=128, heads=2, ffn=256, vocab=100, max_pos=200, classes=3,
+    "bf16": synth.StudentShape(K=3, layers=2, hidden=128, heads=2, ffn=256, vocab=100, max_pos=320, classes=3,
                                dtype="bf16"),
 }
 STAGE_LENGTHS = (5, 1, 96, 33, 64, 200, 70, 129)   # spans several key tiles, query blocks and a ragged tail
@@ -62,7 +62,8 @@ SINGLE_TILE_LENGTHS = (7, 1, 30, 19)                # 57 tokens: the single-tile
 
 
 @pytest.mark.parametrize("dtype,lens", [("fp32", STAGE_LENGTHS), ("bf16", STAGE_LENGTHS),
-                                        ("bf16", SINGLE_TILE_LENGTHS), ("bf16", (64,))])
+                                        ("bf16", SINGLE_TILE_LENGTHS), ("bf16", (64,)),
+                                        ("bf16", (300, 5, 140, 64, 257))])   # > 256 tokens: the key/value-sharing kernel
 def test_every_stage_against_oracle_pieces(sp, oracle64, dtype, lens):
     """Each kernel in isolation: its output against the oracle's piece applied to the kernel's own input
     (as the HIP path left it in the workspace), so that one kernel's rounding is not charged to the next."""
