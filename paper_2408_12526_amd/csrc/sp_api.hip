@@ -244,12 +244,13 @@ static int run_forward(const sp_model* M, const int32_t* ids, const int32_t* cu,
             SP_TRY(launch_gather_first(M, x, cu, B, T, rows, cx, catt, crows, cmrows, k, s));
             SP_MARK(SP_PHASE_EMBED);
             // keys and values of every token (columns H..3H of the fused projection), queries of the first tokens
+            // (row-major values: the one-query attention kernel below reads whole value rows)
             SP_TRY(launch_gemm(M, x, H, lo + L.wqkv + (size_t)H * H * ab, lo + L.bqkv + (size_t)H * 4, (char*)qkv + H * ab,
-                               3 * H, nullptr, 0, mrows, 2 * H, H, k, EPI_QKV, sH, s3H, 0, s, vt, H, rows, sH));
+                               3 * H, nullptr, 0, mrows, 2 * H, H, k, EPI_BIAS, sH, s3H, 0, s));
             SP_TRY(launch_gemm(M, cx, H, lo + L.wqkv, lo + L.bqkv, cq, H, nullptr, 0, cmrows, H, H, k, EPI_BIAS, cH, cH, 0,
                                s));
             SP_MARK(SP_PHASE_QKV);
-            SP_TRY(launch_attention_first(M, cq, qkv, vt, catt, cu, B, T, max_seqlen, rows, crows, k, s));
+            SP_TRY(launch_attention_first(M, cq, qkv, catt, cu, B, T, max_seqlen, rows, crows, k, s));
             SP_MARK(SP_PHASE_ATTENTION);
             SP_TRY(launch_gemm(M, catt, H, lo + L.wo, lo + L.bo, cu2, H, cx, H, cmrows, H, H, k, EPI_BIAS_RESIDUAL, cH, cH,
                                cH, s));

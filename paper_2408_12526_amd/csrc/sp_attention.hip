@@ -321,12 +321,12 @@ __global__ __launch_bounds__(256, 3) void attention_bf16_short_kernel(const bf16
 // -------------------------------------------------------------------------------------
 // Attention of one query per sequence (its first token), used when only the first-token rows of the last layer are
 // needed.  One wave per (student, sequence, head): lanes own keys for the scores and softmax, then head dimensions
-// for the weighted sum of the values (which are stored feature-major, so a lane walks contiguous tokens).
+// for the weighted sum of the values (row-major here: the 64 lanes read one 128-byte row per key).
 // -------------------------------------------------------------------------------------
 constexpr int kFirstMaxKeysPerLane = 8;   // sequences of up to 512 tokens
 
 __global__ __launch_bounds__(256) void attention_first_kernel(const bf16* __restrict__ qc, const bf16* __restrict__ qkv,
-                                                              const bf16* __restrict__ vt, bf16* __restrict__ attc,
+                                                              bf16* __restrict__ attc,
                                                               const int32_t* __restrict__ cu, int B, int Tn, int rows,
                                                               int crows, int H, int heads, int max_seqlen)
 {
@@ -389,18 +389,18 @@ __global__ __launch_bounds__(256) void attention_first_kernel(const bf16* __rest
     for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    // lane = head dimension: walk the sequence's tokens in the feature-major values
-    const bf16* vr = vt + ((size_t)m * H + h * kD + lane) * rows + t0;
+    // lane = head dimension; the value rows sit next to the key rows
+    const bf16* vr = kbase + H + lane;
     float o4[4] = {0.f, 0.f, 0.f, 0.f};             // four independent chains, sixteen loads in flight
     int key = 0;
     for (; key + 16 <= L; key += 16) {
         float v[16];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) v[e] = (float)vr[key + e];
+        for (int e = 0; e < 16; ++e) v[e] = (float)vr[(size_t)(key + e) * ld];
 #pragma unroll
         for (int e = 0; e < 16; ++e) o4[e & 3] = fmaf(sp[key + e], v[e], o4[e & 3]);
     }
-    for (; key < L; ++key) o4[0] = fmaf(sp[key], (float)vr[key], o4[0]);
+    for (; key < L; ++key) o4[0] = fmaf(sp[key], (float)vr[(size_t)key * ld], o4[0]);
     const float o = (o4[0] + o4[1]) + (o4[2] + o4[3]);
     attc[((size_t)m * crows + b) * H + h * kD + lane] = (bf16)(o / sum);
 }
@@ -459,11 +459,11 @@ hipError_t launch_attention(const sp_model* M, const void* qkv, const void* vt, 
     const sp_config& c = M->cfg;
     if (c.hidden / c.heads != kD) return hipErrorInvalidValue;
     if (c.dtype == SP_DTYPE_BF16) {
-        // Short sequences: one wave per (sequence, head); long ones: one workgroup per (sequence, head, 128 queries)
-        // sharing the key/value tiles.  Each kernel skips the other's sequences.  When nothing in the call is longer
-        // than 256 tokens the per-wave kernel takes everything (the few long sequences of a serving batch re-read
-        // their keys per 32 queries from L2, which costs less than a second, mostly idle launch).
-        const int kShortLen = max_seqlen <= 256 ? 256 : 128;
+        // Sequences of up to 128 tokens: one wave per (sequence, head); longer ones: one workgroup per (sequence,
+        // head, 128 queries) sharing the key/value tiles.  Each kernel skips the other's sequences.  (Giving the long
+        // sequences of a serving batch to the per-wave kernel as well was measured slower: a 256-token sequence is 72
+        // tile iterations in one wave, a long tail behind the ~5 of a typical one.)
+        const int kShortLen = 128;
         const int ngroups = (c.heads + 3) / 4;
         hipLaunchKernelGGL(attention_bf16_short_kernel, dim3((unsigned)(B * ngroups), k), dim3(256), 0, s,
                            (const bf16*)qkv, (const bf16*)vt, (bf16*)att, cu, B, T, rows, c.hidden, c.heads, max_seqlen,
@@ -485,7 +485,7 @@ hipError_t launch_attention(const sp_model* M, const void* qkv, const void* vt, 
     return hipGetLastError();
 }
 
-hipError_t launch_attention_first(const sp_model* M, const void* qc, const void* qkv, const void* vt, void* attc,
+hipError_t launch_attention_first(const sp_model* M, const void* qc, const void* qkv, void* attc,
                                   const int32_t* cu, int B, int T, int max_seqlen, int rows, int crows, int k,
                                   hipStream_t s)
 {
@@ -493,8 +493,7 @@ hipError_t launch_attention_first(const sp_model* M, const void* qc, const void*
     if (c.dtype != SP_DTYPE_BF16 || c.hidden / c.heads != kD || max_seqlen > 64 * kFirstMaxKeysPerLane)
         return hipErrorInvalidValue;
     dim3 grid((unsigned)((B * c.heads + 3) / 4), k);
-    hipLaunchKernelGGL(attention_first_kernel, grid, dim3(256), 0, s, (const bf16*)qc, (const bf16*)qkv, (const bf16*)vt,
-                       (bf16*)attc, cu, B, T, rows, crows, c.hidden, c.heads, max_seqlen);
+    hipLaunchKernelGGL(attention_first_kernel, grid, dim3(256), 0, s, (const bf16*)qc, (const bf16*)qkv, (bf16*)attc, cu, B, T, rows, crows, c.hidden, c.heads, max_seqlen);
     return hipGetLastError();
 }
 

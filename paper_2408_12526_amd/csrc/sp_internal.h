@@ -86,8 +86,8 @@ hipError_t launch_gather_first(const sp_model* M, const void* x, const int32_t* 
                                void* attc, int crows, int cmrows, int k, hipStream_t s);
 
 // Attention of the first token of each sequence only: attc[m][b][h*64..] = softmax(qc[m][b] k^T / 8) v, keys and
-// values of sequence b taken from qkv (key slice) and vt.
-hipError_t launch_attention_first(const sp_model* M, const void* qc, const void* qkv, const void* vt, void* attc,
+// values of sequence b taken from the key and value slices of qkv (row-major).
+hipError_t launch_attention_first(const sp_model* M, const void* qc, const void* qkv, void* attc,
                                   const int32_t* cu, int B, int T, int max_seqlen, int rows, int crows, int k,
                                   hipStream_t s);
 
