@@ -49,8 +49,12 @@ __device__ inline float gelu_erf_fast(float x)
 //     two k-steps (a burst of loads stalls the issuing wave behind the address unit's queue), and the
 //     fragments of k-step s + 1 are read while step s multiplies.  One barrier per 64-wide k-tile, placed where
 //     every wave already holds its last fragments of the tile in registers.
-//   * epilogue through LDS: each wave stages its sub-tile (and the residual rows it needs) in its own slice of
-//     the ring, so that global reads and writes are whole 16-byte-per-lane row segments.
+//   * epilogue through LDS: each wave stages its sub-tile in its own slice of the ring, so that global writes are
+//     whole 16-byte-per-lane row segments.  Staged rows are unpadded and their 16-byte chunks XOR-swizzled by row,
+//     which lets the residual rows arrive by the same direct-to-LDS loads: half of them are requested before the
+//     last k-tile (into the ring stage that is already idle), the rest while the first half is being processed.
+//   * the accumulators start from the bias values, which are the first loads of the kernel (sixteen dependent
+//     global loads in the epilogue cost several microseconds per tile, and so the adds disappear as well).
 // -------------------------------------------------------------------------------------
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) const void gbl_void;
@@ -58,14 +62,25 @@ typedef __attribute__((address_space(1))) const void gbl_void;
 template <int N>
 __device__ inline void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
+// Workgroup barrier that waits for this wave's LDS traffic only.  (__syncthreads() also waits for every
+// outstanding global load, which would serialise the loads that are deliberately left in flight across it.)
+__device__ inline void barrier_lds()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 template <int BM, int BN>
 struct GemmTile {
     static constexpr int BK = 64, NS = 2, STEPS = 4, LSPREAD = 2;
     static constexpr int WTM = BM / 2, WTN = BN / 2;        // wave tile
-    static constexpr int PITCH = WTN * 2 + 16;              // bytes per staged epilogue row
     static constexpr size_t ring_bytes = (size_t)NS * (BM + BN) * 8 * 16;
-    static constexpr size_t stage_bytes = (size_t)4 * WTM * PITCH;
-    static constexpr size_t smem_bytes = ring_bytes > stage_bytes ? ring_bytes : stage_bytes;
+    // epilogue staging: wave w keeps rows [h * WTM / 2, (h + 1) * WTM / 2) of its sub-tile, WTN * 2 bytes each, in
+    // one half of the ring (= one stage)
+    static constexpr size_t half_bytes = ring_bytes / 2;
+    static_assert(NS == 2 && (size_t)4 * (WTM / 2) * WTN * 2 <= half_bytes, "staging halves must fit the ring stages");
+    static constexpr size_t smem_bytes = ring_bytes;
 };
 
 template <int BM, int BN, int EPI>
@@ -113,15 +128,52 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
                                              16, 0, 0);
     };
 
-    f32x16 acc[TN][TM];
-#pragma unroll
-    for (int i = 0; i < TN; ++i)
-#pragma unroll
-        for (int j = 0; j < TM; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
+    // The lane's bias values, as the oldest loads in flight: the accumulators start from them.
     const int j31 = lane & 31, g = lane >> 5;
+    f32x4 b4[TN][4];
+    {
+        const float* bias = (const float*)(arena + (size_t)m * student_stride + b_off) + n0 + wn * G::WTN + 4 * g;
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) b4[i][v4] = *(const f32x4*)(bias + i * 32 + 8 * v4);
+    }
+
+    // Epilogue staging geometry (used early by the residual prefetch).
+    constexpr int WTM = G::WTM, WTN = G::WTN;
+    constexpr int ROWB = WTN * 2;                           // bytes per staged row
+    constexpr int CPR = WTN / 8;                            // 16-byte chunks per staged row
+    constexpr int RPI = 64 / CPR;                           // rows per row-wise instruction
+    constexpr int KSH = CPR == 16 ? 0 : (CPR == 8 ? 1 : 2); // rows that share a swizzle key: 256 bytes of LDS
+    constexpr int HR = WTM / 2;                             // rows per staging half
+    const int rr = lane / CPR, cc = lane % CPR;
+    const size_t row0 = (size_t)m0 + wm * WTM;
+    const int col0 = n0 + wn * WTN;
+    const int ha = (Kd / BK) & 1;                           // the ring stage that is idle during the last k-tile
+    auto half_ptr = [&](int h) { return (char*)smem + (size_t)(h ^ ha) * G::half_bytes + (size_t)wave * HR * ROWB; };
+    auto swz = [](int r, int chunk) { return chunk ^ ((r >> KSH) & (CPR - 1)); };
+    // Row-wise instructions (residual loads, output stores) move RPI whole staged rows each; the swizzle repeats
+    // every 16 rows, so NQ per-lane offsets serve every 16-row period and the rest of the address is uniform.
+    constexpr int NQ = 16 / RPI;
+    unsigned soff[NQ], xch[NQ];                             // LDS byte offset inside a period; swizzled chunk
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        xch[q] = (unsigned)swz(q * RPI + rr, cc);
+        soff[q] = (unsigned)((q * RPI + rr) * ROWB) + (xch[q] << 4);
+    }
+    // residual rows of staging half h -> LDS (asynchronous; this wave's own slice)
+    auto issue_residual = [&](int h) {
+        const char* rb = (const char*)(res + (size_t)m * r_ss + (row0 + (size_t)h * HR) * ldr + col0);
+        char* base = half_ptr(h);
+#pragma unroll
+        for (int pr = 0; pr < HR / 16; ++pr)
+#pragma unroll
+            for (int q = 0; q < NQ; ++q)
+                __builtin_amdgcn_global_load_lds(
+                    (gbl_void*)(rb + (size_t)pr * 32 * ldr + (unsigned)((q * RPI + rr) * ldr * 2 + (xch[q] << 4))),
+                    (lds_void*)(base + (pr * 16 + q * RPI) * ROWB), 16, 0, 0);
+    };
+
     int woff[TN], xoff[TM], wkey[TN], xkey[TM];
 #pragma unroll
     for (int i = 0; i < TN; ++i) { const int r = wn * G::WTN + i * 32 + j31; woff[i] = BM * 8 + r * 8; wkey[i] = (r >> 1) & 7; }
@@ -135,8 +187,15 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
         if (t < nk)
 #pragma unroll
             for (int i = 0; i < LPW; ++i) issue1(i, t * BK, t);
+    f32x16 acc[TN][TM];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = b4[i][e >> 2][e & 3];
     if (nk >= NS) wait_vmcnt<(NS - 1) * LPW>(); else wait_vmcnt<0>();
-    __syncthreads();
+    barrier_lds();
 #pragma unroll
     for (int i = 0; i < TN; ++i) fw[0][i] = __builtin_bit_cast(bf16x8, smem[woff[i] + (g ^ wkey[i])]);
 #pragma unroll
@@ -153,9 +212,9 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
             if (s == STEPS - 1) {
                 // every wave holds (or has requested) its last fragments of k-tile j: after the barrier nobody reads
                 // this stage any more, and k-tile j + 1 (waited for here) is visible to all
-                if (STEADY || j + NS <= nk) wait_vmcnt<(NS - 2) * LPW>(); else wait_vmcnt<0>();
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                __syncthreads();
+                // (the last k-tile has no successor to wait for; residual rows may be in flight there)
+                if (STEADY || j + NS <= nk) wait_vmcnt<(NS - 2) * LPW>(); else if (j + 1 < nk) wait_vmcnt<0>();
+                barrier_lds();
             }
             __builtin_amdgcn_sched_barrier(0);
             // refill: k-tile j + NS -> this stage (from the last step on), k-tile j - 1 + NS -> previous stage
@@ -197,72 +256,98 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
     int jt = 0;
     ktile(jt++, std::false_type{});
     for (; jt < nk - NS; ++jt) ktile(jt, std::true_type{});
-    for (; jt < nk; ++jt) ktile(jt, std::false_type{});
+    for (; jt < nk; ++jt) {
+        // from here on the stage of k-tile nk - 2 is read by nobody: the first half of the residual rows goes there
+        if (EPI == EPI_BIAS_RESIDUAL && jt == nk - 1) issue_residual(0);
+        ktile(jt, std::false_type{});
+    }
 
     // ---- epilogue.  Accumulator element v of lane l in block (i, j): token = l % 32,
     // feature = 8 * (v / 4) + 4 * (l / 32) + v % 4 inside the 32x32 block.
-    constexpr int WTM = G::WTM, WTN = G::WTN, PITCH = G::PITCH;
-    constexpr int CPR = WTN / 8;                            // 16-byte chunks per staged row
-    constexpr int RPI = 64 / CPR;                           // rows per row-wise instruction
-    __syncthreads();                                        // all fragment reads are done: the ring is free
-    char* stg = (char*)smem + (size_t)wave * WTM * PITCH;   // this wave's private staging slice
-    const int rr = lane / CPR, cc = lane % CPR;
-    const size_t row0 = (size_t)m0 + wm * WTM;
-    const int col0 = n0 + wn * WTN;
-    if (EPI == EPI_BIAS_RESIDUAL) {                         // residual rows -> staging, whole row segments
-        const bf16* rsrc = res + (size_t)m * r_ss + row0 * ldr + col0 + cc * 8;
-#pragma unroll 4
-        for (int r0 = 0; r0 < WTM; r0 += RPI)
-            *(uint4*)(stg + (r0 + rr) * PITCH + cc * 16) = *(const uint4*)(rsrc + (size_t)(r0 + rr) * ldr);
-    }
-    const float* bias = (const float*)(arena + (size_t)m * student_stride + b_off) + col0;
+    // The barrier in the last step of the last k-tile already separates every fragment read from what follows:
+    // the ring is free.
+    if (EPI == EPI_BIAS_RESIDUAL) issue_residual(1);
     // EPI_QKV: feature tiles at or beyond n_split (the value projection) are staged feature-major and written
     // transposed, out2[feature - n_split][token]; the choice is uniform over the workgroup.
     const bool transposed = EPI == EPI_QKV && n0 >= n_split;
+    // staged cell of (row r of the wave tile, 2-byte column c): half r / HR, chunk c / 8 swizzled by the row
+    auto cell = [&](int r, int c) {
+        const int h = r / HR, rh = r % HR;
+        return half_ptr(h) + rh * ROWB + (swz(rh, c >> 3) << 4) + (c & 7) * 2;
+    };
+    char* dst = (char*)(EPI == EPI_QKV && transposed ? out2 + (size_t)m * o2_ss + (size_t)(col0 - n_split) * ld2 + row0
+                                                     : out + (size_t)m * o_ss + row0 * ldo + col0);
+    const unsigned dpitch = 2u * (unsigned)(EPI == EPI_QKV && transposed ? ld2 : ldo);   // bytes
+    unsigned doff[NQ];
 #pragma unroll
-    for (int i = 0; i < TN; ++i)
+    for (int q = 0; q < NQ; ++q) doff[q] = (unsigned)(q * RPI + rr) * dpitch + (unsigned)cc * 16u;
+    // accumulators of token blocks [j0, j1) -> staging (bias is already in them)
+    auto stage_blocks = [&](int j0, int j1) {
 #pragma unroll
-        for (int v4 = 0; v4 < 4; ++v4) {
-            const int f = i * 32 + 8 * v4 + 4 * g;
-            const f32x4 b4 = *(const f32x4*)(bias + f);
+        for (int jj = j0; jj < j1; ++jj)
 #pragma unroll
-            for (int jj = 0; jj < TM; ++jj) {
-                char* cell = stg + (jj * 32 + j31) * PITCH + f * 2;
-                float r[4];
+            for (int i = 0; i < TN; ++i)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) r[e] = acc[i][jj][4 * v4 + e] + b4[e];
-                if (EPI == EPI_BIAS_GELU) {
+                for (int v4 = 0; v4 < 4; ++v4) {
+                    const int f = i * 32 + 8 * v4 + 4 * g;
+                    float r[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) r[e] = gelu_erf_fast(r[e]);
+                    for (int e = 0; e < 4; ++e) r[e] = acc[i][jj][4 * v4 + e];
+                    if (EPI == EPI_BIAS_GELU) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) r[e] = gelu_erf_fast(r[e]);
+                    }
+                    if (EPI == EPI_BIAS_TANH) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) r[e] = tanhf(r[e]);
+                    }
+                    if (EPI == EPI_QKV && transposed) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) *(bf16*)cell(f + e, jj * 32 + j31) = (bf16)r[e];
+                    } else {
+                        char* c = cell(jj * 32 + j31, f);
+                        if (EPI == EPI_BIAS_RESIDUAL) {
+                            const bf16x4 x4 = *(const bf16x4*)c;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) r[e] += (float)x4[e];
+                        }
+                        bf16x4 o4;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o4[e] = (bf16)r[e];
+                        *(bf16x4*)c = o4;
+                    }
                 }
-                if (EPI == EPI_BIAS_TANH) {
+    };
+    // staged rows of half h -> global memory, 16 bytes per lane, whole row segments (rows are tokens, or features
+    // if transposed)
+    auto store_half = [&](int h) {
+        const char* base = half_ptr(h);
+        char* db = dst + (size_t)h * HR * dpitch;
+#pragma unroll 2
+        for (int pr = 0; pr < HR / 16; ++pr)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) r[e] = tanhf(r[e]);
-                }
-                if (EPI == EPI_BIAS_RESIDUAL) {
-                    const bf16x4 x4 = *(const bf16x4*)cell;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) r[e] += (float)x4[e];
-                }
-                if (EPI == EPI_QKV && transposed) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) *(bf16*)(stg + (f + e) * PITCH + (jj * 32 + j31) * 2) = (bf16)r[e];
-                } else {
-                    bf16x4 o4;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) o4[e] = (bf16)r[e];
-                    *(bf16x4*)cell = o4;
-                }
-            }
-        }
-    // staged rows -> global memory, 16 bytes per lane, whole row segments (rows are tokens, or features if transposed)
-    bf16* dst = EPI == EPI_QKV && transposed
-                    ? out2 + (size_t)m * o2_ss + (size_t)(col0 - n_split) * ld2 + row0 + cc * 8
-                    : out + (size_t)m * o_ss + row0 * ldo + col0 + cc * 8;
-    const size_t dpitch = EPI == EPI_QKV && transposed ? (size_t)ld2 : (size_t)ldo;
-#pragma unroll 4
-    for (int r0 = 0; r0 < WTM; r0 += RPI)
-        *(uint4*)(dst + (size_t)(r0 + rr) * dpitch) = *(const uint4*)(stg + (r0 + rr) * PITCH + cc * 16);
+            for (int q = 0; q < NQ; ++q)
+                *(uint4*)(db + (size_t)pr * 16 * dpitch + doff[q]) = *(const uint4*)(base + pr * 16 * ROWB + soff[q]);
+    };
+    constexpr int NRL = HR / RPI;                           // residual loads, and row stores, per half
+    if (TM >= 2 && !(EPI == EPI_QKV && transposed)) {
+        // token blocks [0, TM / 2) live in half 0: the second half of the residual rows arrives while the first
+        // is computed, and the stores of the first half drain while the second is computed.  The waits are for
+        // this wave's own loads (no barrier); they come before any store is issued, because the counter orders
+        // loads among loads only.
+        if (EPI == EPI_BIAS_RESIDUAL) wait_vmcnt<NRL>();
+        stage_blocks(0, TM / 2);
+        if (EPI == EPI_BIAS_RESIDUAL) wait_vmcnt<0>();
+        store_half(0);
+        stage_blocks(TM / 2, TM);
+        store_half(1);
+    } else {
+        // one token block spans both halves, or staged rows are features: stage everything first
+        if (EPI == EPI_BIAS_RESIDUAL) wait_vmcnt<0>();
+        stage_blocks(0, TM);
+        store_half(0);
+        store_half(1);
+    }
 }
 
 // -------------------------------------------------------------------------------------
