@@ -58,6 +58,7 @@ ArenaLayout make_arena_layout(const sp_config& c)
         L.b2 = take(H * 4) - base;
         L.ln2g = take(H * 4) - base;
         L.ln2b = take(H * 4) - base;
+        L.wk_io = take(H * H * wb) - base;
         L.layer_stride = o - base;
         o = base + L.layer_stride * (size_t)c.layers;
     }
@@ -95,6 +96,8 @@ WsLayout make_ws_layout(const sp_config& c, int total_tokens, int batch)
     W.cu_ = take(K * crows * H * ab);
     W.cx1 = take(K * crows * H * ab);
     W.cg = take(K * crows * F * ab);
+    W.cqt = take(K * crows * (size_t)c.heads * H * ab);
+    W.cxb = take(K * crows * (size_t)c.heads * H * ab);
     W.crows = (int)crows;
     W.end = o;
     W.rows = (int)rows;
@@ -161,6 +164,7 @@ static void fill_student(const sp_config& c, const ArenaLayout& L, const float* 
     for (int l = 0; l < c.layers; ++l) {
         char* lb = dst + L.layer0 + (size_t)l * L.layer_stride;
         for (int part = 0; part < 3; ++part) {  // Wq bq Wk bk Wv bv -> rows [part*H, part*H+H) of the fused matrix
+            if (part == 1) w.copy(lb + L.wk_io, p, H * H);
             w.transpose(lb + L.wqkv + (size_t)part * H * H * wb, p, H, H); p += H * H;
             memcpy(lb + L.bqkv + (size_t)part * H * 4, p, H * 4); p += H;
         }
@@ -230,27 +234,32 @@ static int run_forward(const sp_model* M, const int32_t* ids, const int32_t* cu,
     SP_MARK(SP_PHASE_EMBED);
     // Last layer on the first-token rows only (see sp_config.last_layer_all_tokens).  Not used by the partial
     // forwards of the tests unless they stop before the last layer.
-    const bool first_only = c.dtype == SP_DTYPE_BF16 && !c.last_layer_all_tokens && with_head && T >= 1024 &&
-                            max_seqlen <= 512;
+    const bool first_only = !c.last_layer_all_tokens && with_head && T >= 1024 &&
+                            attention_first_fold_supported(c, max_seqlen);
     const int crows = W.crows;
     const int ctile = B > 256 ? 256 : (B > 64 ? 128 : 64);
     const int cmrows = (B + ctile - 1) / ctile * ctile;
     void *cx = w + W.cx, *cq = w + W.cq, *catt = w + W.catt, *cu2 = w + W.cu_, *cx1 = w + W.cx1, *cg = w + W.cg;
-    const size_t cH = (size_t)crows * H * ab, cF = (size_t)crows * F * ab;
+    void *cqt = w + W.cqt, *cxb = w + W.cxb;
+    const int nh = c.heads;
+    const size_t cH = (size_t)crows * H * ab, cF = (size_t)crows * F * ab, cHH = (size_t)crows * nh * H;   // cHH: elements
     bool compact_final = false;
     for (int l = 0; l < stop_layers; ++l) {
         const size_t lo = L.layer0 + (size_t)l * L.layer_stride;
         if (first_only && l == c.layers - 1) {
             SP_TRY(launch_gather_first(M, x, cu, B, T, rows, cx, catt, crows, cmrows, k, s));
             SP_MARK(SP_PHASE_EMBED);
-            // keys and values of every token (columns H..3H of the fused projection), queries of the first tokens
-            // (row-major values: the one-query attention kernel below reads whole value rows)
-            SP_TRY(launch_gemm(M, x, H, lo + L.wqkv + (size_t)H * H * ab, lo + L.bqkv + (size_t)H * 4, (char*)qkv + H * ab,
-                               3 * H, nullptr, 0, mrows, 2 * H, H, k, EPI_BIAS, sH, s3H, 0, s));
+            // queries of the first tokens, folded through the key projection: qt[b][h] = Wk[:, h] q[b][h]
             SP_TRY(launch_gemm(M, cx, H, lo + L.wqkv, lo + L.bqkv, cq, H, nullptr, 0, cmrows, H, H, k, EPI_BIAS, cH, cH, 0,
                                s));
+            SP_TRY(launch_head_gemm(M, cq, (size_t)crows * H, 64, H, lo + L.wk_io, 64, H, 0, 0, false, cqt, cHH, H, nh * H,
+                                    cmrows, H, 64, k, s));
             SP_MARK(SP_PHASE_QKV);
-            SP_TRY(launch_attention_first(M, cq, qkv, catt, cu, B, T, max_seqlen, rows, crows, k, s));
+            // p-weighted mean of the token rows per (sequence, head), then the value projection of those rows
+            SP_TRY(launch_attention_first_fold(M, x, cqt, cxb, cu, B, T, max_seqlen, rows, crows, cmrows, k, s));
+            SP_TRY(launch_head_gemm(M, cxb, cHH, H, nh * H, lo + L.wqkv + (size_t)2 * H * H * ab, (size_t)64 * H, H,
+                                    lo + L.bqkv + (size_t)2 * H * 4, 64, true, catt, (size_t)crows * H, 64, H, cmrows, 64, H,
+                                    k, s));
             SP_MARK(SP_PHASE_ATTENTION);
             SP_TRY(launch_gemm(M, catt, H, lo + L.wo, lo + L.bo, cu2, H, cx, H, cmrows, H, H, k, EPI_BIAS_RESIDUAL, cH, cH,
                                cH, s));

@@ -320,89 +320,176 @@ __global__ __launch_bounds__(256, 3) void attention_bf16_short_kernel(const bf16
 
 // -------------------------------------------------------------------------------------
 // Attention of one query per sequence (its first token), used when only the first-token rows of the last layer are
-// needed.  One wave per (student, sequence, head): lanes own keys for the scores and softmax, then head dimensions
-// for the weighted sum of the values (row-major here: the 64 lanes read one 128-byte row per key).
+// needed.  With a single query q per (sequence, head) the key and value projections of the other tokens never
+// have to be formed:
+//     score_t = q . (Wk^T x_t + bk) = (Wk q) . x_t + q . bk        (q . bk is the same for every t: softmax drops it)
+//     out     = sum_t p_t (Wv^T x_t + bv) = Wv^T (sum_t p_t x_t) + bv          (the p_t sum to one)
+// so the layer needs q~ = Wk q (one small product per head), one pass over the token rows x that yields the
+// p-weighted mean row x^ per head, and Wv^T x^ + bv (another small product per head).  That replaces a projection
+// of every token onto 2 H features, and reading those back, by one read of x.
 // -------------------------------------------------------------------------------------
-constexpr int kFirstMaxKeysPerLane = 8;   // sequences of up to 512 tokens
 
-__global__ __launch_bounds__(256) void attention_first_kernel(const bf16* __restrict__ qc, const bf16* __restrict__ qkv,
-                                                              bf16* __restrict__ attc,
-                                                              const int32_t* __restrict__ cu, int B, int Tn, int rows,
-                                                              int crows, int H, int heads, int max_seqlen)
+// Per-head small products: out[m][r][h][n] = sum_k A[m][r][h][k] W[m][h][n][k] (+ bias[m][h][n]), r < 32 * mtiles,
+// n < 32 * ntiles, k < Kd.  One 32x32 output tile per wave, fragments read straight from global memory (the work is
+// a few GFLOP per call).  Strides are in elements; the weights live in the arena at w_off (+ student stride).
+__global__ __launch_bounds__(256) void head_gemm_kernel(const bf16* __restrict__ A, size_t a_ss, size_t a_hs, int lda,
+                                                        const char* __restrict__ arena, size_t student_stride,
+                                                        size_t w_off, size_t w_hs, int ldw, size_t b_off, size_t b_hs,
+                                                        int has_bias, bf16* __restrict__ out, size_t o_ss, size_t o_hs,
+                                                        int ldo, int mtiles, int ntiles, int Kd)
 {
-    __shared__ float sp_all[4][64 * kFirstMaxKeysPerLane];
-    const int m = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int item = blockIdx.x * 4 + wave;             // (sequence, head)
-    if (item >= B * heads) return;
-    const int b = item / heads, h = item % heads;
-    float* sp = sp_all[wave];
+    const int m = blockIdx.z, h = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tile = blockIdx.x * 4 + wave;
+    if (tile >= mtiles * ntiles) return;
+    const int nt = tile % ntiles, mt = tile / ntiles;
+    const int j31 = lane & 31, g = lane >> 5;
+    const bf16* a = A + (size_t)m * a_ss + (size_t)h * a_hs + (size_t)(mt * 32 + j31) * lda + 8 * g;
+    const bf16* w = (const bf16*)(arena + (size_t)m * student_stride + w_off) + (size_t)h * w_hs +
+                    (size_t)(nt * 32 + j31) * ldw + 8 * g;
+    f32x16 acc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+#pragma unroll 4
+    for (int k0 = 0; k0 < Kd; k0 += 16) {
+        const bf16x8 fa = *(const bf16x8*)(a + k0);
+        const bf16x8 fw = *(const bf16x8*)(w + k0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw, fa, acc, 0, 0, 0);   // rows: output features, columns: r
+    }
+    // lane: row r = j31 of the tile; output features 8 * (v / 4) + 4 * g + v % 4
+    const float* bias = (const float*)(arena + (size_t)m * student_stride + b_off) + (size_t)h * b_hs + nt * 32;
+    bf16* o = out + (size_t)m * o_ss + (size_t)h * o_hs + (size_t)(mt * 32 + j31) * ldo + nt * 32;
+#pragma unroll
+    for (int v4 = 0; v4 < 4; ++v4) {
+        const int f = 8 * v4 + 4 * g;
+        bf16x4 r;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) r[e] = (bf16)(acc[4 * v4 + e] + (has_bias ? bias[f + e] : 0.f));
+        *(bf16x4*)(o + f) = r;
+    }
+}
+
+// One workgroup per (student, sequence): scores of every token against the folded queries q~ of all heads (matrix
+// cores: heads x tokens tiles, the token rows are the only global reads), softmax per head, then the p-weighted mean
+// of the token rows per head (vector units: each thread owns HEADS / 4 features for all heads).
+//   qt   [m][b][head][H]   folded queries (row stride HEADS * H)
+//   xbar [m][b][head][H]   output; rows b in [B, gridDim.x) are zeroed (they feed padded projections)
+constexpr int kFoldMaxLen = 512;
+constexpr size_t kFoldMaxSmem = (size_t)16 * (1024 + 8) * 2 + (size_t)16 * (kFoldMaxLen + 4) * 4;   // 16 heads, longest sequence
+
+template <int HEADS>
+__global__ __launch_bounds__(256) void attention_first_fold_kernel(const bf16* __restrict__ x, const bf16* __restrict__ qt,
+                                                                   bf16* __restrict__ xbar,
+                                                                   const int32_t* __restrict__ cu, int B, int Tn,
+                                                                   int rows, int crows, int max_seqlen, int LP)
+{
+    constexpr int H = HEADS * kD, NF = HEADS / 4;           // NF features per thread: H = 256 * NF
+    constexpr int QP = H + 8;                               // folded-query row pitch in LDS (elements)
+    extern __shared__ uint4 fold_smem[];
+    bf16* sq = (bf16*)fold_smem;                            // [HEADS][QP]
+    float* sc = (float*)(sq + HEADS * QP);                  // [HEADS][LP] scores, then probabilities
+    const int m = blockIdx.y, b = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    bf16* xb = xbar + ((size_t)m * crows + b) * HEADS * H;
+    if (b >= B) {
+        for (int c = tid; c < HEADS * H / 8; c += 256) ((uint4*)xb)[c] = make_uint4(0, 0, 0, 0);
+        return;
+    }
     int t0 = cu[b], t1 = cu[b + 1];
     t0 = t0 < 0 ? 0 : (t0 > Tn - 1 ? Tn - 1 : t0);
     int L = t1 - t0;
     L = L < 1 ? 1 : L;
     L = L > max_seqlen ? max_seqlen : L;
     L = L > Tn - t0 ? Tn - t0 : L;
-    L = L > 64 * kFirstMaxKeysPerLane ? 64 * kFirstMaxKeysPerLane : L;
+    const bf16* xs = x + ((size_t)m * rows + t0) * H;       // the sequence's token rows
 
-    float q[kD];
     {
-        const bf16* qr = qc + ((size_t)m * crows + b) * H + h * kD;
-#pragma unroll
-        for (int c = 0; c < 8; ++c) {
-            const bf16x8 t = *(const bf16x8*)(qr + c * 8);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) q[c * 8 + e] = (float)t[e];
+        const bf16* qrow = qt + ((size_t)m * crows + b) * HEADS * H;
+        for (int c = tid; c < HEADS * H / 8; c += 256) {
+            const int hh = c / (H / 8), i8 = c % (H / 8);
+            *(uint4*)(sq + hh * QP + i8 * 8) = *(const uint4*)(qrow + (size_t)hh * H + i8 * 8);
         }
     }
-    const size_t ld = (size_t)3 * H;
-    const bf16* kbase = qkv + ((size_t)m * rows + t0) * ld + H + h * kD;
-    float sc[kFirstMaxKeysPerLane];
-    float mx = -INFINITY;
+    __syncthreads();
+
+    // scores[head][token] = (q~[head] . x[token]) / 8, in log2 units
+    const int j31 = lane & 31, g = lane >> 5;
+    const float scale = 0.125f * 1.44269504088896341f;
+    for (int tile = wave; tile * 32 < L; tile += 4) {
+        const int tok = tile * 32 + j31;
+        const bf16* xr = xs + (size_t)(tok < L ? tok : L - 1) * H + 8 * g;
+        const bf16* qr = sq + (j31 < HEADS ? j31 : 0) * QP + 8 * g;
+        f32x16 acc;
 #pragma unroll
-    for (int i = 0; i < kFirstMaxKeysPerLane; ++i) {
-        const int key = lane + 64 * i;
-        sc[i] = -INFINITY;
-        if (key < L) {
-            const bf16* kr = kbase + (size_t)key * ld;
-            float d = 0.f;
+        for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+#pragma unroll 8
+        for (int k0 = 0; k0 < H; k0 += 16) {
+            const bf16x8 fx = *(const bf16x8*)(xr + k0);
+            bf16x8 fq = *(const bf16x8*)(qr + k0);
+            if (j31 >= HEADS) {
 #pragma unroll
-            for (int c = 0; c < 8; ++c) {
-                const bf16x8 t = *(const bf16x8*)(kr + c * 8);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) d = fmaf(q[c * 8 + e], (float)t[e], d);
+                for (int e = 0; e < 8; ++e) fq[e] = (bf16)0.f;
             }
-            sc[i] = d * (0.125f * 1.44269504088896341f);
-            mx = fmaxf(mx, sc[i]);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq, fx, acc, 0, 0, 0);   // rows: heads, columns: tokens
+        }
+        if (tok < L) {
+#pragma unroll
+            for (int v = 0; v < 8; ++v) {                   // rows 0..15 of the tile
+                const int hh = 8 * (v / 4) + 4 * g + v % 4;
+                if (hh < HEADS) sc[hh * LP + tok] = acc[v] * scale;
+            }
+        }
+    }
+    __syncthreads();
+
+    // softmax over the sequence, one wave per head at a time; pad to a multiple of four tokens with p = 0
+    const int L4 = (L + 3) & ~3;
+    for (int hh = wave; hh < HEADS; hh += 4) {
+        float* row = sc + hh * LP;
+        float mx = -INFINITY;
+        for (int t = lane; t < L; t += 64) mx = fmaxf(mx, row[t]);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+        float sum = 0.f;
+        for (int t = lane; t < L; t += 64) {
+            const float e = exp2f(row[t] - mx);
+            row[t] = e;
+            sum += e;
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+        const float inv = 1.0f / sum;
+        for (int t = lane; t < L4; t += 64) row[t] = t < L ? row[t] * inv : 0.f;
+    }
+    __syncthreads();
+
+    // xbar[head][f] = sum_t p[head][t] x[t][f]; thread owns features tid + 256 j
+    float acc[HEADS][NF];
+#pragma unroll
+    for (int hh = 0; hh < HEADS; ++hh)
+#pragma unroll
+        for (int j = 0; j < NF; ++j) acc[hh][j] = 0.f;
+    for (int t = 0; t < L4; t += 4) {
+        float xv[4][NF];
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) {
+            const int tk = t + tt < L ? t + tt : L - 1;     // padded tokens carry p = 0
+#pragma unroll
+            for (int j = 0; j < NF; ++j) xv[tt][j] = (float)xs[(size_t)tk * H + tid + 256 * j];
+        }
+#pragma unroll
+        for (int hh = 0; hh < HEADS; ++hh) {
+            const f32x4 p4 = *(const f32x4*)(sc + hh * LP + t);
+#pragma unroll
+            for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+                for (int j = 0; j < NF; ++j) acc[hh][j] = fmaf(p4[tt], xv[tt][j], acc[hh][j]);
         }
     }
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-    float sum = 0.f;
+    for (int hh = 0; hh < HEADS; ++hh)
 #pragma unroll
-    for (int i = 0; i < kFirstMaxKeysPerLane; ++i) {
-        const int key = lane + 64 * i;
-        const float p = key < L ? exp2f(sc[i] - mx) : 0.f;
-        sum += p;
-        if (key < L) sp[key] = p;
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    // lane = head dimension; the value rows sit next to the key rows
-    const bf16* vr = kbase + H + lane;
-    float o4[4] = {0.f, 0.f, 0.f, 0.f};             // four independent chains, sixteen loads in flight
-    int key = 0;
-    for (; key + 16 <= L; key += 16) {
-        float v[16];
-#pragma unroll
-        for (int e = 0; e < 16; ++e) v[e] = (float)vr[(size_t)(key + e) * ld];
-#pragma unroll
-        for (int e = 0; e < 16; ++e) o4[e & 3] = fmaf(sp[key + e], v[e], o4[e & 3]);
-    }
-    for (; key < L; ++key) o4[0] = fmaf(sp[key], (float)vr[(size_t)key * ld], o4[0]);
-    const float o = (o4[0] + o4[1]) + (o4[2] + o4[3]);
-    attc[((size_t)m * crows + b) * H + h * kD + lane] = (bf16)(o / sum);
+        for (int j = 0; j < NF; ++j) xb[(size_t)hh * H + tid + 256 * j] = (bf16)acc[hh][j];
 }
 
 // -------------------------------------------------------------------------------------
@@ -485,15 +572,57 @@ hipError_t launch_attention(const sp_model* M, const void* qkv, const void* vt, 
     return hipGetLastError();
 }
 
-hipError_t launch_attention_first(const sp_model* M, const void* qc, const void* qkv, void* attc,
-                                  const int32_t* cu, int B, int T, int max_seqlen, int rows, int crows, int k,
-                                  hipStream_t s)
+hipError_t launch_head_gemm(const sp_model* M, const void* A, size_t a_ss, size_t a_hs, int lda, size_t w_off,
+                            size_t w_hs, int ldw, size_t b_off, size_t b_hs, bool has_bias, void* out, size_t o_ss,
+                            size_t o_hs, int ldo, int mrows, int N, int Kd, int k, hipStream_t s)
 {
     const sp_config& c = M->cfg;
-    if (c.dtype != SP_DTYPE_BF16 || c.hidden / c.heads != kD || max_seqlen > 64 * kFirstMaxKeysPerLane)
+    if (c.dtype != SP_DTYPE_BF16 || mrows % 32 || N % 32 || Kd % 16 || lda % 8 || ldw % 8 || ldo % 4 || a_hs % 8 ||
+        w_hs % 8 || o_hs % 4)
         return hipErrorInvalidValue;
-    dim3 grid((unsigned)((B * c.heads + 3) / 4), k);
-    hipLaunchKernelGGL(attention_first_kernel, grid, dim3(256), 0, s, (const bf16*)qc, (const bf16*)qkv, (bf16*)attc, cu, B, T, rows, crows, c.hidden, c.heads, max_seqlen);
+    const int mtiles = mrows / 32, ntiles = N / 32;
+    dim3 grid((unsigned)((mtiles * ntiles + 3) / 4), (unsigned)c.heads, (unsigned)k);
+    hipLaunchKernelGGL(head_gemm_kernel, grid, dim3(256), 0, s, (const bf16*)A, a_ss, a_hs, lda, M->arena,
+                       M->L.student_stride, w_off, w_hs, ldw, b_off, b_hs, has_bias ? 1 : 0, (bf16*)out, o_ss, o_hs, ldo,
+                       mtiles, ntiles, Kd);
+    return hipGetLastError();
+}
+
+bool attention_first_fold_supported(const sp_config& c, int max_seqlen)
+{
+    return c.dtype == SP_DTYPE_BF16 && c.hidden / c.heads == kD && c.heads % 4 == 0 && c.heads <= 16 &&
+           max_seqlen <= kFoldMaxLen;
+}
+
+hipError_t launch_attention_first_fold(const sp_model* M, const void* x, const void* qt, void* xbar, const int32_t* cu,
+                                       int B, int T, int max_seqlen, int rows, int crows, int cmrows, int k,
+                                       hipStream_t s)
+{
+    const sp_config& c = M->cfg;
+    if (!attention_first_fold_supported(c, max_seqlen) || cmrows < B || cmrows > crows) return hipErrorInvalidValue;
+    const int LP = ((max_seqlen + 3) & ~3) + 4;             // score row pitch (floats)
+    const size_t smem = (size_t)c.heads * (c.hidden + 8) * 2 + (size_t)c.heads * LP * 4;
+    dim3 grid((unsigned)cmrows, (unsigned)k);
+#define SP_FOLD(HEADS)                                                                                              \
+    do {                                                                                                            \
+        auto kern = attention_first_fold_kernel<HEADS>;                                                             \
+        static bool raised = false; /* the attribute is sticky for the process */                                  \
+        if (smem > 48 * 1024 && !raised) {                                                                          \
+            hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,      \
+                                               (int)kFoldMaxSmem);                                                  \
+            if (e != hipSuccess) return e;                                                                          \
+            raised = true;                                                                                          \
+        }                                                                                                           \
+        hipLaunchKernelGGL(kern, grid, dim3(256), smem, s, (const bf16*)x, (const bf16*)qt, (bf16*)xbar, cu, B, T,  \
+                           rows, crows, max_seqlen, LP);                                                            \
+    } while (0)
+    switch (c.heads) {
+        case 4: SP_FOLD(4); break;
+        case 8: SP_FOLD(8); break;
+        case 12: SP_FOLD(12); break;
+        default: SP_FOLD(16); break;
+    }
+#undef SP_FOLD
     return hipGetLastError();
 }
 

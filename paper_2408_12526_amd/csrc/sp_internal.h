@@ -27,6 +27,7 @@ struct ArenaLayout {
     size_t layer0, layer_stride;
     // relative to the start of a layer
     size_t wqkv, bqkv, wo, bo, ln1g, ln1b, w1, b1, w2, b2, ln2g, ln2b;
+    size_t wk_io;                  // the key projection once more, [in][out] as in the host blob (folded first-token queries)
     size_t wp, wp_t, bp, wc, bc;   // wp: [in][out] (column-parallel head kernel); wp_t: [out][in] (GEMM operand)
     size_t student_stride;
 };
@@ -37,6 +38,7 @@ ArenaLayout make_arena_layout(const sp_config& c);
 struct WsLayout {
     size_t x, qkv, vt, att, u, x1, g, z, zpart, end;
     size_t cx, cq, catt, cu_, cx1, cg;   // first-token rows only: [K][crows][H] (cg: [F]), last layer
+    size_t cqt, cxb;                     // folded queries / weighted mean rows: [K][crows][heads][H]
     int rows, crows;
     int act_bytes;
 };
@@ -85,11 +87,20 @@ hipError_t launch_attention(const sp_model* M, const void* qkv, const void* vt, 
 hipError_t launch_gather_first(const sp_model* M, const void* x, const int32_t* cu, int B, int T, int rows, void* xc,
                                void* attc, int crows, int cmrows, int k, hipStream_t s);
 
-// Attention of the first token of each sequence only: attc[m][b][h*64..] = softmax(qc[m][b] k^T / 8) v, keys and
-// values of sequence b taken from the key and value slices of qkv (row-major).
-hipError_t launch_attention_first(const sp_model* M, const void* qc, const void* qkv, void* attc,
-                                  const int32_t* cu, int B, int T, int max_seqlen, int rows, int crows, int k,
-                                  hipStream_t s);
+// Per-head small products on the matrix cores: out[m][r][h][n] = sum_k A[m][r][h][k] W[m][h][n][k] (+ bias[m][h][n])
+// for r < mrows, n < N, k < Kd, every head h and student m < k.  Strides (_ss per student, _hs per head, ld per
+// row) are in elements; w_off / b_off are byte offsets into the student slab (bias: fp32).
+hipError_t launch_head_gemm(const sp_model* M, const void* A, size_t a_ss, size_t a_hs, int lda, size_t w_off,
+                            size_t w_hs, int ldw, size_t b_off, size_t b_hs, bool has_bias, void* out, size_t o_ss,
+                            size_t o_hs, int ldo, int mrows, int N, int Kd, int k, hipStream_t s);
+
+// Attention of the first token of each sequence with folded queries: for sequence b and head h,
+// p = softmax_t(qt[m][b][h] . x[m][t] / 8) over the tokens t of the sequence and xbar[m][b][h][:] = sum_t p_t x[m][t][:].
+// qt and xbar are [m][crows][heads][H]; rows b in [B, cmrows) of xbar are zeroed.
+bool attention_first_fold_supported(const sp_config& c, int max_seqlen);
+hipError_t launch_attention_first_fold(const sp_model* M, const void* x, const void* qt, void* xbar, const int32_t* cu,
+                                       int B, int T, int max_seqlen, int rows, int crows, int cmrows, int k,
+                                       hipStream_t s);
 
 // Head on pooled rows: z[m][b][c] = pooled[m][b] . Wc + bc; logits[b][c] = sum_{m<k} z[m][b][c] (m ascending).
 hipError_t launch_head_classify(const sp_model* M, const void* pooled, int B, int crows, int k, float* z, float* logits,

@@ -146,11 +146,14 @@ def test_small_shape_end_to_end(sp, oracle64, dtype):
 def test_first_token_last_layer_matches_all_tokens(sp, oracle64):
     """Calls with >= 1024 tokens run the last layer on the first-token rows only; a stock all-token last layer must
     give the same logits (up to attention's rounding order), and both must match the oracle."""
-    shape = STAGE_SHAPES["bf16"]
+    # four heads: the first-token path needs a head count that is a multiple of four (the small stage shape has two
+    # and would silently take the all-token path for both settings)
+    shape = synth.StudentShape(K=3, layers=2, hidden=256, heads=4, ffn=512, vocab=100, max_pos=320, classes=3,
+                               dtype="bf16")
     rng = np.random.default_rng(23)
     lengths = rng.integers(1, 130, size=37).astype(np.int32)
     lengths[:3] = (200, 1, 129)
-    assert lengths.sum() >= 1024
+    assert lengths.sum() >= 1024 and shape.heads % 4 == 0 and lengths.max() <= 512
     ids = synth.make_ids(rng, int(lengths.sum()), shape.vocab)
     blob = synth.make_weights(rng, shape, std=0.05, ln_random=True, qk_std=0.12)
     d_ids, d_cu, cu = gpu_inputs(lengths, ids, sp)
