@@ -32,24 +32,30 @@ def percentile(xs, q):
     return float(np.percentile(np.asarray(xs), q))
 
 
-def gemm_flops(shape, tokens, batch, k, first_token_last_layer):
-    """Flops actually executed per phase (algorithmic: real tokens, not the padded tile rows)."""
+def gemm_flops(shape, tokens, k, layers):
+    """Algorithmic flops of the four projections over `layers` all-token layers (real tokens, not padded tile rows)."""
     H, F = shape.hidden, shape.ffn
-    full = {"qkv": 2 * tokens * H * 3 * H, "oproj": 2 * tokens * H * H, "ffn_up": 2 * tokens * H * F,
-            "ffn_down": 2 * tokens * F * H}
-    if not first_token_last_layer:
-        return {n: v * k * shape.layers for n, v in full.items()}
-    # last layer: keys and values for every token, everything else for the first token of each sequence only
-    last = {"qkv": 2 * tokens * H * 2 * H + 2 * batch * H * H, "oproj": 2 * batch * H * H, "ffn_up": 2 * batch * H * F,
-            "ffn_down": 2 * batch * F * H}
-    return {n: (full[n] * (shape.layers - 1) + last[n]) * k for n in full}
+    per_layer = {"qkv": 2 * tokens * H * 3 * H, "oproj": 2 * tokens * H * H, "ffn_up": 2 * tokens * H * F,
+                 "ffn_down": 2 * tokens * F * H}
+    return {n: v * k * layers for n, v in per_layer.items()}
 
 
-def attention_flops(shape, lengths, k, first_token_last_layer):
-    sq, lin = int((lengths.astype(np.int64) ** 2).sum()), int(lengths.astype(np.int64).sum())
-    if not first_token_last_layer:
-        return 4 * shape.hidden * sq * k * shape.layers
-    return 4 * shape.hidden * (sq * (shape.layers - 1) + lin) * k
+def attention_flops(shape, lengths, k, layers):
+    sq = int((lengths.astype(np.int64) ** 2).sum())
+    return 4 * shape.hidden * sq * k * layers
+
+
+def last_first_work(shape, tokens, batch, k):
+    """The last layer on first-token rows only: executed flops and the HBM bytes that dominate it (one read of the
+    layer's input rows for the folded attention; the projections run on `batch` rows per student)."""
+    H, F, nh = shape.hidden, shape.ffn, shape.heads
+    flops = k * (2 * batch * H * H                      # queries
+                 + 2 * batch * nh * H * 64              # queries folded through the key projection
+                 + 4 * tokens * nh * H                  # scores and weighted mean rows
+                 + 2 * batch * H * H                    # value projection of the mean rows
+                 + 2 * batch * H * H + 4 * batch * H * F)   # output projection, feed-forward
+    weight_bytes = k * (4 * H * H + 2 * H * F) * 2
+    return flops, k * tokens * H * 2 + weight_bytes
 
 
 def main():
@@ -124,19 +130,25 @@ def main():
             ms = st4.sp_forward_profiled(d_ids4, d_cu4, mx4, 8, logits4, ws4)
             for n, v in ms.items():
                 acc[n] += v / args.steps
-        gf = gemm_flops(w4.shape, T4, B4, 8, True)
         H, F, Ly = w4.shape.hidden, w4.shape.ffn, w4.shape.layers
+        full_layers = Ly - 1 if acc["last_first"] > 0 else Ly   # layers that ran on every token
+        gf = gemm_flops(w4.shape, T4, 8, full_layers)
         for n in ("qkv", "oproj", "ffn_up", "ffn_down"):
             phases[n] = {"ms": acc[n], "bound": "mfma", "tflops": gf[n] / acc[n] / 1e9,
                          "frac": gf[n] / acc[n] / 1e9 / PEAK_BF16_TFLOPS}
-        af = attention_flops(w4.shape, batch4.lengths, 8, True)
+        af = attention_flops(w4.shape, batch4.lengths, 8, full_layers)
         phases["attention"] = {"ms": acc["attention"], "bound": "mfma", "tflops": af / acc["attention"] / 1e9,
                                "frac": af / acc["attention"] / 1e9 / PEAK_BF16_TFLOPS}
         emb_bytes = 8 * T4 * (6 * H + 4)                      # two table rows read, one row written, bf16, + id
-        ln_bytes = 8 * (T4 * (Ly - 1) + B4) * 2 * (4 * H)     # every LayerNorm reads a row and writes a row, bf16
+        ln_bytes = 8 * T4 * full_layers * 2 * (4 * H)         # every LayerNorm reads a row and writes a row, bf16
         head_bytes = 8 * (B4 * H * 2 + (H * H + H * w4.shape.classes) * 2)
         for n, b in (("embed", emb_bytes), ("layernorm", ln_bytes), ("head", head_bytes)):
             phases[n] = {"ms": acc[n], "bound": "hbm", "gbs": b / acc[n] / 1e6, "frac": b / acc[n] / 1e6 / PEAK_HBM_GBS}
+        if acc["last_first"] > 0:
+            lf_flops, lf_bytes = last_first_work(w4.shape, T4, B4, 8)
+            phases["last_layer_first_token_rows"] = {
+                "ms": acc["last_first"], "bound": "hbm", "gbs": lf_bytes / acc["last_first"] / 1e6,
+                "frac": lf_bytes / acc["last_first"] / 1e6 / PEAK_HBM_GBS, "tflops": lf_flops / acc["last_first"] / 1e9}
         gemm_ms = sum(acc[n] for n in ("qkv", "oproj", "ffn_up", "ffn_down"))
         phases["gemm_phase_total"] = {"ms": gemm_ms, "bound": "mfma", "tflops": sum(gf.values()) / gemm_ms / 1e9,
                                       "frac": sum(gf.values()) / gemm_ms / 1e9 / PEAK_BF16_TFLOPS}
@@ -210,7 +222,8 @@ def main():
         "config": {"workload": "c4_burst_b256: K=8 students x 2 layers, hidden 768, 12 heads, FFN 3072, vocab 30522, "
                                "batch 256, lognormal lengths (median 48, sigma 0.6, clipped to [8,256]), k_active=8",
                    "total_tokens": T4, "batch": B4, "k_active": main_k,
-                   "variant": "last layer on first-token rows only (exact work saving; flops below are the executed ones)"},
+                   "variant": "last layer on first-token rows only (exact work saving); the projection and attention "
+                              "phases below are the all-token layer's launches alone"},
         "burst_all_token_last_layer_k8": all_tokens,
         "burst_by_k_active": {str(k): v for k, v in burst.items()},
         "latency_batch1_by_k_active": {str(k): v for k, v in latency.items()},
@@ -220,7 +233,9 @@ def main():
     }
     if phases:
         d = phases["ffn_up"]
-        rec["roofline"] = {"kernel": "gemm_bf16_kernel (FFN up-projection + GELU)", "bound": "mfma",
+        # the ffn_up phase is exactly one launch of this kernel per step (HIP events around it, on the launch stream)
+        rec["roofline"] = {"kernel": "gemm_bf16_kernel<256,256,BIAS_GELU> (FFN up-projection + GELU, all-token layer)",
+                           "bound": "mfma",
                            "achieved": d["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": d["frac"],
                            "traffic": None}
     rec["cpu_baseline"] = cpu

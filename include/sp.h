@@ -174,6 +174,9 @@ enum {
     SP_PHASE_FFN_UP,      /* feed-forward up-projection + GELU */
     SP_PHASE_FFN_DOWN,    /* feed-forward down-projection + residual */
     SP_PHASE_HEAD,        /* pooling, per-student head, cross-student sum */
+    SP_PHASE_LAST_FIRST,  /* every kernel of a last layer that is computed for the first-token rows only
+                           * (sp_config.last_layer_all_tokens == 0 and the call is large enough); the
+                           * phases above then cover the other layers alone */
     SP_PHASE_COUNT
 };
 

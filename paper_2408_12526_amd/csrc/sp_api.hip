@@ -248,32 +248,32 @@ static int run_forward(const sp_model* M, const int32_t* ids, const int32_t* cu,
         const size_t lo = L.layer0 + (size_t)l * L.layer_stride;
         if (first_only && l == c.layers - 1) {
             SP_TRY(launch_gather_first(M, x, cu, B, T, rows, cx, catt, crows, cmrows, k, s));
-            SP_MARK(SP_PHASE_EMBED);
+            SP_MARK(SP_PHASE_LAST_FIRST);
             // queries of the first tokens, folded through the key projection: qt[b][h] = Wk[:, h] q[b][h]
             SP_TRY(launch_gemm(M, cx, H, lo + L.wqkv, lo + L.bqkv, cq, H, nullptr, 0, cmrows, H, H, k, EPI_BIAS, cH, cH, 0,
                                s));
             SP_TRY(launch_head_gemm(M, cq, (size_t)crows * H, 64, H, lo + L.wk_io, 64, H, 0, 0, false, cqt, cHH, H, nh * H,
                                     cmrows, H, 64, k, s));
-            SP_MARK(SP_PHASE_QKV);
+            SP_MARK(SP_PHASE_LAST_FIRST);
             // p-weighted mean of the token rows per (sequence, head), then the value projection of those rows
             SP_TRY(launch_attention_first_fold(M, x, cqt, cxb, cu, B, T, max_seqlen, rows, crows, cmrows, k, s));
             SP_TRY(launch_head_gemm(M, cxb, cHH, H, nh * H, lo + L.wqkv + (size_t)2 * H * H * ab, (size_t)64 * H, H,
                                     lo + L.bqkv + (size_t)2 * H * 4, 64, true, catt, (size_t)crows * H, 64, H, cmrows, 64, H,
                                     k, s));
-            SP_MARK(SP_PHASE_ATTENTION);
+            SP_MARK(SP_PHASE_LAST_FIRST);
             SP_TRY(launch_gemm(M, catt, H, lo + L.wo, lo + L.bo, cu2, H, cx, H, cmrows, H, H, k, EPI_BIAS_RESIDUAL, cH, cH,
                                cH, s));
-            SP_MARK(SP_PHASE_OPROJ);
+            SP_MARK(SP_PHASE_LAST_FIRST);
             SP_TRY(launch_layernorm(M, cu2, cx1, crows, cmrows, k, lo + L.ln1g, lo + L.ln1b, s));
-            SP_MARK(SP_PHASE_LAYERNORM);
+            SP_MARK(SP_PHASE_LAST_FIRST);
             SP_TRY(launch_gemm(M, cx1, H, lo + L.w1, lo + L.b1, cg, F, nullptr, 0, cmrows, F, H, k, EPI_BIAS_GELU, cH, cF, 0,
                                s));
-            SP_MARK(SP_PHASE_FFN_UP);
+            SP_MARK(SP_PHASE_LAST_FIRST);
             SP_TRY(launch_gemm(M, cg, F, lo + L.w2, lo + L.b2, cu2, H, cx1, H, cmrows, H, F, k, EPI_BIAS_RESIDUAL, cF, cH,
                                cH, s));
-            SP_MARK(SP_PHASE_FFN_DOWN);
+            SP_MARK(SP_PHASE_LAST_FIRST);
             SP_TRY(launch_layernorm(M, cu2, cx, crows, cmrows, k, lo + L.ln2g, lo + L.ln2b, s));
-            SP_MARK(SP_PHASE_LAYERNORM);
+            SP_MARK(SP_PHASE_LAST_FIRST);
             compact_final = true;
             continue;
         }

@@ -1,5 +1,7 @@
 // Multi-head self-attention over a packed batch: every sequence attends to itself only,
 // over exactly its own tokens (cu_seqlens gives the boundaries); head width is 64.
+#include <type_traits>
+
 #include "sp_internal.h"
 
 namespace sp {
@@ -350,7 +352,7 @@ __global__ __launch_bounds__(256) void head_gemm_kernel(const bf16* __restrict__
     f32x16 acc;
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-#pragma unroll 4
+#pragma unroll 16
     for (int k0 = 0; k0 < Kd; k0 += 16) {
         const bf16x8 fa = *(const bf16x8*)(a + k0);
         const bf16x8 fw = *(const bf16x8*)(w + k0);
@@ -369,30 +371,38 @@ __global__ __launch_bounds__(256) void head_gemm_kernel(const bf16* __restrict__
     }
 }
 
-// One workgroup per (student, sequence): scores of every token against the folded queries q~ of all heads (matrix
-// cores: heads x tokens tiles, the token rows are the only global reads), softmax per head, then the p-weighted mean
-// of the token rows per head (vector units: each thread owns HEADS / 4 features for all heads).
+// One workgroup (eight waves) per (student, sequence).
+//   scores: heads x tokens tiles on the matrix cores; the waves split the feature (reduction) range, each keeps its
+//           slice of the folded queries in registers, and the eight partial tiles are added in a fixed order;
+//   softmax per head;
+//   weighted mean rows: features x heads tiles on the matrix cores, each wave owns HEADS / 4 blocks of 32 features.
+// The token rows x are the only large global reads (twice, the second time from cache).
 //   qt   [m][b][head][H]   folded queries (row stride HEADS * H)
 //   xbar [m][b][head][H]   output; rows b in [B, gridDim.x) are zeroed (they feed padded projections)
 constexpr int kFoldMaxLen = 512;
-constexpr size_t kFoldMaxSmem = (size_t)16 * (1024 + 8) * 2 + (size_t)16 * (kFoldMaxLen + 4) * 4;   // 16 heads, longest sequence
+constexpr int kFoldWaves = 8;
+constexpr size_t kFoldPartBytes = (size_t)kFoldWaves * 16 * 32 * 4;
+constexpr size_t kFoldMaxSmem =                               // 16 heads, longest sequence
+    kFoldPartBytes + (size_t)16 * (kFoldMaxLen + 4) * 4 + (size_t)16 * (kFoldMaxLen + 8) * 2;
 
 template <int HEADS>
-__global__ __launch_bounds__(256) void attention_first_fold_kernel(const bf16* __restrict__ x, const bf16* __restrict__ qt,
-                                                                   bf16* __restrict__ xbar,
-                                                                   const int32_t* __restrict__ cu, int B, int Tn,
-                                                                   int rows, int crows, int max_seqlen, int LP)
+__global__ __launch_bounds__(512, 4) void attention_first_fold_kernel(const bf16* __restrict__ x,
+                                                                      const bf16* __restrict__ qt,
+                                                                      bf16* __restrict__ xbar,
+                                                                      const int32_t* __restrict__ cu, int B, int Tn,
+                                                                      int rows, int crows, int max_seqlen, int LP, int PP)
 {
-    constexpr int H = HEADS * kD, NF = HEADS / 4;           // NF features per thread: H = 256 * NF
-    constexpr int QP = H + 8;                               // folded-query row pitch in LDS (elements)
+    constexpr int H = HEADS * kD;
+    constexpr int KS = H / (kFoldWaves * 16);               // 16-feature reduction steps per wave (scores)
     extern __shared__ uint4 fold_smem[];
-    bf16* sq = (bf16*)fold_smem;                            // [HEADS][QP]
-    float* sc = (float*)(sq + HEADS * QP);                  // [HEADS][LP] scores, then probabilities
+    float* part = (float*)fold_smem;                        // [waves][16][32] partial score tiles
+    float* sc = part + kFoldWaves * 16 * 32;                // [HEADS][LP] scores
+    bf16* pT = (bf16*)(sc + HEADS * LP);                    // [HEADS][PP] probabilities, zero beyond the sequence
     const int m = blockIdx.y, b = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     bf16* xb = xbar + ((size_t)m * crows + b) * HEADS * H;
     if (b >= B) {
-        for (int c = tid; c < HEADS * H / 8; c += 256) ((uint4*)xb)[c] = make_uint4(0, 0, 0, 0);
+        for (int c = tid; c < HEADS * H / 8; c += 64 * kFoldWaves) ((uint4*)xb)[c] = make_uint4(0, 0, 0, 0);
         return;
     }
     int t0 = cu[b], t1 = cu[b + 1];
@@ -402,49 +412,51 @@ __global__ __launch_bounds__(256) void attention_first_fold_kernel(const bf16* _
     L = L > max_seqlen ? max_seqlen : L;
     L = L > Tn - t0 ? Tn - t0 : L;
     const bf16* xs = x + ((size_t)m * rows + t0) * H;       // the sequence's token rows
-
-    {
-        const bf16* qrow = qt + ((size_t)m * crows + b) * HEADS * H;
-        for (int c = tid; c < HEADS * H / 8; c += 256) {
-            const int hh = c / (H / 8), i8 = c % (H / 8);
-            *(uint4*)(sq + hh * QP + i8 * 8) = *(const uint4*)(qrow + (size_t)hh * H + i8 * 8);
-        }
-    }
-    __syncthreads();
+    const int j31 = lane & 31, g = lane >> 5;
 
     // scores[head][token] = (q~[head] . x[token]) / 8, in log2 units
-    const int j31 = lane & 31, g = lane >> 5;
+    bf16x8 fq[KS];
+    {
+        const bf16* qr = qt + (((size_t)m * crows + b) * HEADS + (j31 < HEADS ? j31 : 0)) * H + wave * (H / kFoldWaves) + 8 * g;
+#pragma unroll
+        for (int st = 0; st < KS; ++st) {
+            fq[st] = *(const bf16x8*)(qr + 16 * st);
+            if (j31 >= HEADS) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) fq[st][e] = (bf16)0.f;
+            }
+        }
+    }
     const float scale = 0.125f * 1.44269504088896341f;
-    for (int tile = wave; tile * 32 < L; tile += 4) {
+    for (int tile = 0; tile * 32 < L; ++tile) {
         const int tok = tile * 32 + j31;
-        const bf16* xr = xs + (size_t)(tok < L ? tok : L - 1) * H + 8 * g;
-        const bf16* qr = sq + (j31 < HEADS ? j31 : 0) * QP + 8 * g;
+        const bf16* xr = xs + (size_t)(tok < L ? tok : L - 1) * H + wave * (H / kFoldWaves) + 8 * g;
+        bf16x8 fx[KS];
+#pragma unroll
+        for (int st = 0; st < KS; ++st) fx[st] = *(const bf16x8*)(xr + 16 * st);
         f32x16 acc;
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-#pragma unroll 8
-        for (int k0 = 0; k0 < H; k0 += 16) {
-            const bf16x8 fx = *(const bf16x8*)(xr + k0);
-            bf16x8 fq = *(const bf16x8*)(qr + k0);
-            if (j31 >= HEADS) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) fq[e] = (bf16)0.f;
-            }
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq, fx, acc, 0, 0, 0);   // rows: heads, columns: tokens
-        }
-        if (tok < L) {
+        for (int st = 0; st < KS; ++st)
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[st], fx[st], acc, 0, 0, 0);   // rows: heads, columns: tokens
 #pragma unroll
-            for (int v = 0; v < 8; ++v) {                   // rows 0..15 of the tile
-                const int hh = 8 * (v / 4) + 4 * g + v % 4;
-                if (hh < HEADS) sc[hh * LP + tok] = acc[v] * scale;
-            }
+        for (int v = 0; v < 8; ++v)                         // rows 0..15 of the tile
+            part[(wave * 16 + 8 * (v / 4) + 4 * g + v % 4) * 32 + j31] = acc[v];
+        __syncthreads();
+        {
+            const int hh = tid >> 5, t = tid & 31;          // 16 x 32 sums, one per thread, waves in a fixed order
+            float sum = 0.f;
+#pragma unroll
+            for (int w = 0; w < kFoldWaves; ++w) sum += part[(w * 16 + hh) * 32 + t];
+            if (hh < HEADS && tile * 32 + t < L) sc[hh * LP + tile * 32 + t] = sum * scale;
         }
+        __syncthreads();
     }
-    __syncthreads();
 
-    // softmax over the sequence, one wave per head at a time; pad to a multiple of four tokens with p = 0
-    const int L4 = (L + 3) & ~3;
-    for (int hh = wave; hh < HEADS; hh += 4) {
+    // softmax over the sequence, one wave per head at a time; probabilities as bf16, zero up to a multiple of 16 tokens
+    const int L16 = (L + 15) & ~15;
+    for (int hh = wave; hh < HEADS; hh += kFoldWaves) {
         float* row = sc + hh * LP;
         float mx = -INFINITY;
         for (int t = lane; t < L; t += 64) mx = fmaxf(mx, row[t]);
@@ -459,37 +471,61 @@ __global__ __launch_bounds__(256) void attention_first_fold_kernel(const bf16* _
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
         const float inv = 1.0f / sum;
-        for (int t = lane; t < L4; t += 64) row[t] = t < L ? row[t] * inv : 0.f;
+        for (int t = lane; t < L16; t += 64) pT[hh * PP + t] = (bf16)(t < L ? row[t] * inv : 0.f);
     }
     __syncthreads();
 
-    // xbar[head][f] = sum_t p[head][t] x[t][f]; thread owns features tid + 256 j
-    float acc[HEADS][NF];
+    // xbar^T[feature][head] = sum_t x[t][feature] p[head][t].  The instruction wants, per lane, eight tokens of one
+    // feature; token rows are feature-contiguous, so a lane loads four neighbouring features (8 bytes) of each of
+    // its eight tokens and unzips them into four operands: row r of operand c is feature 4 r + c of a block of 128
+    // features.  (Two-byte gathers would be one load instruction per token and feature row, and the address unit
+    // spends the same sixteen cycles on a wave's load whatever its width.)  Wave w < H / 128 owns block w.
+    if (wave < H / 128) {
+        f32x16 acc[4];
 #pragma unroll
-    for (int hh = 0; hh < HEADS; ++hh)
+        for (int c = 0; c < 4; ++c)
 #pragma unroll
-        for (int j = 0; j < NF; ++j) acc[hh][j] = 0.f;
-    for (int t = 0; t < L4; t += 4) {
-        float xv[4][NF];
+            for (int e = 0; e < 16; ++e) acc[c][e] = 0.f;
+        const bf16* pr = pT + (j31 < HEADS ? j31 : 0) * PP + 8 * g;
+        const bf16* xc = xs + wave * 128 + 4 * j31;         // this lane's four feature columns
+        auto kstep = [&](int k0, auto clamp_c) {
+            constexpr bool CLAMP = decltype(clamp_c)::value;
+            bf16x8 fp = *(const bf16x8*)(pr + k0);
+            if (j31 >= HEADS) {
 #pragma unroll
-        for (int tt = 0; tt < 4; ++tt) {
-            const int tk = t + tt < L ? t + tt : L - 1;     // padded tokens carry p = 0
+                for (int e = 0; e < 8; ++e) fp[e] = (bf16)0.f;
+            }
+            bf16x4 xv[8];
 #pragma unroll
-            for (int j = 0; j < NF; ++j) xv[tt][j] = (float)xs[(size_t)tk * H + tid + 256 * j];
-        }
+            for (int e = 0; e < 8; ++e) {
+                int tk = k0 + 8 * g + e;
+                if (CLAMP) tk = tk < L ? tk : L - 1;        // tokens beyond the sequence carry p = 0
+                xv[e] = *(const bf16x4*)(xc + (size_t)tk * H);
+            }
 #pragma unroll
-        for (int hh = 0; hh < HEADS; ++hh) {
-            const f32x4 p4 = *(const f32x4*)(sc + hh * LP + t);
+            for (int c = 0; c < 4; ++c) {
+                bf16x8 fx;
 #pragma unroll
-            for (int tt = 0; tt < 4; ++tt)
+                for (int e = 0; e < 8; ++e) fx[e] = xv[e][c];
+                acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx, fp, acc[c], 0, 0, 0);   // rows: features, columns: heads
+            }
+        };
+        int k0 = 0;
+        for (; k0 + 16 <= L; k0 += 16) kstep(k0, std::false_type{});
+        if (k0 < L16) kstep(k0, std::true_type{});
+        // lane: head j31; accumulator element 4 v4 + e of operand c is feature 4 (8 v4 + 4 g + e) + c of the block
+        if (j31 < HEADS) {
 #pragma unroll
-                for (int j = 0; j < NF; ++j) acc[hh][j] = fmaf(p4[tt], xv[tt][j], acc[hh][j]);
+            for (int v4 = 0; v4 < 4; ++v4)
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    bf16x8 r;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) r[i] = (bf16)acc[i & 3][4 * v4 + 2 * half + (i >> 2)];
+                    *(bf16x8*)(xb + (size_t)j31 * H + wave * 128 + 32 * v4 + 16 * g + 8 * half) = r;
+                }
         }
     }
-#pragma unroll
-    for (int hh = 0; hh < HEADS; ++hh)
-#pragma unroll
-        for (int j = 0; j < NF; ++j) xb[(size_t)hh * H + tid + 256 * j] = (bf16)acc[hh][j];
 }
 
 // -------------------------------------------------------------------------------------
@@ -601,7 +637,8 @@ hipError_t launch_attention_first_fold(const sp_model* M, const void* x, const v
     const sp_config& c = M->cfg;
     if (!attention_first_fold_supported(c, max_seqlen) || cmrows < B || cmrows > crows) return hipErrorInvalidValue;
     const int LP = ((max_seqlen + 3) & ~3) + 4;             // score row pitch (floats)
-    const size_t smem = (size_t)c.heads * (c.hidden + 8) * 2 + (size_t)c.heads * LP * 4;
+    const int PP = ((max_seqlen + 15) & ~15) + 8;           // probability row pitch (bf16)
+    const size_t smem = kFoldPartBytes + (size_t)c.heads * LP * 4 + (size_t)c.heads * PP * 2;
     dim3 grid((unsigned)cmrows, (unsigned)k);
 #define SP_FOLD(HEADS)                                                                                              \
     do {                                                                                                            \
@@ -613,8 +650,8 @@ hipError_t launch_attention_first_fold(const sp_model* M, const void* x, const v
             if (e != hipSuccess) return e;                                                                          \
             raised = true;                                                                                          \
         }                                                                                                           \
-        hipLaunchKernelGGL(kern, grid, dim3(256), smem, s, (const bf16*)x, (const bf16*)qt, (bf16*)xbar, cu, B, T,  \
-                           rows, crows, max_seqlen, LP);                                                            \
+        hipLaunchKernelGGL(kern, grid, dim3(64 * kFoldWaves), smem, s, (const bf16*)x, (const bf16*)qt, (bf16*)xbar,  \
+                           cu, B, T, rows, crows, max_seqlen, LP, PP);                                              \
     } while (0)
     switch (c.heads) {
         case 4: SP_FOLD(4); break;

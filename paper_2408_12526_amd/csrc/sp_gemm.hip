@@ -437,7 +437,9 @@ hipError_t launch_bf16(const sp_model* M, const void* A, int lda, size_t w_off, 
     // a feature tile must lie entirely on one side of n_split
     if (mrows % 256 == 0 && mrows >= 2048 && N % 256 == 0 && n_split % 256 == 0)
         return launch_bf16_tile<256, 256, EPI>(SP_ARGS);
-    if (mrows % 128 == 0 && N % 128 == 0 && n_split % 128 == 0) return launch_bf16_tile<128, 128, EPI>(SP_ARGS);
+    // (a grid of fewer 128x128 tiles than compute units would leave most of the chip idle: smaller tiles then)
+    if (mrows % 128 == 0 && N % 128 == 0 && n_split % 128 == 0 && (long)k * (mrows / 128) * (N / 128) >= 256)
+        return launch_bf16_tile<128, 128, EPI>(SP_ARGS);
     return launch_bf16_tile<64, 64, EPI>(SP_ARGS);
 #undef SP_ARGS
 }

@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsp_mi355x.so")
 
 SP_DTYPE_FP32, SP_DTYPE_BF16 = 0, 1
-PHASES = ("embed", "qkv", "attention", "oproj", "layernorm", "ffn_up", "ffn_down", "head")
+PHASES = ("embed", "qkv", "attention", "oproj", "layernorm", "ffn_up", "ffn_down", "head", "last_first")
 
 
 class sp_config(C.Structure):
