@@ -13,6 +13,7 @@ constexpr int kQPerWg = 128;    // queries per workgroup: 4 waves x 32
 constexpr int kKeyTile = 64;    // keys staged in LDS per step
 constexpr int kKStride = kKeyTile + 1;   // 16-byte units per k-group of the key tile
 constexpr int kVStride = 68;    // bf16 elements per row of the transposed value tile (136 B)
+constexpr int kOutPitch = kD * 2 + 16;   // bytes per staged output row
 
 // -------------------------------------------------------------------------------------
 // bf16 kernel on the matrix cores.  One workgroup = (student, sequence, head, block of 128
@@ -32,6 +33,7 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(const bf16* __restr
 {
     __shared__ uint4 sK[8 * kKStride];             // [d-group of 8][key]
     __shared__ __attribute__((aligned(16))) bf16 sVt[kD * kVStride];   // [d][key]
+    __shared__ __attribute__((aligned(16))) char sOut[4][32 * kOutPitch];   // per wave: 32 output rows
 
     const int m = blockIdx.y;
     int idx = blockIdx.x;
@@ -156,18 +158,26 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(const bf16* __restr
     if (wave_active) {
         const float lsum = lrun + __shfl_xor(lrun, 32);
         const float inv = 1.0f / lsum;
-        if (q < L) {
-            bf16* dst = att + ((size_t)m * rows + t0 + q) * H + h * kD;
+        // the wave's 32 x 64 output block leaves through a private LDS tile as whole 128-byte rows
+        char* stg = sOut[wave];
 #pragma unroll
-            for (int db = 0; db < 2; ++db)
+        for (int db = 0; db < 2; ++db)
 #pragma unroll
-                for (int v4 = 0; v4 < 4; ++v4) {
-                    bf16x4 w;
+            for (int v4 = 0; v4 < 4; ++v4) {
+                bf16x4 w;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) w[e] = (bf16)(o[db][4 * v4 + e] * inv);
-                    *(bf16x4*)(dst + db * 32 + 8 * v4 + 4 * g) = w;
-                }
-        }
+                for (int e = 0; e < 4; ++e) w[e] = (bf16)(o[db][4 * v4 + e] * inv);
+                *(bf16x4*)(stg + j * kOutPitch + (db * 32 + 8 * v4 + 4 * g) * 2) = w;
+            }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        const int orow = lane >> 3, oc = lane & 7;
+        const int qw = q0 + wave * 32;                      // the wave's first query
+        bf16* dst = att + ((size_t)m * rows + t0 + qw) * H + h * kD + oc * 8;
+#pragma unroll
+        for (int r0 = 0; r0 < 32; r0 += 8)
+            if (qw + r0 + orow < L)
+                *(uint4*)(dst + (size_t)(r0 + orow) * H) = *(const uint4*)(stg + (r0 + orow) * kOutPitch + oc * 16);
     }
 }
 
@@ -182,6 +192,7 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(const bf16* __restr
 constexpr int kSKey = 32;                 // keys per tile
 constexpr int kSKStride = kSKey + 1;      // 16-byte units per d-group of the key tile
 constexpr int kSVStride = 36;             // bf16 elements per row of the transposed value tile (72 B)
+static_assert(kD * kSVStride * 2 == 32 * (kSVStride * 4) && kSVStride * 4 >= kD * 2 + 16, "the value slice doubles as the 32 x 64 output staging tile");
 
 __global__ __launch_bounds__(256, 3) void attention_bf16_short_kernel(const bf16* __restrict__ qkv,
                                                                       const bf16* __restrict__ vt, bf16* __restrict__ att,
@@ -305,8 +316,11 @@ __global__ __launch_bounds__(256, 3) void attention_bf16_short_kernel(const bf16
             __builtin_amdgcn_wave_barrier();       // the slice is rewritten at the top of the next iteration
         }
         const float inv = 1.0f / (lrun + __shfl_xor(lrun, 32));
-        if (q < L) {
-            bf16* dst = att + ((size_t)m * rows + t0 + q) * H + h * kD;
+        // The 32 x 64 output block leaves through this wave's (now idle) value slice, so that a store instruction
+        // writes eight whole 128-byte rows (eight-byte pieces of 32 rows per instruction are several times slower
+        // on the way to memory).
+        {
+            char* stg = (char*)sVt;                         // 32 rows of 144 bytes = the whole slice
 #pragma unroll
             for (int db = 0; db < 2; ++db)
 #pragma unroll
@@ -314,8 +328,18 @@ __global__ __launch_bounds__(256, 3) void attention_bf16_short_kernel(const bf16
                     bf16x4 w;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) w[e] = (bf16)(o[db][4 * v4 + e] * inv);
-                    *(bf16x4*)(dst + db * 32 + 8 * v4 + 4 * g) = w;
+                    *(bf16x4*)(stg + j * (kSVStride * 4) + (db * 32 + 8 * v4 + 4 * g) * 2) = w;
                 }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            const int orow = lane >> 3, oc = lane & 7;
+            bf16* dst = att + ((size_t)m * rows + t0 + q0) * H + h * kD + oc * 8;
+#pragma unroll
+            for (int r0 = 0; r0 < 32; r0 += 8)
+                if (q0 + r0 + orow < L)
+                    *(uint4*)(dst + (size_t)(r0 + orow) * H) = *(const uint4*)(stg + (r0 + orow) * (kSVStride * 4) + oc * 16);
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();                // the slice is rewritten by the next pass
         }
     }
 }
@@ -332,43 +356,65 @@ __global__ __launch_bounds__(256, 3) void attention_bf16_short_kernel(const bf16
 // -------------------------------------------------------------------------------------
 
 // Per-head small products: out[m][r][h][n] = sum_k A[m][r][h][k] W[m][h][n][k] (+ bias[m][h][n]), r < 32 * mtiles,
-// n < 32 * ntiles, k < Kd.  One 32x32 output tile per wave, fragments read straight from global memory (the work is
-// a few GFLOP per call).  Strides are in elements; the weights live in the arena at w_off (+ student stride).
+// n < 32 * NT * nstrips, k < Kd.  One strip of 32 rows x (32 NT) outputs per wave (the strip shares the row operand and
+// writes runs of 64 NT contiguous bytes), fragments read straight from global memory (the work is a few GFLOP per
+// call).  Strides are in elements; the weights live in the arena at w_off (+ student stride).
+template <int NT>
 __global__ __launch_bounds__(256) void head_gemm_kernel(const bf16* __restrict__ A, size_t a_ss, size_t a_hs, int lda,
                                                         const char* __restrict__ arena, size_t student_stride,
                                                         size_t w_off, size_t w_hs, int ldw, size_t b_off, size_t b_hs,
                                                         int has_bias, bf16* __restrict__ out, size_t o_ss, size_t o_hs,
-                                                        int ldo, int mtiles, int ntiles, int Kd)
+                                                        int ldo, int mtiles, int nstrips, int Kd)
 {
     const int m = blockIdx.z, h = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int tile = blockIdx.x * 4 + wave;
-    if (tile >= mtiles * ntiles) return;
-    const int nt = tile % ntiles, mt = tile / ntiles;
+    const int item = blockIdx.x * 4 + wave;
+    if (item >= mtiles * nstrips) return;
+    const int ns = item % nstrips, mt = item / nstrips;
     const int j31 = lane & 31, g = lane >> 5;
     const bf16* a = A + (size_t)m * a_ss + (size_t)h * a_hs + (size_t)(mt * 32 + j31) * lda + 8 * g;
     const bf16* w = (const bf16*)(arena + (size_t)m * student_stride + w_off) + (size_t)h * w_hs +
-                    (size_t)(nt * 32 + j31) * ldw + 8 * g;
-    f32x16 acc;
+                    (size_t)(ns * NT * 32 + j31) * ldw + 8 * g;
+    f32x16 acc[NT];
 #pragma unroll
-    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-#pragma unroll 16
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+#pragma unroll 8
     for (int k0 = 0; k0 < Kd; k0 += 16) {
         const bf16x8 fa = *(const bf16x8*)(a + k0);
-        const bf16x8 fw = *(const bf16x8*)(w + k0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw, fa, acc, 0, 0, 0);   // rows: output features, columns: r
-    }
-    // lane: row r = j31 of the tile; output features 8 * (v / 4) + 4 * g + v % 4
-    const float* bias = (const float*)(arena + (size_t)m * student_stride + b_off) + (size_t)h * b_hs + nt * 32;
-    bf16* o = out + (size_t)m * o_ss + (size_t)h * o_hs + (size_t)(mt * 32 + j31) * ldo + nt * 32;
 #pragma unroll
-    for (int v4 = 0; v4 < 4; ++v4) {
-        const int f = 8 * v4 + 4 * g;
-        bf16x4 r;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) r[e] = (bf16)(acc[4 * v4 + e] + (has_bias ? bias[f + e] : 0.f));
-        *(bf16x4*)(o + f) = r;
+        for (int t = 0; t < NT; ++t) {
+            const bf16x8 fw = *(const bf16x8*)(w + (size_t)t * 32 * ldw + k0);
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw, fa, acc[t], 0, 0, 0);   // rows: output features, columns: r
+        }
     }
+    // lane: row r = j31 of the strip; output features 32 t + 8 (v / 4) + 4 g + v % 4.  The strip goes through a
+    // wave-private LDS tile so that it leaves as whole 16-byte-per-lane row segments (eight-byte pieces scattered
+    // over 32 rows per instruction are several times slower on the way to memory).
+    constexpr int SW = NT * 32;                             // strip width (features)
+    constexpr int PITCH = SW * 2 + 16;                      // bytes per staged row
+    __shared__ __attribute__((aligned(16))) char stage_all[4][32 * PITCH];
+    char* stg = stage_all[wave];
+    const float* bias = (const float*)(arena + (size_t)m * student_stride + b_off) + (size_t)h * b_hs + ns * SW;
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int v4 = 0; v4 < 4; ++v4) {
+            const int f = 32 * t + 8 * v4 + 4 * g;
+            bf16x4 r;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) r[e] = (bf16)(acc[t][4 * v4 + e] + (has_bias ? bias[f + e] : 0.f));
+            *(bf16x4*)(stg + j31 * PITCH + f * 2) = r;
+        }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    constexpr int CPR = SW / 8, RPI = 64 / CPR;             // 16-byte chunks per row, rows per instruction
+    const int rr = lane / CPR, cc = lane % CPR;
+    bf16* o = out + (size_t)m * o_ss + (size_t)h * o_hs + (size_t)(mt * 32) * ldo + ns * SW + cc * 8;
+#pragma unroll
+    for (int r0 = 0; r0 < 32; r0 += RPI)
+        *(uint4*)(o + (size_t)(r0 + rr) * ldo) = *(const uint4*)(stg + (r0 + rr) * PITCH + cc * 16);
 }
 
 // One workgroup (eight waves) per (student, sequence).
@@ -428,18 +474,23 @@ __global__ __launch_bounds__(512, 4) void attention_first_fold_kernel(const bf16
         }
     }
     const float scale = 0.125f * 1.44269504088896341f;
-    for (int tile = 0; tile * 32 < L; ++tile) {
+    // (the rows of the next tile are requested before the current tile is multiplied and reduced)
+    bf16x8 fx[KS];
+    auto load_tile = [&](int tile) {
         const int tok = tile * 32 + j31;
         const bf16* xr = xs + (size_t)(tok < L ? tok : L - 1) * H + wave * (H / kFoldWaves) + 8 * g;
-        bf16x8 fx[KS];
 #pragma unroll
         for (int st = 0; st < KS; ++st) fx[st] = *(const bf16x8*)(xr + 16 * st);
+    };
+    load_tile(0);
+    for (int tile = 0; tile * 32 < L; ++tile) {
         f32x16 acc;
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[e] = 0.f;
 #pragma unroll
         for (int st = 0; st < KS; ++st)
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[st], fx[st], acc, 0, 0, 0);   // rows: heads, columns: tokens
+        if ((tile + 1) * 32 < L) load_tile(tile + 1);
 #pragma unroll
         for (int v = 0; v < 8; ++v)                         // rows 0..15 of the tile
             part[(wave * 16 + 8 * (v / 4) + 4 * g + v % 4) * 32 + j31] = acc[v];
@@ -488,31 +539,34 @@ __global__ __launch_bounds__(512, 4) void attention_first_fold_kernel(const bf16
             for (int e = 0; e < 16; ++e) acc[c][e] = 0.f;
         const bf16* pr = pT + (j31 < HEADS ? j31 : 0) * PP + 8 * g;
         const bf16* xc = xs + wave * 128 + 4 * j31;         // this lane's four feature columns
-        auto kstep = [&](int k0, auto clamp_c) {
-            constexpr bool CLAMP = decltype(clamp_c)::value;
+        // (the rows of the next sixteen tokens are requested before the current ones are multiplied; rows beyond the
+        // sequence are clamped to its last row and carry p = 0)
+        bf16x4 xv[8];
+        auto load_rows = [&](int k0) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                int tk = k0 + 8 * g + e;
+                tk = tk < L ? tk : L - 1;
+                xv[e] = *(const bf16x4*)(xc + (size_t)tk * H);
+            }
+        };
+        load_rows(0);
+        for (int k0 = 0; k0 < L16; k0 += 16) {
             bf16x8 fp = *(const bf16x8*)(pr + k0);
             if (j31 >= HEADS) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) fp[e] = (bf16)0.f;
             }
-            bf16x4 xv[8];
+            bf16x8 fxc[4];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                int tk = k0 + 8 * g + e;
-                if (CLAMP) tk = tk < L ? tk : L - 1;        // tokens beyond the sequence carry p = 0
-                xv[e] = *(const bf16x4*)(xc + (size_t)tk * H);
-            }
+            for (int c = 0; c < 4; ++c)
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                bf16x8 fx;
+                for (int e = 0; e < 8; ++e) fxc[c][e] = xv[e][c];
+            if (k0 + 16 < L16) load_rows(k0 + 16);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) fx[e] = xv[e][c];
-                acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx, fp, acc[c], 0, 0, 0);   // rows: features, columns: heads
-            }
-        };
-        int k0 = 0;
-        for (; k0 + 16 <= L; k0 += 16) kstep(k0, std::false_type{});
-        if (k0 < L16) kstep(k0, std::true_type{});
+            for (int c = 0; c < 4; ++c)
+                acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fxc[c], fp, acc[c], 0, 0, 0);   // rows: features, columns: heads
+        }
         // lane: head j31; accumulator element 4 v4 + e of operand c is feature 4 (8 v4 + 4 g + e) + c of the block
         if (j31 < HEADS) {
 #pragma unroll
@@ -613,14 +667,22 @@ hipError_t launch_head_gemm(const sp_model* M, const void* A, size_t a_ss, size_
                             size_t o_hs, int ldo, int mrows, int N, int Kd, int k, hipStream_t s)
 {
     const sp_config& c = M->cfg;
-    if (c.dtype != SP_DTYPE_BF16 || mrows % 32 || N % 32 || Kd % 16 || lda % 8 || ldw % 8 || ldo % 4 || a_hs % 8 ||
-        w_hs % 8 || o_hs % 4)
+    if (c.dtype != SP_DTYPE_BF16 || mrows % 32 || N % 32 || Kd % 16 || lda % 8 || ldw % 8 || ldo % 8 || a_hs % 8 ||
+        w_hs % 8 || o_hs % 8)
         return hipErrorInvalidValue;
-    const int mtiles = mrows / 32, ntiles = N / 32;
-    dim3 grid((unsigned)((mtiles * ntiles + 3) / 4), (unsigned)c.heads, (unsigned)k);
-    hipLaunchKernelGGL(head_gemm_kernel, grid, dim3(256), 0, s, (const bf16*)A, a_ss, a_hs, lda, M->arena,
-                       M->L.student_stride, w_off, w_hs, ldw, b_off, b_hs, has_bias ? 1 : 0, (bf16*)out, o_ss, o_hs, ldo,
-                       mtiles, ntiles, Kd);
+    const int mtiles = mrows / 32;
+#define SP_HEAD_GEMM(NT)                                                                                            \
+    do {                                                                                                            \
+        const int nstrips = N / (32 * NT);                                                                          \
+        dim3 grid((unsigned)((mtiles * nstrips + 3) / 4), (unsigned)c.heads, (unsigned)k);                          \
+        hipLaunchKernelGGL(head_gemm_kernel<NT>, grid, dim3(256), 0, s, (const bf16*)A, a_ss, a_hs, lda, M->arena,  \
+                           M->L.student_stride, w_off, w_hs, ldw, b_off, b_hs, has_bias ? 1 : 0, (bf16*)out, o_ss,  \
+                           o_hs, ldo, mtiles, nstrips, Kd);                                                         \
+    } while (0)
+    if (N % 128 == 0) SP_HEAD_GEMM(4);
+    else if (N % 64 == 0) SP_HEAD_GEMM(2);
+    else SP_HEAD_GEMM(1);
+#undef SP_HEAD_GEMM
     return hipGetLastError();
 }
 
