@@ -41,108 +41,140 @@ __device__ inline void store8(bf16* p, const float (&v)[8])
 
 // LayerNorm of one row held across a wave as v[chunk][8]; chunk c of lane l covers
 // elements 8*(l + 64c) .. +7.  Two passes over registers: mean, then centred variance.
-template <typename T>
-__device__ inline void ln_row_store(float (&v)[kMaxChunks][8], int nch, int lane, int H, const float* g,
-                                    const float* b, float eps, T* out)
+// gamma and beta are held the same way (a wave keeps them for all the rows it normalises).
+template <typename T, int MAXC>
+__device__ inline void ln_row_store(float (&v)[MAXC][8], int nch, int lane, int H, const float (&gg)[MAXC][8],
+                                    const float (&bb)[MAXC][8], float eps, T* out)
 {
     float s = 0.f;
 #pragma unroll
-    for (int i = 0; i < kMaxChunks; ++i)
+    for (int i = 0; i < MAXC; ++i)
         if (lane + 64 * i < nch)
 #pragma unroll
             for (int e = 0; e < 8; ++e) s += v[i][e];
     const float mean = wave_sum(s) / (float)H;
     float q = 0.f;
 #pragma unroll
-    for (int i = 0; i < kMaxChunks; ++i)
+    for (int i = 0; i < MAXC; ++i)
         if (lane + 64 * i < nch)
 #pragma unroll
             for (int e = 0; e < 8; ++e) { const float d = v[i][e] - mean; q += d * d; }
     const float inv = 1.0f / sqrtf(wave_sum(q) / (float)H + eps);
 #pragma unroll
-    for (int i = 0; i < kMaxChunks; ++i) {
+    for (int i = 0; i < MAXC; ++i) {
         const int c = lane + 64 * i;
         if (c < nch) {
-            float gg[8], bb[8], o[8];
-            load8(g + c * 8, gg);
-            load8(b + c * 8, bb);
+            float o[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = gg[e] * ((v[i][e] - mean) * inv) + bb[e];
+            for (int e = 0; e < 8; ++e) o[e] = gg[i][e] * ((v[i][e] - mean) * inv) + bb[i][e];
             store8(out + c * 8, o);
         }
     }
 }
 
-// One wave per packed token row, grid.y = student.
-template <typename T>
+template <int MAXC>
+__device__ inline void load_gamma_beta(const float* g, const float* b, int nch, int lane, float (&gg)[MAXC][8],
+                                       float (&bb)[MAXC][8])
+{
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+        const int c = lane + 64 * i;
+        if (c < nch) { load8(g + c * 8, gg[i]); load8(b + c * 8, bb[i]); }
+    }
+}
+
+// Consecutive rows normalised by one wave (gamma / beta are fetched once for them): 8 for calls that fill the chip
+// either way, 1 for small calls, where the row-parallelism is worth more than the saved fetches.
+inline int rows_per_wave(int mrows, int k) { return (long)mrows * k >= 32768 ? 8 : 1; }
+
+// One wave per rpw consecutive packed token rows, grid.y = student.
+template <typename T, int MAXC>
 __global__ __launch_bounds__(256) void embed_ln_kernel(const char* arena, size_t student_stride, size_t tok_off,
                                                        size_t pos_off, size_t g_off, size_t b_off,
                                                        const int32_t* __restrict__ ids,
                                                        const int32_t* __restrict__ cu, int B, int Tn, int rows,
                                                        int mrows, int H, int V, int P, float eps, T* __restrict__ x,
-                                                       T* __restrict__ att)
+                                                       T* __restrict__ att, int rpw)
 {
     const int m = blockIdx.y, lane = threadIdx.x & 63;
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= mrows) return;
+    const int row0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * rpw;
+    if (row0 >= mrows) return;
     const int nch = H >> 3;
-    T* out = x + ((size_t)m * rows + row) * H;
-    if (row >= Tn) {
-        // Padding rows of the token tile.  They never reach a result, but the projections compute them and the
-        // attention kernels fetch values in chunks of eight tokens, so they must hold finite numbers: zero the
-        // hidden state here and, once per call, the attention output rows that no kernel writes.
-        const float zero8[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        T* arow = att + ((size_t)m * rows + row) * H;
-        for (int c = lane; c < nch; c += 64) { store8(out + c * 8, zero8); store8(arow + c * 8, zero8); }
-        return;
-    }
-    // sequence of this row: largest b with cu[b] <= row
-    int lo = 0, hi = B;
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (cu[mid] <= row) lo = mid; else hi = mid;
-    }
-    int pos = row - cu[lo];
-    pos = pos < 0 ? 0 : (pos >= P ? P - 1 : pos);
-    int id = ids[row];
-    id = id < 0 ? 0 : (id >= V ? V - 1 : id);
     const char* sb = arena + (size_t)m * student_stride;
-    const T* te = (const T*)(sb + tok_off) + (size_t)id * H;
-    const T* pe = (const T*)(sb + pos_off) + (size_t)pos * H;
-    float v[kMaxChunks][8];
-#pragma unroll
-    for (int i = 0; i < kMaxChunks; ++i) {
-        const int c = lane + 64 * i;
-        if (c < nch) {
-            float a[8], p8[8];
-            load8(te + c * 8, a);
-            load8(pe + c * 8, p8);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[i][e] = a[e] + p8[e];
+    float gg[MAXC][8], bb[MAXC][8];
+    load_gamma_beta<MAXC>((const float*)(sb + g_off), (const float*)(sb + b_off), nch, lane, gg, bb);
+    // sequence of the first row: largest b with cu[b] <= row; later rows walk forward from there
+    int seq = 0;
+    if (row0 < Tn) {
+        int lo = 0, hi = B;
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (cu[mid] <= row0) lo = mid; else hi = mid;
         }
+        seq = lo;
     }
-    ln_row_store<T>(v, nch, lane, H, (const float*)(sb + g_off), (const float*)(sb + b_off), eps, out);
+#pragma unroll 2
+    for (int r = 0; r < rpw; ++r) {
+        const int row = row0 + r;
+        if (row >= mrows) break;
+        T* out = x + ((size_t)m * rows + row) * H;
+        if (row >= Tn) {
+            // Padding rows of the token tile.  They never reach a result, but the projections compute them and the
+            // attention kernels fetch values in chunks of eight tokens, so they must hold finite numbers: zero the
+            // hidden state here and, once per call, the attention output rows that no kernel writes.
+            const float zero8[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+            T* arow = att + ((size_t)m * rows + row) * H;
+            for (int c = lane; c < nch; c += 64) { store8(out + c * 8, zero8); store8(arow + c * 8, zero8); }
+            continue;
+        }
+        while (seq + 1 < B && cu[seq + 1] <= row) ++seq;
+        int pos = row - cu[seq];
+        pos = pos < 0 ? 0 : (pos >= P ? P - 1 : pos);
+        int id = ids[row];
+        id = id < 0 ? 0 : (id >= V ? V - 1 : id);
+        const T* te = (const T*)(sb + tok_off) + (size_t)id * H;
+        const T* pe = (const T*)(sb + pos_off) + (size_t)pos * H;
+        float v[MAXC][8];
+#pragma unroll
+        for (int i = 0; i < MAXC; ++i) {
+            const int c = lane + 64 * i;
+            if (c < nch) {
+                float a[8], p8[8];
+                load8(te + c * 8, a);
+                load8(pe + c * 8, p8);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[i][e] = a[e] + p8[e];
+            }
+        }
+        ln_row_store<T, MAXC>(v, nch, lane, H, gg, bb, eps, out);
+    }
 }
 
-template <typename T>
+template <typename T, int MAXC>
 __global__ __launch_bounds__(256) void layernorm_kernel(const char* arena, size_t student_stride, size_t g_off,
                                                         size_t b_off, const T* __restrict__ u, T* __restrict__ out,
-                                                        int rows, int mrows, int H, float eps)
+                                                        int rows, int mrows, int H, float eps, int rpw)
 {
     const int m = blockIdx.y, lane = threadIdx.x & 63;
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= mrows) return;
+    const int row0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * rpw;
+    if (row0 >= mrows) return;
     const int nch = H >> 3;
-    const T* in = u + ((size_t)m * rows + row) * H;
-    float v[kMaxChunks][8];
-#pragma unroll
-    for (int i = 0; i < kMaxChunks; ++i) {
-        const int c = lane + 64 * i;
-        if (c < nch) load8(in + c * 8, v[i]);
-    }
     const char* sb = arena + (size_t)m * student_stride;
-    ln_row_store<T>(v, nch, lane, H, (const float*)(sb + g_off), (const float*)(sb + b_off), eps,
-                    out + ((size_t)m * rows + row) * H);
+    float gg[MAXC][8], bb[MAXC][8];
+    load_gamma_beta<MAXC>((const float*)(sb + g_off), (const float*)(sb + b_off), nch, lane, gg, bb);
+#pragma unroll 2
+    for (int r = 0; r < rpw; ++r) {
+        const int row = row0 + r;
+        if (row >= mrows) break;
+        const T* in = u + ((size_t)m * rows + row) * H;
+        float v[MAXC][8];
+#pragma unroll
+        for (int i = 0; i < MAXC; ++i) {
+            const int c = lane + 64 * i;
+            if (c < nch) load8(in + c * 8, v[i]);
+        }
+        ln_row_store<T, MAXC>(v, nch, lane, H, gg, bb, eps, out + ((size_t)m * rows + row) * H);
+    }
 }
 
 // First-token rows: one wave per (student, sequence).
@@ -298,13 +330,21 @@ hipError_t launch_embed_ln(const sp_model* M, const int32_t* ids, const int32_t*
 {
     const sp_config& c = M->cfg;
     const ArenaLayout& L = M->L;
-    dim3 grid((mrows + 3) / 4, k);
-    if (c.dtype == SP_DTYPE_BF16)
-        hipLaunchKernelGGL(embed_ln_kernel<bf16>, grid, dim3(256), 0, s, M->arena, L.student_stride, L.tok, L.pos,
-                           L.emb_g, L.emb_b, ids, cu, B, T, rows, mrows, c.hidden, c.vocab, c.max_pos, c.ln_eps, (bf16*)x, (bf16*)att);
-    else
-        hipLaunchKernelGGL(embed_ln_kernel<float>, grid, dim3(256), 0, s, M->arena, L.student_stride, L.tok, L.pos,
-                           L.emb_g, L.emb_b, ids, cu, B, T, rows, mrows, c.hidden, c.vocab, c.max_pos, c.ln_eps, (float*)x, (float*)att);
+    const int rpw = rows_per_wave(mrows, k);
+    dim3 grid((mrows + 4 * rpw - 1) / (4 * rpw), k);
+    const int maxc = (c.hidden / 8 + 63) / 64;              // 8-element chunks per lane
+#define SP_EMBED(T, MAXC)                                                                                          \
+    hipLaunchKernelGGL((embed_ln_kernel<T, MAXC>), grid, dim3(256), 0, s, M->arena, L.student_stride, L.tok, L.pos, \
+                       L.emb_g, L.emb_b, ids, cu, B, T_, rows, mrows, c.hidden, c.vocab, c.max_pos, c.ln_eps, (T*)x, \
+                       (T*)att, rpw)
+    const int T_ = T;
+    if (maxc > kMaxChunks) return hipErrorInvalidValue;
+    if (c.dtype == SP_DTYPE_BF16) {
+        if (maxc <= 1) SP_EMBED(bf16, 1); else if (maxc == 2) SP_EMBED(bf16, 2); else SP_EMBED(bf16, 4);
+    } else {
+        if (maxc <= 1) SP_EMBED(float, 1); else if (maxc == 2) SP_EMBED(float, 2); else SP_EMBED(float, 4);
+    }
+#undef SP_EMBED
     return hipGetLastError();
 }
 
@@ -312,13 +352,19 @@ hipError_t launch_layernorm(const sp_model* M, const void* u, void* out, int row
                             size_t b_off, hipStream_t s)
 {
     const sp_config& c = M->cfg;
-    dim3 grid((mrows + 3) / 4, k);
-    if (c.dtype == SP_DTYPE_BF16)
-        hipLaunchKernelGGL(layernorm_kernel<bf16>, grid, dim3(256), 0, s, M->arena, M->L.student_stride, g_off, b_off,
-                           (const bf16*)u, (bf16*)out, rows, mrows, c.hidden, c.ln_eps);
-    else
-        hipLaunchKernelGGL(layernorm_kernel<float>, grid, dim3(256), 0, s, M->arena, M->L.student_stride, g_off, b_off,
-                           (const float*)u, (float*)out, rows, mrows, c.hidden, c.ln_eps);
+    const int rpw = rows_per_wave(mrows, k);
+    dim3 grid((mrows + 4 * rpw - 1) / (4 * rpw), k);
+    const int maxc = (c.hidden / 8 + 63) / 64;              // 8-element chunks per lane
+    if (maxc > kMaxChunks) return hipErrorInvalidValue;
+#define SP_LN(T, MAXC)                                                                                              \
+    hipLaunchKernelGGL((layernorm_kernel<T, MAXC>), grid, dim3(256), 0, s, M->arena, M->L.student_stride, g_off,    \
+                       b_off, (const T*)u, (T*)out, rows, mrows, c.hidden, c.ln_eps, rpw)
+    if (c.dtype == SP_DTYPE_BF16) {
+        if (maxc <= 1) SP_LN(bf16, 1); else if (maxc == 2) SP_LN(bf16, 2); else SP_LN(bf16, 4);
+    } else {
+        if (maxc <= 1) SP_LN(float, 1); else if (maxc == 2) SP_LN(float, 2); else SP_LN(float, 4);
+    }
+#undef SP_LN
     return hipGetLastError();
 }
 
