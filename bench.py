@@ -32,6 +32,12 @@ def percentile(xs, q):
     return float(np.percentile(np.asarray(xs), q))
 
 
+# HBM-side bytes of one launch of the FFN-up GEMM at k_active = 8 on the burst workload, from two rocprofv3 --pmc runs
+# (FETCH_SIZE, WRITE_SIZE) scaled by the same counters on a 1 GiB copy; the summary with the commands is
+# profiles/hbm_traffic_gemm_ffn_up_c4_burst_b256.txt.  A counter run cannot be made from inside the timed process.
+FFN_UP_HBM_BYTES_PER_LAUNCH = {"read": 1.298e9, "written": 7.298e8}
+
+
 def gemm_flops(shape, tokens, k, layers):
     """Algorithmic flops of the four projections over `layers` all-token layers (real tokens, not padded tile rows)."""
     H, F = shape.hidden, shape.ffn
@@ -237,7 +243,12 @@ def main():
         rec["roofline"] = {"kernel": "gemm_bf16_kernel<256,256,BIAS_GELU> (FFN up-projection + GELU, all-token layer)",
                            "bound": "mfma",
                            "achieved": d["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": d["frac"],
-                           "traffic": None}
+                           "traffic": FFN_UP_HBM_BYTES_PER_LAUNCH["read"] + FFN_UP_HBM_BYTES_PER_LAUNCH["written"],
+                           "traffic_unit": "bytes beyond L2 per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)",
+                           "traffic_read": FFN_UP_HBM_BYTES_PER_LAUNCH["read"],
+                           "traffic_written": FFN_UP_HBM_BYTES_PER_LAUNCH["written"],
+                           "algorithmic_bytes": 8 * 14848 * (H + F) * 2 + 8 * H * F * 2,
+                           "algorithmic_flops": gf["ffn_up"], "launch_ms": d["ms"]}
     rec["cpu_baseline"] = cpu
     print(json.dumps(rec))
 

@@ -166,6 +166,40 @@ def test_first_token_last_layer_matches_all_tokens(sp, oracle64):
     assert rel_err(got[False], got[True]) < 1e-2
 
 
+# ---- the other student shapes the paper uses (Table 2: 2L256D, its headline student; 6L768D; 12L1024D) -------------
+
+OTHER_SHAPES = {
+    # name: (shape, number of sequences, length range); batches sized so that the fp64 oracle takes seconds
+    "2L256D": (synth.StudentShape(K=4, layers=2, hidden=256, heads=4, ffn=1024, vocab=1000, max_pos=128, classes=2,
+                                  dtype="bf16"), 28, (8, 100)),       # >= 1024 tokens: first-token last layer, 4 heads
+    "6L768D": (synth.StudentShape(K=1, layers=6, hidden=768, heads=12, ffn=3072, vocab=500, max_pos=128, classes=2,
+                                  dtype="bf16"), 7, (8, 80)),
+    "12L1024D": (synth.StudentShape(K=1, layers=12, hidden=1024, heads=16, ffn=4096, vocab=500, max_pos=128, classes=3,
+                                    dtype="bf16"), 4, (8, 48)),
+}
+
+
+@pytest.mark.parametrize("name", list(OTHER_SHAPES))
+def test_other_student_shapes(sp, oracle64, name):
+    """The kernels are shape-generic (hidden 256 / 768 / 1024 with 64-wide heads) and the layer count is a loop
+    bound only: whole forward against the oracle, weights N(0, 0.02) as in the workloads.  The query/key weights are
+    spread so that the attention scores have a standard deviation of about 1.5 at every width (far from uniform, so a
+    wrong scale or mask shows, but not the near-argmax regime in which twelve layers amplify any rounding chaotically)."""
+    shape, nseq, (lo, hi) = OTHER_SHAPES[name]
+    rng = np.random.default_rng(31)
+    lengths = rng.integers(lo, hi + 1, size=nseq).astype(np.int32)
+    if name == "2L256D":
+        lengths[:2] = (100, 100)
+        assert lengths.sum() >= 1024
+    ids = synth.make_ids(rng, int(lengths.sum()), shape.vocab)
+    blob = synth.make_weights(rng, shape, std=0.02, ln_random=True, qk_std=float(np.sqrt(1.5 / shape.hidden)))
+    st = sp.Students(sp.config_from_shape(shape), blob)
+    d_ids, d_cu, cu = gpu_inputs(lengths, ids, sp)
+    got = st.sp_forward(d_ids, d_cu, int(lengths.max()), shape.K).cpu().numpy().astype(np.float64)
+    want = oracle64.forward(ocfg(shape), oracle_weights(blob, shape), ids, cu, shape.K)
+    check_logits(got, want, shape, name)
+
+
 # ---- the five workloads ----------------------------------------------------------------------------
 
 _cache = {}
