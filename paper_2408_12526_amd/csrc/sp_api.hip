@@ -98,6 +98,7 @@ WsLayout make_ws_layout(const sp_config& c, int total_tokens, int batch)
     W.cg = take(K * crows * F * ab);
     W.cqt = take(K * crows * (size_t)c.heads * H * ab);
     W.cxb = take(K * crows * (size_t)c.heads * H * ab);
+    W.part = take(K * (size_t)kSplitMax * kSplitRows * H * 4);
     W.crows = (int)crows;
     W.end = o;
     W.rows = (int)rows;
@@ -244,6 +245,17 @@ static int run_forward(const sp_model* M, const int32_t* ids, const int32_t* cu,
     const int nh = c.heads;
     const size_t cH = (size_t)crows * H * ab, cF = (size_t)crows * F * ab, cHH = (size_t)crows * nh * H;   // cHH: elements
     bool compact_final = false;
+    // Calls of a few dozen tokens: split the reduction range of the two projections that are followed by a LayerNorm
+    // (largest slice count that leaves every slice at least two 64-wide k-tiles).
+    float* part = (float*)(w + W.part);
+    const size_t slice = (size_t)kSplitRows * H;
+    int split_o = 1, split_d = 1;
+    if (c.dtype == SP_DTYPE_BF16 && mrows <= kSplitRows) {
+        for (int sp = kSplitMax; sp > 1; --sp) {
+            if (split_o == 1 && (H / 64) % sp == 0 && H / 64 / sp >= 2) split_o = sp;
+            if (split_d == 1 && (F / 64) % sp == 0 && F / 64 / sp >= 2) split_d = sp;
+        }
+    }
     for (int l = 0; l < stop_layers; ++l) {
         const size_t lo = L.layer0 + (size_t)l * L.layer_stride;
         if (first_only && l == c.layers - 1) {
@@ -286,19 +298,35 @@ static int run_forward(const sp_model* M, const int32_t* ids, const int32_t* cu,
         SP_MARK(SP_PHASE_QKV);
         SP_TRY(launch_attention(M, qkv, vt, att, cu, B, T, max_seqlen, rows, k, s));
         SP_MARK(SP_PHASE_ATTENTION);
-        SP_TRY(launch_gemm(M, att, H, lo + L.wo, lo + L.bo, u, H, x, H, mrows, H, H, k, EPI_BIAS_RESIDUAL, sH, sH, sH,
-                           s));
-        SP_MARK(SP_PHASE_OPROJ);
-        SP_TRY(launch_layernorm(M, u, x1, rows, mrows, k, lo + L.ln1g, lo + L.ln1b, s));
-        SP_MARK(SP_PHASE_LAYERNORM);
+        if (split_o > 1) {
+            // few tokens: the reduction range is split over workgroups, and the slices are added together with the
+            // bias, the residual and the LayerNorm
+            SP_TRY(launch_gemm_splitk(M, att, H, lo + L.wo, part, mrows, H, H, k, split_o, sH, slice, s));
+            SP_MARK(SP_PHASE_OPROJ);
+            SP_TRY(launch_ln_reduce(M, part, split_o, slice, lo + L.bo, x, x1, rows, mrows, k, lo + L.ln1g, lo + L.ln1b, s));
+            SP_MARK(SP_PHASE_LAYERNORM);
+        } else {
+            SP_TRY(launch_gemm(M, att, H, lo + L.wo, lo + L.bo, u, H, x, H, mrows, H, H, k, EPI_BIAS_RESIDUAL, sH, sH, sH,
+                               s));
+            SP_MARK(SP_PHASE_OPROJ);
+            SP_TRY(launch_layernorm(M, u, x1, rows, mrows, k, lo + L.ln1g, lo + L.ln1b, s));
+            SP_MARK(SP_PHASE_LAYERNORM);
+        }
         SP_TRY(launch_gemm(M, x1, H, lo + L.w1, lo + L.b1, g, F, nullptr, 0, mrows, F, H, k, EPI_BIAS_GELU, sH, sF, 0,
                            s));
         SP_MARK(SP_PHASE_FFN_UP);
-        SP_TRY(launch_gemm(M, g, F, lo + L.w2, lo + L.b2, u, H, x1, H, mrows, H, F, k, EPI_BIAS_RESIDUAL, sF, sH, sH,
-                           s));
-        SP_MARK(SP_PHASE_FFN_DOWN);
-        SP_TRY(launch_layernorm(M, u, x, rows, mrows, k, lo + L.ln2g, lo + L.ln2b, s));
-        SP_MARK(SP_PHASE_LAYERNORM);
+        if (split_d > 1) {
+            SP_TRY(launch_gemm_splitk(M, g, F, lo + L.w2, part, mrows, H, F, k, split_d, sF, slice, s));
+            SP_MARK(SP_PHASE_FFN_DOWN);
+            SP_TRY(launch_ln_reduce(M, part, split_d, slice, lo + L.b2, x1, x, rows, mrows, k, lo + L.ln2g, lo + L.ln2b, s));
+            SP_MARK(SP_PHASE_LAYERNORM);
+        } else {
+            SP_TRY(launch_gemm(M, g, F, lo + L.w2, lo + L.b2, u, H, x1, H, mrows, H, F, k, EPI_BIAS_RESIDUAL, sF, sH, sH,
+                               s));
+            SP_MARK(SP_PHASE_FFN_DOWN);
+            SP_TRY(launch_layernorm(M, u, x, rows, mrows, k, lo + L.ln2g, lo + L.ln2b, s));
+            SP_MARK(SP_PHASE_LAYERNORM);
+        }
     }
     if (with_head) {
         if (compact_final) {

@@ -177,6 +177,48 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const char* arena, size_
     }
 }
 
+// Sum of the slices of a split reduction + bias + residual, then LayerNorm: one wave per row.
+template <typename T, int MAXC>
+__global__ __launch_bounds__(256) void ln_reduce_kernel(const char* arena, size_t student_stride, size_t g_off,
+                                                        size_t b_off, size_t bias_off, const float* __restrict__ part,
+                                                        int splits, size_t slice_elems, const T* __restrict__ res,
+                                                        T* __restrict__ out, int rows, int mrows, int H, float eps)
+{
+    const int m = blockIdx.y, lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= mrows) return;
+    const int nch = H >> 3;
+    const char* sb = arena + (size_t)m * student_stride;
+    float gg[MAXC][8], bb[MAXC][8];
+    load_gamma_beta<MAXC>((const float*)(sb + g_off), (const float*)(sb + b_off), nch, lane, gg, bb);
+    const float* bias = (const float*)(sb + bias_off);
+    const T* rrow = res + ((size_t)m * rows + row) * H;
+    const float* prow = part + (size_t)m * splits * slice_elems + (size_t)row * H;
+    float v[MAXC][8];
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+        const int c = lane + 64 * i;
+        if (c < nch) {
+            float r8[8], b8[8];
+            load8(rrow + c * 8, r8);
+            load8(bias + c * 8, b8);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[i][e] = r8[e] + b8[e];
+            float p8[kSplitMax][8];                           // all slices requested at once, added in ascending order
+#pragma unroll
+            for (int sidx = 0; sidx < kSplitMax; ++sidx)
+                if (sidx < splits) load8(prow + (size_t)sidx * slice_elems + c * 8, p8[sidx]);
+#pragma unroll
+            for (int sidx = 0; sidx < kSplitMax; ++sidx)
+                if (sidx < splits) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) v[i][e] += p8[sidx][e];
+                }
+        }
+    }
+    ln_row_store<T, MAXC>(v, nch, lane, H, gg, bb, eps, out + ((size_t)m * rows + row) * H);
+}
+
 // First-token rows: one wave per (student, sequence).
 template <typename T>
 __global__ __launch_bounds__(256) void gather_first_kernel(const T* __restrict__ x, const int32_t* __restrict__ cu, int B,
@@ -236,8 +278,8 @@ __global__ __launch_bounds__(256) void head_pool_kernel(const char* arena, size_
 #pragma unroll
     for (int s = 0; s < kSeqPerWg; ++s) acc[s] = 0.f;
     const int per = H / 4, i0 = part * per;   // this wave's share of the reduction index (a multiple of 16)
-#pragma unroll 4
-    for (int i = i0; i < i0 + per; i += 4) {     // unrolled: sixteen weight loads in flight per lane
+#pragma unroll 8
+    for (int i = i0; i < i0 + per; i += 4) {     // unrolled: 32 weight loads in flight per lane
         float w[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) w[e] = (float)Wp[(size_t)(i + e) * H + n];
@@ -266,22 +308,35 @@ __global__ __launch_bounds__(256) void head_pool_kernel(const char* arena, size_
 }
 
 // Stage 2: z[m][b][c] = bc[m][c] + sum over slices (ascending); logits[b][c] = sum_m z (m ascending).
-__global__ void head_sum_kernel(const char* arena, size_t student_stride, size_t bc_off,
-                                const float* __restrict__ zpart, int B, int C, int k, int nslice,
-                                float* __restrict__ z, float* __restrict__ logits)
+// 256 threads = 8 student lanes x 32 outputs: the students' slice sums run in parallel, the sum over students is taken
+// in order by the first lane of each output.
+constexpr int kSumStudents = 64;   // most students (sp_config.K is capped at this)
+
+__global__ __launch_bounds__(256) void head_sum_kernel(const char* arena, size_t student_stride, size_t bc_off,
+                                                       const float* __restrict__ zpart, int B, int C, int k, int nslice,
+                                                       float* __restrict__ z, float* __restrict__ logits)
 {
-    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= B * C) return;
-    const int c = idx % C;
-    float total = 0.f;
-    for (int m = 0; m < k; ++m) {
+    __shared__ float zs[kSumStudents][32];
+    const int ox = threadIdx.x & 31, my = threadIdx.x >> 5;
+    const int idx = blockIdx.x * 32 + ox;
+    const bool live = idx < B * C;
+    const int c = live ? idx % C : 0;
+    for (int m = my; m < k; m += 8) {
         float zm = 0.f;
-        for (int sl = 0; sl < nslice; ++sl) zm += zpart[((size_t)m * nslice + sl) * B * C + idx];
-        zm += ((const float*)(arena + (size_t)m * student_stride + bc_off))[c];
-        z[(size_t)m * B * C + idx] = zm;
-        total += zm;
+        if (live) {
+#pragma unroll 4
+            for (int sl = 0; sl < nslice; ++sl) zm += zpart[((size_t)m * nslice + sl) * B * C + idx];
+            zm += ((const float*)(arena + (size_t)m * student_stride + bc_off))[c];
+            z[(size_t)m * B * C + idx] = zm;
+        }
+        zs[m][ox] = zm;
     }
-    logits[idx] = total;
+    __syncthreads();
+    if (my == 0 && live) {
+        float total = 0.f;
+        for (int m = 0; m < k; ++m) total += zs[m][ox];
+        logits[idx] = total;
+    }
 }
 
 // Classifier on pooled rows and the cross-student sum: one workgroup per sequence, wave w takes students w, w + 4, ...
@@ -368,6 +423,24 @@ hipError_t launch_layernorm(const sp_model* M, const void* u, void* out, int row
     return hipGetLastError();
 }
 
+hipError_t launch_ln_reduce(const sp_model* M, const float* partials, int splits, size_t slice_elems, size_t bias_off,
+                            const void* residual, void* out, int rows, int mrows, int k, size_t g_off, size_t b_off,
+                            hipStream_t s)
+{
+    const sp_config& c = M->cfg;
+    if (c.dtype != SP_DTYPE_BF16 || splits < 1 || splits > kSplitMax) return hipErrorInvalidValue;
+    dim3 grid((mrows + 3) / 4, k);
+    const int maxc = (c.hidden / 8 + 63) / 64;
+    if (maxc > kMaxChunks) return hipErrorInvalidValue;
+#define SP_LNR(MAXC)                                                                                               \
+    hipLaunchKernelGGL((ln_reduce_kernel<bf16, MAXC>), grid, dim3(256), 0, s, M->arena, M->L.student_stride, g_off, \
+                       b_off, bias_off, partials, splits, slice_elems, (const bf16*)residual, (bf16*)out, rows, mrows, \
+                       c.hidden, c.ln_eps)
+    if (maxc <= 1) SP_LNR(1); else if (maxc == 2) SP_LNR(2); else SP_LNR(4);
+#undef SP_LNR
+    return hipGetLastError();
+}
+
 hipError_t launch_gather_first(const sp_model* M, const void* x, const int32_t* cu, int B, int T, int rows, void* xc,
                                void* attc, int crows, int cmrows, int k, hipStream_t s)
 {
@@ -399,7 +472,8 @@ hipError_t launch_head(const sp_model* M, const void* x, const int32_t* cu, int 
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int n = B * c.classes;
-    hipLaunchKernelGGL(head_sum_kernel, dim3((n + 255) / 256), dim3(256), 0, s, M->arena, L.student_stride, L.bc,
+    if (k > kSumStudents) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(head_sum_kernel, dim3((n + 31) / 32), dim3(256), 0, s, M->arena, L.student_stride, L.bc,
                        zpart, B, c.classes, k, nslice, z, logits);
     return hipGetLastError();
 }

@@ -89,7 +89,8 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
                                                            size_t w_off, size_t b_off, bf16* __restrict__ out, int ldo,
                                                            size_t o_ss, const bf16* __restrict__ res, int ldr,
                                                            size_t r_ss, int Kd, int mtiles, int ntiles, int total,
-                                                           bf16* __restrict__ out2, int n_split, int ld2, size_t o2_ss)
+                                                           bf16* __restrict__ out2, int n_split, int ld2, size_t o2_ss,
+                                                           int ksplit, int ldw)
 {
     using G = GemmTile<BM, BN>;
     constexpr int BK = G::BK, NS = G::NS, STEPS = G::STEPS, LSPREAD = G::LSPREAD;
@@ -106,24 +107,27 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
     const int chunk = (total + 7) >> 3;
     const int lin = (int)(blockIdx.x & 7) * chunk + (int)(blockIdx.x >> 3);
     if (lin >= total) return;
-    const int nt = lin % ntiles, mt = (lin / ntiles) % mtiles, m = lin / (ntiles * mtiles);
+    // (student, slice of the reduction range, token tile, feature tile); ksplit > 1 only with EPI_PARTIAL, where a
+    // workgroup reduces over Kd elements starting at sp * Kd and the slices are added by a later kernel
+    const int nt = lin % ntiles, mt = (lin / ntiles) % mtiles, sp = (lin / (ntiles * mtiles)) % ksplit;
+    const int m = lin / (ntiles * mtiles * ksplit);
     const int m0 = mt * BM, n0 = nt * BN;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave & 1, wn = wave >> 1;
-    const bf16* Ag = A + (size_t)m * a_ss + (size_t)m0 * lda;
-    const bf16* Wg = (const bf16*)(arena + (size_t)m * student_stride + w_off) + (size_t)n0 * Kd;
+    const bf16* Ag = A + (size_t)m * a_ss + (size_t)m0 * lda + (size_t)sp * Kd;
+    const bf16* Wg = (const bf16*)(arena + (size_t)m * student_stride + w_off) + (size_t)n0 * ldw + (size_t)sp * Kd;
 
     // loader: lane -> (row lane / 8 of the wave-load, LDS slot lane % 8); it fetches k-chunk slot ^ key(row)
     const int lrow = lane >> 3, lslot = lane & 7;
     const int lchunk = lslot ^ ((4 * wave + (lrow >> 1)) & 7);
     const bf16* a_src = Ag + (size_t)(wave * 8 + lrow) * lda + lchunk * 8;
-    const bf16* w_src = Wg + (size_t)(wave * 8 + lrow) * Kd + lchunk * 8;
+    const bf16* w_src = Wg + (size_t)(wave * 8 + lrow) * ldw + lchunk * 8;
     auto issue1 = [&](int i, int k0, int stage) {           // i-th wave-load of a stage (activation rows first)
         if (i < LA)
             __builtin_amdgcn_global_load_lds((gbl_void*)(a_src + (size_t)i * 32 * lda + k0),
                                              (lds_void*)(smem + stage * STAGE + (wave + i * 4) * 64), 16, 0, 0);
         else
-            __builtin_amdgcn_global_load_lds((gbl_void*)(w_src + (size_t)(i - LA) * 32 * Kd + k0),
+            __builtin_amdgcn_global_load_lds((gbl_void*)(w_src + (size_t)(i - LA) * 32 * ldw + k0),
                                              (lds_void*)(smem + stage * STAGE + BM * 8 + (wave + (i - LA) * 4) * 64),
                                              16, 0, 0);
     };
@@ -136,7 +140,8 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
 #pragma unroll
         for (int i = 0; i < TN; ++i)
 #pragma unroll
-            for (int v4 = 0; v4 < 4; ++v4) b4[i][v4] = *(const f32x4*)(bias + i * 32 + 8 * v4);
+            for (int v4 = 0; v4 < 4; ++v4)
+                b4[i][v4] = EPI == EPI_PARTIAL ? f32x4{0.f, 0.f, 0.f, 0.f} : *(const f32x4*)(bias + i * 32 + 8 * v4);
     }
 
     // Epilogue staging geometry (used early by the residual prefetch).
@@ -266,6 +271,19 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
     // feature = 8 * (v / 4) + 4 * (l / 32) + v % 4 inside the 32x32 block.
     // The barrier in the last step of the last k-tile already separates every fragment read from what follows:
     // the ring is free.
+    if (EPI == EPI_PARTIAL) {
+        // fp32 partial sums of this slice of the reduction range: out[(m * ksplit + sp)][row][feature], no bias
+        float* po = (float*)out + ((size_t)m * ksplit + sp) * o_ss + (row0 + j31) * ldo + col0 + 4 * g;
+#pragma unroll
+        for (int jj = 0; jj < TM; ++jj)
+#pragma unroll
+            for (int i = 0; i < TN; ++i)
+#pragma unroll
+                for (int v4 = 0; v4 < 4; ++v4)
+                    *(f32x4*)(po + (size_t)jj * 32 * ldo + i * 32 + 8 * v4) =
+                        f32x4{acc[i][jj][4 * v4], acc[i][jj][4 * v4 + 1], acc[i][jj][4 * v4 + 2], acc[i][jj][4 * v4 + 3]};
+        return;
+    }
     if (EPI == EPI_BIAS_RESIDUAL) issue_residual(1);
     // EPI_QKV: feature tiles at or beyond n_split (the value projection) are staged feature-major and written
     // transposed, out2[feature - n_split][token]; the choice is uniform over the workgroup.
@@ -407,9 +425,11 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
 template <int BM, int BN, int EPI>
 hipError_t launch_bf16_tile(const sp_model* M, const void* A, int lda, size_t w_off, size_t b_off, void* out, int ldo,
                             const void* residual, int ldr, int mrows, int N, int Kd, int k, size_t a_ss, size_t o_ss,
-                            size_t r_ss, hipStream_t s, void* out2, int n_split, int ld2, size_t o2_ss)
+                            size_t r_ss, hipStream_t s, void* out2, int n_split, int ld2, size_t o2_ss, int ksplit = 1,
+                            int ldw = 0)
 {
     static_assert(BM == BN, "the transposed epilogue assumes a square wave tile");
+    if (ldw == 0) ldw = Kd;
     constexpr size_t smem = GemmTile<BM, BN>::smem_bytes;
     auto kern = gemm_bf16_kernel<BM, BN, EPI>;
     if (smem > 48 * 1024) {
@@ -420,11 +440,13 @@ hipError_t launch_bf16_tile(const sp_model* M, const void* A, int lda, size_t w_
             raised = true;
         }
     }
-    const int mtiles = mrows / BM, ntiles = N / BN, total = k * mtiles * ntiles;
+    const int mtiles = mrows / BM, ntiles = N / BN, total = k * ksplit * mtiles * ntiles;
     const int grid = ((total + 7) / 8) * 8;
+    // (o_ss: bytes per student for the bf16 epilogues, fp32 elements per slice for EPI_PARTIAL)
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), smem, s, (const bf16*)A, lda, a_ss / 2, M->arena,
-                       M->L.student_stride, w_off, b_off, (bf16*)out, ldo, o_ss / 2, (const bf16*)residual, ldr,
-                       r_ss / 2, Kd, mtiles, ntiles, total, (bf16*)out2, n_split, ld2, o2_ss / 2);
+                       M->L.student_stride, w_off, b_off, (bf16*)out, ldo, EPI == EPI_PARTIAL ? o_ss : o_ss / 2,
+                       (const bf16*)residual, ldr, r_ss / 2, Kd, mtiles, ntiles, total, (bf16*)out2, n_split, ld2,
+                       o2_ss / 2, ksplit, ldw);
     return hipGetLastError();
 }
 
@@ -457,6 +479,16 @@ hipError_t launch_f32(const sp_model* M, const void* A, int lda, size_t w_off, s
 }
 
 }  // namespace
+
+hipError_t launch_gemm_splitk(const sp_model* M, const void* A, int lda, size_t w_off, float* partials, int mrows, int N,
+                              int Kd, int k, int splits, size_t a_student_stride, size_t slice_elems, hipStream_t s)
+{
+    if (M->cfg.dtype != SP_DTYPE_BF16 || splits < 1 || mrows % 64 || N % 64 || Kd % (64 * splits) || Kd / splits < 128 ||
+        slice_elems < (size_t)mrows * N)
+        return hipErrorInvalidValue;
+    return launch_bf16_tile<64, 64, EPI_PARTIAL>(M, A, lda, w_off, 0, partials, N, nullptr, 0, mrows, N, Kd / splits, k,
+                                                 a_student_stride, slice_elems, 0, s, nullptr, 0, 0, 0, splits, Kd);
+}
 
 hipError_t launch_gemm(const sp_model* M, const void* A, int lda, size_t w_off, size_t b_off, void* out, int ldo,
                        const void* residual, int ldr, int mrows, int N, int Kd, int k, Epilogue epi,

@@ -17,6 +17,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kRowPad = 256;  // activation rows per student are padded to a multiple of this
+constexpr int kSplitMax = 8;  // slices of a split reduction (small calls only)
+constexpr int kSplitRows = 128;   // most token rows a call may compute and still take the split path
 
 // Byte offsets of every tensor inside one student's slab of the weight arena.
 // The encoder matrices are stored transposed with respect to the host blob,
@@ -39,6 +41,7 @@ struct WsLayout {
     size_t x, qkv, vt, att, u, x1, g, z, zpart, end;
     size_t cx, cq, catt, cu_, cx1, cg;   // first-token rows only: [K][crows][H] (cg: [F]), last layer
     size_t cqt, cxb;                     // folded queries / weighted mean rows: [K][crows][heads][H]
+    size_t part;                         // fp32 partial sums of split reductions: [K][kSplitMax][kSplitRows][H]
     int rows, crows;
     int act_bytes;
 };
@@ -67,7 +70,7 @@ hipError_t launch_layernorm(const sp_model* M, const void* u, void* out, int row
 
 // EPI_QKV (bf16 path only): bias; output columns >= n_split (the value projection) are written transposed,
 // out2[m][column - n_split][row], so that attention reads key-contiguous value tiles.
-enum Epilogue { EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_BIAS_RESIDUAL = 2, EPI_QKV = 3, EPI_BIAS_TANH = 4 };
+enum Epilogue { EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_BIAS_RESIDUAL = 2, EPI_QKV = 3, EPI_BIAS_TANH = 4, EPI_PARTIAL = 5 };
 
 // out[m][row][0..N) = epi(A[m][row][0..Kd) . W^T + bias), W stored [N][Kd] at w_off of each student.
 // lda / ldo / ldr are row strides in elements; residual may be null unless EPI_BIAS_RESIDUAL;
@@ -76,6 +79,18 @@ hipError_t launch_gemm(const sp_model* M, const void* A, int lda, size_t w_off, 
                        const void* residual, int ldr, int mrows, int N, int Kd, int k, Epilogue epi,
                        size_t a_student_stride, size_t o_student_stride, size_t r_student_stride, hipStream_t s,
                        void* out2 = nullptr, int n_split = 0, int ld2 = 0, size_t o2_student_stride = 0);
+
+// Split reduction for calls of a few dozen tokens, where one workgroup per 64x64 output tile walking the whole
+// reduction range is a long serial chain: partials[m][s][row][0..N) = A[m][row][s*Kd/splits ..) . W^T (fp32, no bias),
+// s < splits; slice_elems = elements between consecutive slices (>= mrows * N).  bf16 path only.
+hipError_t launch_gemm_splitk(const sp_model* M, const void* A, int lda, size_t w_off, float* partials, int mrows, int N,
+                              int Kd, int k, int splits, size_t a_student_stride, size_t slice_elems, hipStream_t s);
+
+// out[m][row][:] = LN(sum_s partials[m][s][row][:] + bias + residual[m][row][:]; g, b): the reduction of
+// launch_gemm_splitk fused with the bias, the residual add and the LayerNorm that follow the projection.
+hipError_t launch_ln_reduce(const sp_model* M, const float* partials, int splits, size_t slice_elems, size_t bias_off,
+                            const void* residual, void* out, int rows, int mrows, int k, size_t g_off, size_t b_off,
+                            hipStream_t s);
 
 // att[m][t][h*64..] = softmax(q k^T / 8) v inside each sequence; qkv rows are [q | k | v] of width 3H.
 // bf16 path: the values are read from vt[m][H][rows] (transposed) instead of the third slice of qkv.
