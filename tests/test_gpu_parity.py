@@ -166,6 +166,34 @@ def test_first_token_last_layer_matches_all_tokens(sp, oracle64):
     assert rel_err(got[False], got[True]) < 1e-2
 
 
+FIRST_EDGE_CASES = {
+    # the longest sequence the one-query attention kernel takes, the shortest possible ones, a ragged mix
+    "len512_and_len1": [512, 1, 1, 2, 257, 33, 128, 129, 64, 7],
+    # every sequence is a single token (its own first token): 1100 sequences, not a multiple of any tile
+    "all_single_tokens": [1] * 1100,
+    # a sequence longer than that kernel's limit: the call must take the all-token last layer and still be right
+    "len600_falls_back": [600, 5, 300, 150, 31],
+}
+
+
+@pytest.mark.parametrize("case", list(FIRST_EDGE_CASES))
+def test_first_token_edge_cases(sp, oracle64, case):
+    """Calls of >= 1024 tokens at the edges of the first-token last layer: longest / shortest sequences, a batch of
+    single tokens, and a sequence beyond its length limit (fallback to the all-token layer)."""
+    shape = synth.StudentShape(K=2, layers=2, hidden=256, heads=4, ffn=512, vocab=100, max_pos=640, classes=3,
+                               dtype="bf16")
+    rng = np.random.default_rng(29)
+    lengths = np.array(FIRST_EDGE_CASES[case], dtype=np.int32)
+    assert lengths.sum() >= 1024
+    ids = synth.make_ids(rng, int(lengths.sum()), shape.vocab)
+    blob = synth.make_weights(rng, shape, std=0.05, ln_random=True, qk_std=0.1)
+    st = sp.Students(sp.config_from_shape(shape), blob)
+    d_ids, d_cu, cu = gpu_inputs(lengths, ids, sp)
+    got = st.sp_forward(d_ids, d_cu, int(lengths.max()), shape.K).cpu().numpy().astype(np.float64)
+    want = oracle64.forward(ocfg(shape), oracle_weights(blob, shape), ids, cu, shape.K)
+    check_logits(got, want, shape, case)
+
+
 # ---- the other student shapes the paper uses (Table 2: 2L256D, its headline student; 6L768D; 12L1024D) -------------
 
 OTHER_SHAPES = {
