@@ -228,8 +228,10 @@ def main():
         "config": {"workload": "c4_burst_b256: K=8 students x 2 layers, hidden 768, 12 heads, FFN 3072, vocab 30522, "
                                "batch 256, lognormal lengths (median 48, sigma 0.6, clipped to [8,256]), k_active=8",
                    "total_tokens": T4, "batch": B4, "k_active": main_k,
-                   "variant": "last layer on first-token rows only (exact work saving); the projection and attention "
-                              "phases below are the all-token layer's launches alone"},
+                   "variant": "last layer on first-token rows only (exact work saving); active students run as two "
+                              "groups on two streams inside the call; phases_k8 is one single-stream forward with an "
+                              "event after every launch, its projection and attention phases are the all-token "
+                              "layer's launches alone"},
         "burst_all_token_last_layer_k8": all_tokens,
         "burst_by_k_active": {str(k): v for k, v in burst.items()},
         "latency_batch1_by_k_active": {str(k): v for k, v in latency.items()},

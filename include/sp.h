@@ -55,12 +55,20 @@ typedef struct {
                          LayerNorm statistics, softmax, GELU, pooling and logits */
     float ln_eps;     /* LayerNorm epsilon (BERT: 1e-12) */
     int32_t last_layer_all_tokens;
-                      /* Only the first token of each sequence feeds the head, so after the last layer's
-                         key/value projections every other row is dead work.  0 (default): bf16 calls with
-                         >= 1024 tokens run the last layer's attention queries, output projection, FFN and
-                         LayerNorms on the first-token rows only (same results up to rounding order in
-                         attention).  1: every token goes through the whole last layer (what a stock BERT
-                         does; the fp32 path always does). */
+                      /* Only the first token of each sequence feeds the head (the pooled representation of
+                         Section 3.1), so in the last layer every other row is dead work.  0 (default): bf16
+                         calls with >= 1024 tokens compute the last layer for the first-token rows only:
+                         their queries are folded through the key projection, the other tokens' keys and
+                         values are never formed, and the output projection, FFN and LayerNorms run on
+                         `batch` rows (same function; the rounding points of attention differ).  1: every
+                         token goes through the whole last layer (what a stock BERT does; the fp32 path
+                         always does). */
+    int32_t single_stream;
+                      /* 0 (default): a call with >= 2048 tokens and k_active >= 2 runs the active students
+                         as two groups side by side, the second on a stream the model owns, forked from and
+                         joined to the caller's stream with events (the call stays asynchronous and can be
+                         captured in a graph; the logits are bit-identical to the single-stream result).
+                         1: everything is enqueued on the caller's stream. */
 } sp_config;
 
 typedef struct sp_model sp_model; /* opaque host-side handle */

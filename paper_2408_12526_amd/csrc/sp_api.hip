@@ -3,6 +3,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <mutex>
 #include <thread>
 #include <vector>
 
@@ -99,6 +100,7 @@ WsLayout make_ws_layout(const sp_config& c, int total_tokens, int batch)
     W.cqt = take(K * crows * (size_t)c.heads * H * ab);
     W.cxb = take(K * crows * (size_t)c.heads * H * ab);
     W.part = take(K * (size_t)kSplitMax * kSplitRows * H * 4);
+    W.lpart = take(2 * (size_t)batch * c.classes * 4);
     W.crows = (int)crows;
     W.end = o;
     W.rows = (int)rows;
@@ -204,28 +206,27 @@ struct PhaseTimer {
     void release() { for (int i = 0; i < n; ++i) (void)hipEventDestroy(ev[i]); n = 0; }
 };
 
-static int run_forward(const sp_model* M, const int32_t* ids, const int32_t* cu, int B, int T, int max_seqlen, int k,
-                       int stop_layers, bool with_head, void* ws, size_t ws_bytes, float* logits, hipStream_t s,
-                       PhaseTimer* pt = nullptr)
+// The forward of students [m0, m0 + k) of the model (k >= 1), all of it enqueued on stream s.  Every buffer of the
+// workspace is sliced per student, so groups of students can run side by side on different streams.  With
+// with_head the group's z rows are written; logits (the group's own sum, in student order) only if non-null.
+static int run_students(const sp_model* M0, const WsLayout& W, const int32_t* ids, const int32_t* cu, int B, int T,
+                        int max_seqlen, int m0, int k, int stop_layers, bool with_head, char* w, float* logits,
+                        hipStream_t s, PhaseTimer* pt)
 {
-    if (!M || !ids || !cu || !ws || (with_head && !logits)) return SP_EINVAL;
-    if (((uintptr_t)ws & 255) || ((uintptr_t)ids & 3) || ((uintptr_t)cu & 3) || ((uintptr_t)logits & 3)) return SP_EINVAL;
-    const sp_config& c = M->cfg;
-    if (B < 1 || T < B || max_seqlen < 1 || max_seqlen > c.max_pos || (int64_t)B * max_seqlen < T) return SP_ESHAPE;
-    if (k < 1 || k > c.K) return SP_EKACTIVE;
-    if (stop_layers < 0 || stop_layers > c.layers) return SP_EINVAL;
-    const WsLayout W = make_ws_layout(c, T, B);
-    if (ws_bytes < W.end) return SP_ENOMEM;
-
-    char* w = (char*)ws;
+    const sp_config& c = M0->cfg;
+    sp_model shifted = *M0;                 // launchers address student i of the group as arena + i * stride
+    shifted.arena = M0->arena + (size_t)m0 * M0->L.student_stride;
+    const sp_model* M = &shifted;
     const int H = c.hidden, F = c.ffn, rows = W.rows;
     // rows actually computed: the packed tokens rounded up to the token tile the GEMMs will use
     const int mtile = T > 256 ? 256 : (T > 64 ? 128 : 64);
     const int mrows = (T + mtile - 1) / mtile * mtile;
     const size_t ab = W.act_bytes;
-    void *x = w + W.x, *qkv = w + W.qkv, *vt = w + W.vt, *att = w + W.att, *u = w + W.u, *x1 = w + W.x1, *g = w + W.g;
-    float* z = (float*)(w + W.z);
     const size_t sH = (size_t)rows * H * ab, s3H = 3 * sH, sF = (size_t)rows * F * ab;
+    char *x = w + W.x + m0 * sH, *qkv = w + W.qkv + m0 * s3H, *vt = w + W.vt + m0 * sH, *att = w + W.att + m0 * sH;
+    char *u = w + W.u + m0 * sH, *x1 = w + W.x1 + m0 * sH, *g = w + W.g + m0 * sF;
+    float* z = (float*)(w + W.z) + (size_t)m0 * B * c.classes;
+    float* zpart = (float*)(w + W.zpart) + (size_t)m0 * (H / 64) * B * c.classes;
     const ArenaLayout& L = M->L;
 
 #define SP_TRY(expr) do { if ((expr) != hipSuccess) return SP_EHIP; } while (0)
@@ -240,15 +241,16 @@ static int run_forward(const sp_model* M, const int32_t* ids, const int32_t* cu,
     const int crows = W.crows;
     const int ctile = B > 256 ? 256 : (B > 64 ? 128 : 64);
     const int cmrows = (B + ctile - 1) / ctile * ctile;
-    void *cx = w + W.cx, *cq = w + W.cq, *catt = w + W.catt, *cu2 = w + W.cu_, *cx1 = w + W.cx1, *cg = w + W.cg;
-    void *cqt = w + W.cqt, *cxb = w + W.cxb;
     const int nh = c.heads;
     const size_t cH = (size_t)crows * H * ab, cF = (size_t)crows * F * ab, cHH = (size_t)crows * nh * H;   // cHH: elements
+    char *cx = w + W.cx + m0 * cH, *cq = w + W.cq + m0 * cH, *catt = w + W.catt + m0 * cH, *cu2 = w + W.cu_ + m0 * cH;
+    char *cx1 = w + W.cx1 + m0 * cH, *cg = w + W.cg + m0 * cF;
+    char *cqt = w + W.cqt + m0 * cHH * ab, *cxb = w + W.cxb + m0 * cHH * ab;
     bool compact_final = false;
     // Calls of a few dozen tokens: split the reduction range of the two projections that are followed by a LayerNorm
     // (largest slice count that leaves every slice at least two 64-wide k-tiles).
-    float* part = (float*)(w + W.part);
     const size_t slice = (size_t)kSplitRows * H;
+    float* part = (float*)(w + W.part) + (size_t)m0 * kSplitMax * slice;
     int split_o = 1, split_d = 1;
     if (c.dtype == SP_DTYPE_BF16 && mrows <= kSplitRows) {
         for (int sp = kSplitMax; sp > 1; --sp) {
@@ -334,11 +336,54 @@ static int run_forward(const sp_model* M, const int32_t* ids, const int32_t* cu,
             SP_TRY(launch_gemm(M, cx, H, L.wp_t, L.bp, cq, H, nullptr, 0, cmrows, H, H, k, EPI_BIAS_TANH, cH, cH, 0, s));
             SP_TRY(launch_head_classify(M, cq, B, crows, k, z, logits, s));
         } else
-            SP_TRY(launch_head(M, x, cu, B, T, rows, k, z, (float*)(w + W.zpart), logits, s));
+            SP_TRY(launch_head(M, x, cu, B, T, rows, k, z, zpart, logits, s));
         SP_MARK(SP_PHASE_HEAD);
     }
 #undef SP_MARK
 #undef SP_TRY
+    return SP_OK;
+}
+
+// Whole call: argument checks, then either all active students on the caller's stream, or, for large calls, two
+// halves of them side by side: the first on the caller's stream, the second on the model's auxiliary stream (forked
+// and joined with events, so the call stays asynchronous and capturable).  The matrix-core phases run at the
+// package power limit while the bandwidth-bound phases leave most of it unused; two groups of students drift out
+// of phase and fill each other's gaps (measured about 3 % on the burst workload; starting the second group late,
+// after the first group's first projection, measured no better).  The logits are summed over all
+// students in ascending order after the join, so the result does not depend on the grouping.
+static int run_forward(const sp_model* M, const int32_t* ids, const int32_t* cu, int B, int T, int max_seqlen, int k,
+                       int stop_layers, bool with_head, void* ws, size_t ws_bytes, float* logits, hipStream_t s,
+                       PhaseTimer* pt = nullptr)
+{
+    if (!M || !ids || !cu || !ws || (with_head && !logits)) return SP_EINVAL;
+    if (((uintptr_t)ws & 255) || ((uintptr_t)ids & 3) || ((uintptr_t)cu & 3) || ((uintptr_t)logits & 3)) return SP_EINVAL;
+    const sp_config& c = M->cfg;
+    if (B < 1 || T < B || max_seqlen < 1 || max_seqlen > c.max_pos || (int64_t)B * max_seqlen < T) return SP_ESHAPE;
+    if (k < 1 || k > c.K) return SP_EKACTIVE;
+    if (stop_layers < 0 || stop_layers > c.layers) return SP_EINVAL;
+    const WsLayout W = make_ws_layout(c, T, B);
+    if (ws_bytes < W.end) return SP_ENOMEM;
+    char* w = (char*)ws;
+
+    const bool two_groups = with_head && !pt && k >= 2 && T >= 2048 && !c.single_stream && M->aux;
+    if (!two_groups)
+        return run_students(M, W, ids, cu, B, T, max_seqlen, 0, k, stop_layers, with_head, w, logits, s, pt);
+
+    const int ka = (k + 1) / 2;
+    float* lpart = (float*)(w + W.lpart);
+    const size_t n = (size_t)B * c.classes;
+    std::lock_guard<std::mutex> hold(*M->mu);       // one fork/join at a time on the model's stream and events
+    if (hipEventRecord(M->ev_fork, s) != hipSuccess || hipStreamWaitEvent(M->aux, M->ev_fork, 0) != hipSuccess)
+        return SP_EHIP;
+    int rc = run_students(M, W, ids, cu, B, T, max_seqlen, 0, ka, stop_layers, true, w, lpart, s, nullptr);
+    const int rc2 = run_students(M, W, ids, cu, B, T, max_seqlen, ka, k - ka, stop_layers, true, w, lpart + n, M->aux,
+                                 nullptr);
+    // join even after an error, so that the auxiliary stream never runs on beyond the call
+    if (hipEventRecord(M->ev_join, M->aux) != hipSuccess || hipStreamWaitEvent(s, M->ev_join, 0) != hipSuccess)
+        return SP_EHIP;
+    if (rc == SP_OK) rc = rc2;
+    if (rc != SP_OK) return rc;
+    if (launch_sum_students((const float*)(w + W.z), (int)n, k, logits, s) != hipSuccess) return SP_EHIP;
     return SP_OK;
 }
 
@@ -411,6 +456,19 @@ int sp_load_students(const sp_config* cfg, const float* host_weights, size_t nfl
     }
     free(stage);
     if (rc != SP_OK) { delete m; return rc; }
+    // Auxiliary stream (default priority) and events for calls that run two groups of students side by side; without
+    // them every call stays on the caller's stream.
+    m->mu = new (std::nothrow) std::mutex;
+    if (m->mu && hipStreamCreateWithFlags(&m->aux, hipStreamNonBlocking) == hipSuccess) {
+        if (hipEventCreateWithFlags(&m->ev_fork, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&m->ev_join, hipEventDisableTiming) != hipSuccess) {
+            if (m->ev_fork) (void)hipEventDestroy(m->ev_fork);
+            (void)hipStreamDestroy(m->aux);
+            m->aux = nullptr; m->ev_fork = m->ev_join = nullptr;
+        }
+    } else {
+        m->aux = nullptr;
+    }
     *out = m;
     return SP_OK;
 }
@@ -454,7 +512,18 @@ int sp_forward_profiled(const sp_model* model, const int32_t* token_ids, const i
     return rc;
 }
 
-void sp_free(sp_model* model) { delete model; }
+void sp_free(sp_model* model)
+{
+    if (!model) return;
+    if (model->aux) {
+        (void)hipStreamSynchronize(model->aux);
+        (void)hipEventDestroy(model->ev_fork);
+        (void)hipEventDestroy(model->ev_join);
+        (void)hipStreamDestroy(model->aux);
+    }
+    delete model->mu;
+    delete model;
+}
 
 const char* sp_strerror(int code)
 {

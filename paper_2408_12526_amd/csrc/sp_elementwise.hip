@@ -339,6 +339,17 @@ __global__ __launch_bounds__(256) void head_sum_kernel(const char* arena, size_t
     }
 }
 
+// logits[i] = sum over students of z[m][i], m ascending.
+__global__ void sum_students_kernel(const float* __restrict__ z, int n, int k, float* __restrict__ logits)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    float total = 0.f;
+#pragma unroll 4
+    for (int m = 0; m < k; ++m) total += z[(size_t)m * n + i];
+    logits[i] = total;
+}
+
 // Classifier on pooled rows and the cross-student sum: one workgroup per sequence, wave w takes students w, w + 4, ...
 template <typename T>
 __global__ __launch_bounds__(256) void head_classify_kernel(const char* arena, size_t student_stride, size_t wc_off,
@@ -420,6 +431,12 @@ hipError_t launch_layernorm(const sp_model* M, const void* u, void* out, int row
         if (maxc <= 1) SP_LN(float, 1); else if (maxc == 2) SP_LN(float, 2); else SP_LN(float, 4);
     }
 #undef SP_LN
+    return hipGetLastError();
+}
+
+hipError_t launch_sum_students(const float* z, int n, int k, float* logits, hipStream_t s)
+{
+    hipLaunchKernelGGL(sum_students_kernel, dim3((n + 255) / 256), dim3(256), 0, s, z, n, k, logits);
     return hipGetLastError();
 }
 

@@ -6,6 +6,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "sp.h"
 
 namespace sp {
@@ -42,6 +44,7 @@ struct WsLayout {
     size_t cx, cq, catt, cu_, cx1, cg;   // first-token rows only: [K][crows][H] (cg: [F]), last layer
     size_t cqt, cxb;                     // folded queries / weighted mean rows: [K][crows][heads][H]
     size_t part;                         // fp32 partial sums of split reductions: [K][kSplitMax][kSplitRows][H]
+    size_t lpart;                        // per-group logit sums when two groups of students run side by side: [2][B][C]
     int rows, crows;
     int act_bytes;
 };
@@ -53,6 +56,10 @@ struct sp_model {
     sp_config cfg;
     char* arena;
     sp::ArenaLayout L;
+    // for calls that run two groups of students side by side (null: never)
+    hipStream_t aux = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    std::mutex* mu = nullptr;
 };
 
 namespace sp {
@@ -120,6 +127,9 @@ hipError_t launch_attention_first_fold(const sp_model* M, const void* x, const v
 // Head on pooled rows: z[m][b][c] = pooled[m][b] . Wc + bc; logits[b][c] = sum_{m<k} z[m][b][c] (m ascending).
 hipError_t launch_head_classify(const sp_model* M, const void* pooled, int B, int crows, int k, float* z, float* logits,
                                 hipStream_t s);
+
+// logits[i] = sum_{m<k} z[m][i], m ascending (i < n).
+hipError_t launch_sum_students(const float* z, int n, int k, float* logits, hipStream_t s);
 
 // z[m][b][c] = tanh(x[m][cu[b]] Wp + bp) Wc + bc (row b itself if cu is null) ; logits[b][c] = sum_{m<k} z[m][b][c] (m ascending).
 hipError_t launch_head(const sp_model* M, const void* x, const int32_t* cu, int B, int T, int rows, int k, float* z,

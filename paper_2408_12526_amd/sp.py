@@ -23,7 +23,7 @@ PHASES = ("embed", "qkv", "attention", "oproj", "layernorm", "ffn_up", "ffn_down
 class sp_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
                 ("K", "layers", "hidden", "heads", "ffn", "vocab", "max_pos", "classes", "dtype")] + [
-        ("ln_eps", C.c_float), ("last_layer_all_tokens", C.c_int32)]
+        ("ln_eps", C.c_float), ("last_layer_all_tokens", C.c_int32), ("single_stream", C.c_int32)]
 
 
 class sp_ws_layout(C.Structure):
@@ -71,15 +71,16 @@ def _check(rc: int) -> None:
 
 
 def make_config(K, layers, hidden, heads, ffn, vocab, max_pos, classes, dtype="bf16", ln_eps=1e-12,
-                last_layer_all_tokens=False) -> sp_config:
+                last_layer_all_tokens=False, single_stream=False) -> sp_config:
     return sp_config(K, layers, hidden, heads, ffn, vocab, max_pos, classes,
-                     SP_DTYPE_BF16 if dtype == "bf16" else SP_DTYPE_FP32, ln_eps, 1 if last_layer_all_tokens else 0)
+                     SP_DTYPE_BF16 if dtype == "bf16" else SP_DTYPE_FP32, ln_eps, 1 if last_layer_all_tokens else 0,
+                     1 if single_stream else 0)
 
 
-def config_from_shape(shape, last_layer_all_tokens=False) -> sp_config:
+def config_from_shape(shape, last_layer_all_tokens=False, single_stream=False) -> sp_config:
     """shape: any object with the StudentShape fields (see synth.py)."""
     return make_config(shape.K, shape.layers, shape.hidden, shape.heads, shape.ffn, shape.vocab, shape.max_pos,
-                       shape.classes, shape.dtype, shape.ln_eps, last_layer_all_tokens)
+                       shape.classes, shape.dtype, shape.ln_eps, last_layer_all_tokens, single_stream)
 
 
 def sp_blob_floats(cfg: sp_config) -> int:

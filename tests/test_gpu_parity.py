@@ -306,6 +306,21 @@ def test_prefix_property_and_determinism_at_full_size(sp):
             assert torch.equal(got, acc), f"k_active={k} is not the fixed-order prefix sum"
 
 
+def test_two_groups_of_students_bit_identical_to_single_stream(sp):
+    """Large calls run the active students as two groups on two streams; the logits are summed over all students in
+    ascending order afterwards, so they must equal the single-stream result bit for bit, for even and odd k_active."""
+    w, batch, _, st = loaded(sp, 4)
+    d_ids, d_cu, cu = gpu_inputs(batch.lengths, batch.ids, sp)
+    mx = int(batch.lengths.max())
+    _, blob = synth.make_workload(w)
+    single = sp.Students(sp.config_from_shape(w.shape, single_stream=True), blob)
+    for k in (8, 5, 2):
+        a = st.sp_forward(d_ids, d_cu, mx, k).cpu().numpy()
+        b = single.sp_forward(d_ids, d_cu, mx, k).cpu().numpy()
+        assert np.array_equal(a, b), f"k_active={k}: max diff {np.abs(a - b).max():.3e}"
+    single.close()
+
+
 def test_sample_is_independent_of_batch_mates(sp):
     """A sequence's logits do not depend on where it sits in the packed batch (bitwise in the fp32 path)."""
     w = synth.WORKLOADS[1]
