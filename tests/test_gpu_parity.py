@@ -321,6 +321,35 @@ def test_two_groups_of_students_bit_identical_to_single_stream(sp):
     single.close()
 
 
+def test_forward_can_be_captured_in_a_graph(sp):
+    """sp_forward only enqueues work (also when it forks to the model's second stream), so it can be captured; every
+    replay, with eager calls and synchronisations between them, must reproduce the eager logits bit for bit."""
+    w, batch, _, st = loaded(sp, 4)
+    d_ids, d_cu, cu = gpu_inputs(batch.lengths, batch.ids, sp)
+    mx, B = int(batch.lengths.max()), len(batch.lengths)
+    ws = st.workspace(int(cu[-1]), B)
+    out = torch.empty(B, w.shape.classes, dtype=torch.float32, device="cuda")
+    st.sp_forward(d_ids, d_cu, mx, 8, out, ws)
+    torch.cuda.synchronize()
+    ref = out.clone()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        st.sp_forward(d_ids, d_cu, mx, 8, out, ws, stream=side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        st.sp_forward(d_ids, d_cu, mx, 8, out, ws, stream=side)
+    torch.cuda.synchronize()
+    for i in range(3):
+        out.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref), f"replay {i}"
+        st.sp_forward(d_ids, d_cu, mx, 4, out, ws)     # eager work between the replays
+        torch.cuda.synchronize()
+
+
 def test_sample_is_independent_of_batch_mates(sp):
     """A sequence's logits do not depend on where it sits in the packed batch (bitwise in the fp32 path)."""
     w = synth.WORKLOADS[1]
