@@ -35,7 +35,7 @@ def percentile(xs, q):
 # HBM-side bytes of one launch of the FFN-up GEMM at k_active = 8 on the burst workload, from two rocprofv3 --pmc runs
 # (FETCH_SIZE, WRITE_SIZE) scaled by the same counters on a 1 GiB copy; the summary with the commands is
 # profiles/hbm_traffic_gemm_ffn_up_c4_burst_b256.txt.  A counter run cannot be made from inside the timed process.
-FFN_UP_HBM_BYTES_PER_LAUNCH = {"read": 1.298e9, "written": 7.298e8}
+FFN_UP_HBM_BYTES_PER_LAUNCH = {"read": 1.333e9, "written": 7.298e8}
 
 
 def gemm_flops(shape, tokens, k, layers):
@@ -76,6 +76,10 @@ def main():
     ap.add_argument("--burst-k", default=None,
                     help="comma-separated k_active values for the burst workload (default: 8,4,2); profiles of one "
                          "launch configuration use --burst-k 8")
+    ap.add_argument("--single-stream", action="store_true",
+                    help="load the students with sp_config.single_stream = 1: every call stays on one stream instead of "
+                         "running two groups of students side by side (the configuration the per-kernel profiles use: "
+                         "one launch of each kernel per layer, all active students in it)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device-to-device copy a few times (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -105,7 +109,7 @@ def main():
     batch4, blob4 = synth.make_workload(w4)
     cu4 = sp.sp_pack(batch4.lengths)
     T4, B4, mx4 = int(cu4[-1]), len(batch4.lengths), int(batch4.lengths.max())
-    st4 = sp.Students(sp.config_from_shape(w4.shape), blob4)
+    st4 = sp.Students(sp.config_from_shape(w4.shape, single_stream=args.single_stream), blob4)
     d_ids4, d_cu4 = torch.from_numpy(batch4.ids).to(dev), torch.from_numpy(cu4).to(dev)
     logits4 = torch.empty(B4, w4.shape.classes, dtype=torch.float32, device=dev)
     ws4 = st4.workspace(T4, B4)
@@ -160,7 +164,8 @@ def main():
                                       "frac": sum(gf.values()) / gemm_ms / 1e9 / PEAK_BF16_TFLOPS}
         phases["sum_ms"] = sum(acc.values())
         # the stock variant (every token through the whole last layer), for reference
-        st4a = sp.Students(sp.config_from_shape(w4.shape, last_layer_all_tokens=True), blob4)
+        st4a = sp.Students(sp.config_from_shape(w4.shape, last_layer_all_tokens=True, single_stream=args.single_stream),
+                           blob4)
         sec = timed_steps(st4a, d_ids4, d_cu4, mx4, 8, logits4, ws4, args.steps, args.warmup)
         all_tokens = {"ms_per_step": sec * 1e3, "sequences_per_s": B4 / sec}
         del st4a
@@ -228,10 +233,12 @@ def main():
         "config": {"workload": "c4_burst_b256: K=8 students x 2 layers, hidden 768, 12 heads, FFN 3072, vocab 30522, "
                                "batch 256, lognormal lengths (median 48, sigma 0.6, clipped to [8,256]), k_active=8",
                    "total_tokens": T4, "batch": B4, "k_active": main_k,
-                   "variant": "last layer on first-token rows only (exact work saving); active students run as two "
-                              "groups on two streams inside the call; phases_k8 is one single-stream forward with an "
-                              "event after every launch, its projection and attention phases are the all-token "
-                              "layer's launches alone"},
+                   "variant": "last layer on first-token rows only (exact work saving); "
+                              + ("every call on one stream" if args.single_stream else
+                                 "active students run as two groups on two streams inside the call")
+                              + "; phases_k8 and roofline: one single-stream forward with an event after every launch "
+                                "(all active students in each launch), projection and attention phases = the all-token "
+                                "layer's launches alone"},
         "burst_all_token_last_layer_k8": all_tokens,
         "burst_by_k_active": {str(k): v for k, v in burst.items()},
         "latency_batch1_by_k_active": {str(k): v for k, v in latency.items()},
