@@ -156,11 +156,18 @@ int sp_pack(const int32_t* lengths_host, int32_t batch, int32_t* cu_seqlens_host
  *   att  [rows][H]  attention output of the last layer run
  *   x1   [rows][H]  state after the attention block's LayerNorm
  *   g    [rows][F]  GELU(FFN up-projection)
- *   z    float32 [K][batch][C] per-student classifier outputs before the sum */
+ *   z    float32 [K][batch][C] per-student classifier outputs before the sum
+ * and, written only when the last layer ran on the first-token rows (see
+ * sp_config.last_layer_all_tokens; `x` then still holds the last layer's input), per
+ * student first_rows rows, row b = sequence b:
+ *   first_q    [first_rows][H]  the last layer's queries of the first tokens
+ *   first_att  [first_rows][H]  its attention output for the first tokens */
 typedef struct {
     size_t x, qkv, vt, att, x1, g, z;
     int32_t rows;      /* padded token rows per student */
     int32_t act_bytes; /* 4 or 2 */
+    size_t first_q, first_att;
+    int32_t first_rows;
 } sp_ws_layout;
 int sp_workspace_layout(const sp_config* cfg, int32_t total_tokens, int32_t batch, sp_ws_layout* out);
 

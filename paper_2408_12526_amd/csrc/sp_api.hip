@@ -333,8 +333,10 @@ static int run_students(const sp_model* M0, const WsLayout& W, const int32_t* id
     if (with_head) {
         if (compact_final) {
             // pooler as one more student-grouped projection (tanh epilogue) on the first-token rows, then the classifier
-            SP_TRY(launch_gemm(M, cx, H, L.wp_t, L.bp, cq, H, nullptr, 0, cmrows, H, H, k, EPI_BIAS_TANH, cH, cH, 0, s));
-            SP_TRY(launch_head_classify(M, cq, B, crows, k, z, logits, s));
+            // (into the pre-LayerNorm scratch rows, which are free by now: the queries and the attention output of the
+            // first tokens stay readable after the call)
+            SP_TRY(launch_gemm(M, cx, H, L.wp_t, L.bp, cu2, H, nullptr, 0, cmrows, H, H, k, EPI_BIAS_TANH, cH, cH, 0, s));
+            SP_TRY(launch_head_classify(M, cu2, B, crows, k, z, logits, s));
         } else
             SP_TRY(launch_head(M, x, cu, B, T, rows, k, z, zpart, logits, s));
         SP_MARK(SP_PHASE_HEAD);
@@ -418,6 +420,7 @@ int sp_workspace_layout(const sp_config* cfg, int32_t total_tokens, int32_t batc
     const WsLayout W = make_ws_layout(*cfg, total_tokens, batch);
     out->x = W.x; out->qkv = W.qkv; out->vt = W.vt; out->att = W.att; out->x1 = W.x1; out->g = W.g; out->z = W.z;
     out->rows = W.rows; out->act_bytes = W.act_bytes;
+    out->first_q = W.cq; out->first_att = W.catt; out->first_rows = W.crows;
     return SP_OK;
 }
 

@@ -27,8 +27,9 @@ class sp_config(C.Structure):
 
 
 class sp_ws_layout(C.Structure):
-    _fields_ = [(n, C.c_size_t) for n in ("x", "qkv", "vt", "att", "x1", "g", "z")] + [("rows", C.c_int32),
-                                                                                   ("act_bytes", C.c_int32)]
+    _fields_ = [(n, C.c_size_t) for n in ("x", "qkv", "vt", "att", "x1", "g", "z")] + [
+        ("rows", C.c_int32), ("act_bytes", C.c_int32), ("first_q", C.c_size_t), ("first_att", C.c_size_t),
+        ("first_rows", C.c_int32)]
 
 
 def _load() -> C.CDLL:
@@ -179,6 +180,11 @@ class Students:
             n = self.cfg.K * batch * self.cfg.classes
             z = ws[lay.z:lay.z + 4 * n].view(torch.float32).view(self.cfg.K, batch, self.cfg.classes)
             return z[:k_active].double().cpu().numpy()
+        if name in ("first_q", "first_att"):        # compact rows of the first-token last layer: [k][batch][H]
+            off, dt = getattr(lay, name), (torch.bfloat16 if lay.act_bytes == 2 else torch.float32)
+            n = k_active * lay.first_rows * H
+            t = ws[off:off + n * lay.act_bytes].view(dt).view(k_active, lay.first_rows, H)
+            return t[:, :batch].double().cpu().numpy()
         width = {"x": H, "qkv": 3 * H, "att": H, "x1": H, "g": F}[name]
         off = getattr(lay, name)
         dt = torch.bfloat16 if lay.act_bytes == 2 else torch.float32

@@ -166,6 +166,46 @@ def test_first_token_last_layer_matches_all_tokens(sp, oracle64):
     assert rel_err(got[False], got[True]) < 1e-2
 
 
+def test_folded_first_token_attention_against_the_definition(sp, oracle64):
+    """The first-token last layer never forms keys and values (the query is folded through the key projection, the
+    value projection is applied to the weighted mean of the token rows).  Its attention output is checked against the
+    definition: keys and values projected by the oracle from the layer's own input rows as the HIP path left them,
+    softmax attention of the HIP path's own first-token queries over them."""
+    shape = synth.StudentShape(K=2, layers=2, hidden=256, heads=4, ffn=512, vocab=100, max_pos=320, classes=3,
+                               dtype="bf16")
+    rng = np.random.default_rng(27)
+    lengths = rng.integers(1, 130, size=30).astype(np.int32)
+    lengths[:4] = (300, 1, 129, 64)
+    assert lengths.sum() >= 1024
+    ids = synth.make_ids(rng, int(lengths.sum()), shape.vocab)
+    # score spread about 4 (query/key weights at 0.12): sharp enough that a wrong scale, mask or fold shows; the
+    # rounding of the folded query moves a score by about 2^-9 of its size, like the rounding of a key would
+    blob = synth.make_weights(rng, shape, std=0.08, ln_random=True, qk_std=0.12)
+    ow = oracle_weights(blob, shape)
+    st = sp.Students(sp.config_from_shape(shape), blob)
+    d_ids, d_cu, cu = gpu_inputs(lengths, ids, sp)
+    T, B, k, H = int(cu[-1]), len(lengths), shape.K, shape.hidden
+    ws = st.workspace(T, B)
+    st.sp_forward(d_ids, d_cu, int(lengths.max()), k, workspace=ws)
+    torch.cuda.synchronize()
+    x = st.read_activation(ws, "x", T, B, k)               # input of the last layer
+    q = st.read_activation(ws, "first_q", T, B, k)
+    got = st.read_activation(ws, "first_att", T, B, k)
+    p = f"l{shape.layers - 1}."
+    for m in range(k):
+        v = synth.student_views(ow, shape, m)
+        qref = oracle64.linear(x[m][cu[:-1]], v[p + "Wq"], v[p + "bq"])
+        assert rel_err(q[m], qref) < 1.2e-2, f"student {m}: first-token queries"
+        want = np.empty((B, H))
+        for b in range(B):
+            xs = x[m][cu[b]:cu[b + 1]]
+            keys, vals = oracle64.linear(xs, v[p + "Wk"], v[p + "bk"]), oracle64.linear(xs, v[p + "Wv"], v[p + "bv"])
+            qs = np.repeat(q[m][b][None, :], len(xs), axis=0)      # rows are independent: row 0 is the first token's
+            want[b] = oracle64.attention(qs, keys, vals, shape.heads)[0]
+        e = rel_err(got[m], want)
+        assert e < 1.2e-2, f"student {m}: folded first-token attention, rel err {e:.3e}"
+
+
 FIRST_EDGE_CASES = {
     # the longest sequence the one-query attention kernel takes, the shortest possible ones, a ragged mix
     "len512_and_len1": [512, 1, 1, 2, 257, 33, 128, 129, 64, 7],
