@@ -364,11 +364,17 @@ __global__ __launch_bounds__(256) void head_gemm_kernel(const bf16* __restrict__
                                                         const char* __restrict__ arena, size_t student_stride,
                                                         size_t w_off, size_t w_hs, int ldw, size_t b_off, size_t b_hs,
                                                         int has_bias, bf16* __restrict__ out, size_t o_ss, size_t o_hs,
-                                                        int ldo, int mtiles, int nstrips, int Kd)
+                                                        int ldo, int mtiles, int nstrips, int Kd, int heads, int total)
 {
-    const int m = blockIdx.z, h = blockIdx.y;
+    // XCD-aware order: consecutive workgroup ids go to different XCDs; each XCD gets a contiguous run of (student,
+    // head, group of four strips), so a head's weight slice is fetched into one L2 instead of all eight.
+    const int chunk = (total + 7) >> 3;
+    const int lin = (int)(blockIdx.x & 7) * chunk + (int)(blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= chunk || lin >= total) return;
+    const int per_head = (mtiles * nstrips + 3) / 4;
+    const int m = lin / (per_head * heads), h = (lin / per_head) % heads;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int item = blockIdx.x * 4 + wave;
+    const int item = (lin % per_head) * 4 + wave;
     if (item >= mtiles * nstrips) return;
     const int ns = item % nstrips, mt = item / nstrips;
     const int j31 = lane & 31, g = lane >> 5;
@@ -674,10 +680,11 @@ hipError_t launch_head_gemm(const sp_model* M, const void* A, size_t a_ss, size_
 #define SP_HEAD_GEMM(NT)                                                                                            \
     do {                                                                                                            \
         const int nstrips = N / (32 * NT);                                                                          \
-        dim3 grid((unsigned)((mtiles * nstrips + 3) / 4), (unsigned)c.heads, (unsigned)k);                          \
+        const int total = k * c.heads * ((mtiles * nstrips + 3) / 4);                                               \
+        dim3 grid((unsigned)((total + 7) / 8 * 8));                                                                 \
         hipLaunchKernelGGL(head_gemm_kernel<NT>, grid, dim3(256), 0, s, (const bf16*)A, a_ss, a_hs, lda, M->arena,  \
                            M->L.student_stride, w_off, w_hs, ldw, b_off, b_hs, has_bias ? 1 : 0, (bf16*)out, o_ss,  \
-                           o_hs, ldo, mtiles, nstrips, Kd);                                                         \
+                           o_hs, ldo, mtiles, nstrips, Kd, c.heads, total);                                         \
     } while (0)
     if (N % 128 == 0) SP_HEAD_GEMM(4);
     else if (N % 64 == 0) SP_HEAD_GEMM(2);
