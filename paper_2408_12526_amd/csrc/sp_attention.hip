@@ -36,6 +36,8 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(const bf16* __restr
     __shared__ __attribute__((aligned(16))) char sOut[4][32 * kOutPitch];   // per wave: 32 output rows
 
     const int m = blockIdx.y;
+    // plain order: the few long sequences are spread over the XCDs by the round-robin placement of workgroups; a
+    // contiguous run of sequences per XCD leaves them unevenly loaded and was measured 1.5x slower
     int idx = blockIdx.x;
     const int qc = idx % nqc; idx /= nqc;
     const int h = idx % heads;
@@ -204,7 +206,12 @@ __global__ __launch_bounds__(256, 3) void attention_bf16_short_kernel(const bf16
     __shared__ __attribute__((aligned(16))) bf16 sVt_all[4][kD * kSVStride];
 
     const int m = blockIdx.y;
-    const int b = blockIdx.x / ngroups, hg = blockIdx.x % ngroups;
+    // XCD-aware order (workgroup id mod 8 selects the XCD): each XCD takes a contiguous run of sequences, so that
+    // the lines of the token-contiguous value rows which neighbouring sequences share are fetched into one L2
+    const int total = B * ngroups, chunk = (total + 7) >> 3;
+    const int lin = (int)(blockIdx.x & 7) * chunk + (int)(blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= chunk || lin >= total) return;
+    const int b = lin / ngroups, hg = lin % ngroups;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int h = hg * 4 + wave;
     int t0 = cu[b], t1 = cu[b + 1];
@@ -648,7 +655,7 @@ hipError_t launch_attention(const sp_model* M, const void* qkv, const void* vt, 
         // tile iterations in one wave, a long tail behind the ~5 of a typical one.)
         const int kShortLen = 128;
         const int ngroups = (c.heads + 3) / 4;
-        hipLaunchKernelGGL(attention_bf16_short_kernel, dim3((unsigned)(B * ngroups), k), dim3(256), 0, s,
+        hipLaunchKernelGGL(attention_bf16_short_kernel, dim3((unsigned)((B * ngroups + 7) / 8 * 8), k), dim3(256), 0, s,
                            (const bf16*)qkv, (const bf16*)vt, (bf16*)att, cu, B, T, rows, c.hidden, c.heads, max_seqlen,
                            ngroups, kShortLen);
         if (max_seqlen > kShortLen) {
