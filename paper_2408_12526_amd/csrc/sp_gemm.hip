@@ -49,6 +49,11 @@ __device__ inline float gelu_erf_fast(float x)
 //     two k-steps (a burst of loads stalls the issuing wave behind the address unit's queue), and the
 //     fragments of k-step s + 1 are read while step s multiplies.  One barrier per 64-wide k-tile, placed where
 //     every wave already holds its last fragments of the tile in registers.
+//   * 256 x 256 tile: a wave stalls on its direct-to-LDS loads once more than about four of them per k-step are
+//     issued (the address unit's queue), and two stages force sixteen loads per k-tile into the two k-steps that
+//     leave them time to land.  Five slots of one operand tile each allow four loads in every k-step: the weight
+//     tile of k-tile j + 2 is requested when k-tile j is finished (into its activation slot), the activation tile
+//     of k-tile j + 2 already during k-tile j (into the weight slot of k-tile j - 1).
 //   * epilogue through LDS: each wave stages its sub-tile in its own slice of the ring, so that global writes are
 //     whole 16-byte-per-lane row segments.  Staged rows are unpadded and their 16-byte chunks XOR-swizzled by row,
 //     which lets the residual rows arrive by the same direct-to-LDS loads: half of them are requested before the
@@ -75,10 +80,13 @@ template <int BM, int BN>
 struct GemmTile {
     static constexpr int BK = 64, NS = 2, STEPS = 4, LSPREAD = 2;
     static constexpr int WTM = BM / 2, WTN = BN / 2;        // wave tile
-    static constexpr size_t ring_bytes = (size_t)NS * (BM + BN) * 8 * 16;
+    // The 256 x 256 tile keeps a ring of five operand tiles (256 rows x 64 reduction elements, 32 KB each: the whole
+    // LDS) instead of two stages of an activation and a weight tile; the smaller tiles use the two-stage ring.
+    static constexpr bool RING5 = BM == 256 && BN == 256;
+    static constexpr size_t ring_bytes = RING5 ? (size_t)5 * 256 * 8 * 16 : (size_t)NS * (BM + BN) * 8 * 16;
     // epilogue staging: wave w keeps rows [h * WTM / 2, (h + 1) * WTM / 2) of its sub-tile, WTN * 2 bytes each, in
-    // one half of the ring (= one stage)
-    static constexpr size_t half_bytes = ring_bytes / 2;
+    // one half of the staging area (= one stage of the two-stage ring, two slots of the five-slot ring)
+    static constexpr size_t half_bytes = (size_t)(BM + BN) * 8 * 16;
     static_assert(NS == 2 && (size_t)4 * (WTM / 2) * WTN * 2 <= half_bytes, "staging halves must fit the ring stages");
     static constexpr size_t smem_bytes = ring_bytes;
 };
@@ -160,7 +168,14 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
     const size_t row0 = (size_t)m0 + wm * WTM;
     const int col0 = n0 + wn * WTN;
     const int ha = (Kd / BK) & 1;                           // the ring stage that is idle during the last k-tile
-    auto half_ptr = [&](int h) { return (char*)smem + (size_t)(h ^ ha) * G::half_bytes + (size_t)wave * HR * ROWB; };
+    // five-slot ring: the last k-tile sits in slots sl, sl + 1 (mod 5).  Staging half 0 is a pair of adjacent slots
+    // among the other three (idle during the last k-tile), half 1 a pair among the rest (free once the loop is over).
+    const int sl = (2 * (Kd / BK - 1)) % 5;
+    const int hs0 = sl == 0 ? 2 : (sl == 1 ? 3 : (sl == 4 ? 1 : 0)), hs1 = sl <= 1 ? 0 : (sl == 4 ? 3 : 2);
+    auto half_ptr = [&](int h) {
+        const size_t hb = G::RING5 ? (size_t)(h ? hs1 : hs0) * (256 * 8 * 16) : (size_t)(h ^ ha) * G::half_bytes;
+        return (char*)smem + hb + (size_t)wave * HR * ROWB;
+    };
     auto swz = [](int r, int chunk) { return chunk ^ ((r >> KSH) & (CPR - 1)); };
     // Row-wise instructions (residual loads, output stores) move RPI whole staged rows each; the swizzle repeats
     // every 16 rows, so NQ per-lane offsets serve every 16-row period and the rest of the address is uniform.
@@ -186,90 +201,191 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
 
     int woff[TN], xoff[TM], wkey[TN], xkey[TM];
 #pragma unroll
-    for (int i = 0; i < TN; ++i) { const int r = wn * G::WTN + i * 32 + j31; woff[i] = BM * 8 + r * 8; wkey[i] = (r >> 1) & 7; }
+    for (int i = 0; i < TN; ++i) { const int r = wn * G::WTN + i * 32 + j31; woff[i] = (G::RING5 ? 0 : BM * 8) + r * 8; wkey[i] = (r >> 1) & 7; }
 #pragma unroll
     for (int j = 0; j < TM; ++j) { const int r = wm * G::WTM + j * 32 + j31; xoff[j] = r * 8; xkey[j] = (r >> 1) & 7; }
     bf16x8 fw[2][TN], fx[2][TM];
 
     const int nk = Kd / BK;
-#pragma unroll
-    for (int t = 0; t < NS; ++t)
-        if (t < nk)
-#pragma unroll
-            for (int i = 0; i < LPW; ++i) issue1(i, t * BK, t);
     f32x16 acc[TN][TM];
+    if constexpr (G::RING5) {
+        constexpr int SLOT = 256 * 8;                       // 16-byte units per slot
+        auto issue_a = [&](int i, int k0, int slot) {       // i-th of the 8 wave-loads of an activation tile
+            __builtin_amdgcn_global_load_lds((gbl_void*)(a_src + (size_t)i * 32 * lda + k0),
+                                             (lds_void*)(smem + slot * SLOT + (wave + i * 4) * 64), 16, 0, 0);
+        };
+        auto issue_w = [&](int i, int k0, int slot) {       // ... of a weight tile
+            __builtin_amdgcn_global_load_lds((gbl_void*)(w_src + (size_t)i * 32 * ldw + k0),
+                                             (lds_void*)(smem + slot * SLOT + (wave + i * 4) * 64), 16, 0, 0);
+        };
+        // k-tile t: activations in slot 2 t mod 5, weights in slot (2 t + 1) mod 5.  Start: both tiles of k-tiles 0
+        // and 1 and the activation tile of k-tile 2 (Kd is a multiple of 128, so there are at least two k-tiles).
 #pragma unroll
-    for (int i = 0; i < TN; ++i)
+        for (int i = 0; i < 8; ++i) issue_a(i, 0, 0);
 #pragma unroll
-        for (int j = 0; j < TM; ++j)
+        for (int i = 0; i < 8; ++i) issue_w(i, 0, 1);
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = b4[i][e >> 2][e & 3];
-    if (nk >= NS) wait_vmcnt<(NS - 1) * LPW>(); else wait_vmcnt<0>();
-    barrier_lds();
+        for (int i = 0; i < 8; ++i) issue_a(i, BK, 2);
 #pragma unroll
-    for (int i = 0; i < TN; ++i) fw[0][i] = __builtin_bit_cast(bf16x8, smem[woff[i] + (g ^ wkey[i])]);
+        for (int i = 0; i < 8; ++i) issue_w(i, BK, 3);
+        if (nk > 2) {
 #pragma unroll
-    for (int j = 0; j < TM; ++j) fx[0][j] = __builtin_bit_cast(bf16x8, smem[xoff[j] + (g ^ xkey[j])]);
+            for (int i = 0; i < 8; ++i) issue_a(i, 2 * BK, 4);
+        }
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int j = 0; j < TM; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = b4[i][e >> 2][e & 3];
+        if (nk > 2) wait_vmcnt<24>(); else wait_vmcnt<16>();
+        barrier_lds();
+#pragma unroll
+        for (int i = 0; i < TN; ++i) fw[0][i] = __builtin_bit_cast(bf16x8, smem[SLOT + woff[i] + (g ^ wkey[i])]);
+#pragma unroll
+        for (int j = 0; j < TM; ++j) fx[0][j] = __builtin_bit_cast(bf16x8, smem[xoff[j] + (g ^ xkey[j])]);
 
-    int stage = 0, pstage = NS - 1;                         // stage of k-tile j, of k-tile j - 1
-    // One k-tile.  STEADY: every load / prefetch condition is known to hold, so the body has no branches and
-    // the scheduling fences below fix the interleaving of loads, LDS reads and MFMAs.
-    auto ktile = [&](int j, auto steady_c) {
-        constexpr bool STEADY = decltype(steady_c)::value;
-        const int nstage = stage + 1 == NS ? 0 : stage + 1;
+        int sa = 0;                                         // activation slot of k-tile j
+        // One k-tile.  Loads, four per k-step (one per quarter-step):
+        //   step 0: second half of the weight tile of k-tile j + 1 -> slot sa + 3 (activations of k-tile j - 1)
+        //   steps 1, 2: activation tile of k-tile j + 2            -> slot sa + 4 (weights of k-tile j - 1)
+        //   step 3, after the barrier: first half of the weight tile of k-tile j + 2 -> slot sa (idle from here on)
+        // The barrier of step 3 needs k-tile j + 1 complete; the only younger loads are the eight of the activation
+        // tile of k-tile j + 2.  STEADY: 1 <= j <= nk - 3, every load exists, no branches in the body.
+        auto ktile = [&](int j, auto steady_c) {
+            constexpr bool STEADY = decltype(steady_c)::value;
+            auto rot = [](int s0, int d) { const int t = s0 + d; return t >= 5 ? t - 5 : t; };
+            const int s1 = rot(sa, 1), s2 = rot(sa, 2), s3 = rot(sa, 3), s4 = rot(sa, 4);
 #pragma unroll
-        for (int s = 0; s < STEPS; ++s) {
-            if (s == STEPS - 1) {
-                // every wave holds (or has requested) its last fragments of k-tile j: after the barrier nobody reads
-                // this stage any more, and k-tile j + 1 (waited for here) is visible to all
-                // (the last k-tile has no successor to wait for; residual rows may be in flight there)
-                if (STEADY || j + NS <= nk) wait_vmcnt<(NS - 2) * LPW>(); else if (j + 1 < nk) wait_vmcnt<0>();
-                barrier_lds();
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            // refill: k-tile j + NS -> this stage (from the last step on), k-tile j - 1 + NS -> previous stage
-            const int lt = s == STEPS - 1 ? j + NS : j - 1 + NS;
-            const int lstage = s == STEPS - 1 ? stage : pstage;
-            const bool do_loads = ((s + 1) % STEPS) < LSPREAD && (STEADY || ((s == STEPS - 1 || j >= 1) && lt < nk));
-            const bool do_frags = s + 1 < STEPS || STEADY || j + 1 < nk;
-            const int fstage = s + 1 < STEPS ? stage : nstage, fstep = s + 1 < STEPS ? s + 1 : 0;
-            const int kg = 2 * fstep + g;
-            constexpr int NF = TM + TN, NM = TM * TN;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {                   // quarter-steps: a share of loads, fragment reads, MFMAs
-                if (do_loads) {
-#pragma unroll
-                    for (int i = q * LPS / 4; i < (q + 1) * LPS / 4; ++i)
-                        issue1(((s + 1) % STEPS) * LPS + i, lt * BK, lstage);
-                }
-                if (do_frags) {
-#pragma unroll
-                    for (int f = q * NF / 4; f < (q + 1) * NF / 4; ++f) {
-                        if (f < TN)
-                            fw[(s + 1) & 1][f] = __builtin_bit_cast(bf16x8, smem[fstage * STAGE + woff[f] + (kg ^ wkey[f])]);
-                        else
-                            fx[(s + 1) & 1][f - TN] =
-                                __builtin_bit_cast(bf16x8, smem[fstage * STAGE + xoff[f - TN] + (kg ^ xkey[f - TN])]);
-                    }
-                }
-#pragma unroll
-                for (int idx = q * NM / 4; idx < (q + 1) * NM / 4; ++idx) {
-                    const int i = idx / TM, jj = idx % TM;
-                    acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[s & 1][i], fx[s & 1][jj], acc[i][jj], 0, 0, 0);
+            for (int s = 0; s < STEPS; ++s) {
+                if (s == STEPS - 1) {
+                    if (STEADY || j + 2 < nk) wait_vmcnt<8>(); else if (j + 1 < nk) wait_vmcnt<0>();
+                    barrier_lds();
                 }
                 __builtin_amdgcn_sched_barrier(0);
+                const bool do_loads =
+                    STEADY || (s == 3 ? j + 2 < nk : (s == 0 ? j >= 1 && j + 1 < nk : j >= 1 && j + 2 < nk));
+                const bool do_frags = s + 1 < STEPS || STEADY || j + 1 < nk;
+                const int xslot = s + 1 < STEPS ? sa : s2, wslot = s + 1 < STEPS ? s1 : s3;
+                const int kg = 2 * (s + 1 < STEPS ? s + 1 : 0) + g;
+                constexpr int NF = TM + TN, NM = TM * TN;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {               // quarter-steps: one load, two fragment reads, four MFMAs
+                    if (do_loads) {
+                        if (s == 0) issue_w(4 + q, (j + 1) * BK, s3);
+                        else if (s == 1) issue_a(q, (j + 2) * BK, s4);
+                        else if (s == 2) issue_a(4 + q, (j + 2) * BK, s4);
+                        else issue_w(q, (j + 2) * BK, sa);
+                    }
+                    if (do_frags) {
+#pragma unroll
+                        for (int f = q * NF / 4; f < (q + 1) * NF / 4; ++f) {
+                            if (f < TN)
+                                fw[(s + 1) & 1][f] = __builtin_bit_cast(bf16x8, smem[wslot * SLOT + woff[f] + (kg ^ wkey[f])]);
+                            else
+                                fx[(s + 1) & 1][f - TN] =
+                                    __builtin_bit_cast(bf16x8, smem[xslot * SLOT + xoff[f - TN] + (kg ^ xkey[f - TN])]);
+                        }
+                    }
+#pragma unroll
+                    for (int idx = q * NM / 4; idx < (q + 1) * NM / 4; ++idx) {
+                        const int i = idx / TM, jj = idx % TM;
+                        acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[s & 1][i], fx[s & 1][jj], acc[i][jj], 0, 0, 0);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
+            sa = s2;
+        };
+        int jt = 0;
+        ktile(jt++, std::false_type{});
+        for (; jt < nk - 2; ++jt) ktile(jt, std::true_type{});
+        for (; jt < nk; ++jt) {
+            // from here on only the two slots of the last k-tile are read: the first half of the residual rows goes
+            // into two of the others
+            if (EPI == EPI_BIAS_RESIDUAL && jt == nk - 1) issue_residual(0);
+            ktile(jt, std::false_type{});
         }
-        pstage = stage;
-        stage = nstage;
-    };
-    int jt = 0;
-    ktile(jt++, std::false_type{});
-    for (; jt < nk - NS; ++jt) ktile(jt, std::true_type{});
-    for (; jt < nk; ++jt) {
-        // from here on the stage of k-tile nk - 2 is read by nobody: the first half of the residual rows goes there
-        if (EPI == EPI_BIAS_RESIDUAL && jt == nk - 1) issue_residual(0);
-        ktile(jt, std::false_type{});
+    } else {
+#pragma unroll
+        for (int t = 0; t < NS; ++t)
+            if (t < nk)
+#pragma unroll
+                for (int i = 0; i < LPW; ++i) issue1(i, t * BK, t);
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int j = 0; j < TM; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = b4[i][e >> 2][e & 3];
+        if (nk >= NS) wait_vmcnt<(NS - 1) * LPW>(); else wait_vmcnt<0>();
+        barrier_lds();
+#pragma unroll
+        for (int i = 0; i < TN; ++i) fw[0][i] = __builtin_bit_cast(bf16x8, smem[woff[i] + (g ^ wkey[i])]);
+#pragma unroll
+        for (int j = 0; j < TM; ++j) fx[0][j] = __builtin_bit_cast(bf16x8, smem[xoff[j] + (g ^ xkey[j])]);
+
+        int stage = 0, pstage = NS - 1;                         // stage of k-tile j, of k-tile j - 1
+        // One k-tile.  STEADY: every load / prefetch condition is known to hold, so the body has no branches and
+        // the scheduling fences below fix the interleaving of loads, LDS reads and MFMAs.
+        auto ktile = [&](int j, auto steady_c) {
+            constexpr bool STEADY = decltype(steady_c)::value;
+            const int nstage = stage + 1 == NS ? 0 : stage + 1;
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s) {
+                if (s == STEPS - 1) {
+                    // every wave holds (or has requested) its last fragments of k-tile j: after the barrier nobody reads
+                    // this stage any more, and k-tile j + 1 (waited for here) is visible to all
+                    // (the last k-tile has no successor to wait for; residual rows may be in flight there)
+                    if (STEADY || j + NS <= nk) wait_vmcnt<(NS - 2) * LPW>(); else if (j + 1 < nk) wait_vmcnt<0>();
+                    barrier_lds();
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                // refill: k-tile j + NS -> this stage (from the last step on), k-tile j - 1 + NS -> previous stage
+                const int lt = s == STEPS - 1 ? j + NS : j - 1 + NS;
+                const int lstage = s == STEPS - 1 ? stage : pstage;
+                const bool do_loads = ((s + 1) % STEPS) < LSPREAD && (STEADY || ((s == STEPS - 1 || j >= 1) && lt < nk));
+                const bool do_frags = s + 1 < STEPS || STEADY || j + 1 < nk;
+                const int fstage = s + 1 < STEPS ? stage : nstage, fstep = s + 1 < STEPS ? s + 1 : 0;
+                const int kg = 2 * fstep + g;
+                constexpr int NF = TM + TN, NM = TM * TN;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {                   // quarter-steps: a share of loads, fragment reads, MFMAs
+                    if (do_loads) {
+#pragma unroll
+                        for (int i = q * LPS / 4; i < (q + 1) * LPS / 4; ++i)
+                            issue1(((s + 1) % STEPS) * LPS + i, lt * BK, lstage);
+                    }
+                    if (do_frags) {
+#pragma unroll
+                        for (int f = q * NF / 4; f < (q + 1) * NF / 4; ++f) {
+                            if (f < TN)
+                                fw[(s + 1) & 1][f] = __builtin_bit_cast(bf16x8, smem[fstage * STAGE + woff[f] + (kg ^ wkey[f])]);
+                            else
+                                fx[(s + 1) & 1][f - TN] =
+                                    __builtin_bit_cast(bf16x8, smem[fstage * STAGE + xoff[f - TN] + (kg ^ xkey[f - TN])]);
+                        }
+                    }
+#pragma unroll
+                    for (int idx = q * NM / 4; idx < (q + 1) * NM / 4; ++idx) {
+                        const int i = idx / TM, jj = idx % TM;
+                        acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[s & 1][i], fx[s & 1][jj], acc[i][jj], 0, 0, 0);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            pstage = stage;
+            stage = nstage;
+        };
+        int jt = 0;
+        ktile(jt++, std::false_type{});
+        for (; jt < nk - NS; ++jt) ktile(jt, std::true_type{});
+        for (; jt < nk; ++jt) {
+            // from here on the stage of k-tile nk - 2 is read by nobody: the first half of the residual rows goes there
+            if (EPI == EPI_BIAS_RESIDUAL && jt == nk - 1) issue_residual(0);
+            ktile(jt, std::false_type{});
+        }
+
     }
 
     // ---- epilogue.  Accumulator element v of lane l in block (i, j): token = l % 32,
