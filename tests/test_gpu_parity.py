@@ -268,6 +268,40 @@ def test_other_student_shapes(sp, oracle64, name):
     check_logits(got, want, shape, name)
 
 
+LARGE_OTHER = {
+    # reduction depths 256 / 1024 and 512 / 1280: with the depths 768 / 3072 of the workloads, the last k-tile of the
+    # large-tile projection kernel ends in every position of its five-slot operand ring
+    "256D_ffn1024": synth.StudentShape(K=2, layers=2, hidden=256, heads=4, ffn=1024, vocab=1000, max_pos=128,
+                                       classes=2, dtype="bf16"),
+    "512D_ffn1280": synth.StudentShape(K=2, layers=2, hidden=512, heads=8, ffn=1280, vocab=1000, max_pos=128,
+                                       classes=3, dtype="bf16"),
+}
+
+
+@pytest.mark.parametrize("name", list(LARGE_OTHER))
+def test_large_calls_on_other_widths(sp, oracle64, name):
+    """Calls of more than 2048 tokens (the 256 x 256 projection tiles, the long-call LayerNorm and embedding paths) on
+    widths other than the workloads'.  The oracle checks a sample of the sequences (sequences are independent)."""
+    shape = LARGE_OTHER[name]
+    rng = np.random.default_rng(37)
+    lengths = rng.integers(24, 97, size=40).astype(np.int32)
+    assert 2048 < lengths.sum()
+    ids = synth.make_ids(rng, int(lengths.sum()), shape.vocab)
+    blob = synth.make_weights(rng, shape, std=0.02, ln_random=True, qk_std=float(np.sqrt(1.5 / shape.hidden)))
+    st = sp.Students(sp.config_from_shape(shape), blob)
+    d_ids, d_cu, cu = gpu_inputs(lengths, ids, sp)
+    got = st.sp_forward(d_ids, d_cu, int(lengths.max()), shape.K).cpu().numpy().astype(np.float64)
+    pick = np.sort(rng.choice(len(lengths), size=6, replace=False))
+    sub_ids = np.concatenate([ids[cu[b]:cu[b + 1]] for b in pick])
+    sub_cu = np.concatenate([[0], np.cumsum(lengths[pick])]).astype(np.int32)
+    want = oracle64.forward(ocfg(shape), oracle_weights(blob, shape), sub_ids, sub_cu, shape.K)
+    check_logits(got[pick], want, shape, name)
+    # and the all-token last layer (the same projections on every row of the last layer as well)
+    st2 = sp.Students(sp.config_from_shape(shape, last_layer_all_tokens=True), blob)
+    got2 = st2.sp_forward(d_ids, d_cu, int(lengths.max()), shape.K).cpu().numpy().astype(np.float64)
+    check_logits(got2[pick], want, shape, name + " all-token last layer")
+
+
 # ---- the five workloads ----------------------------------------------------------------------------
 
 _cache = {}
