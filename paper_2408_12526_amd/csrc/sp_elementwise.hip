@@ -103,15 +103,20 @@ __global__ __launch_bounds__(256) void embed_ln_kernel(const char* arena, size_t
     const char* sb = arena + (size_t)m * student_stride;
     float gg[MAXC][8], bb[MAXC][8];
     load_gamma_beta<MAXC>((const float*)(sb + g_off), (const float*)(sb + b_off), nch, lane, gg, bb);
-    // sequence of the first row: largest b with cu[b] <= row; later rows walk forward from there
-    int seq = 0;
-    if (row0 < Tn) {
+    // Token id and position of the wave's rows, found by one lane per row before any row is fetched (rpw <= 64):
+    // the sequence of a row is the largest b with cu[b] <= row.  The row loop then has no dependent index loads.
+    int my_id = 0, my_pos = 0;
+    if (lane < rpw && row0 + lane < Tn) {
+        const int row = row0 + lane;
+        my_id = ids[row];
         int lo = 0, hi = B;
         while (hi - lo > 1) {
             const int mid = (lo + hi) >> 1;
-            if (cu[mid] <= row0) lo = mid; else hi = mid;
+            if (cu[mid] <= row) lo = mid; else hi = mid;
         }
-        seq = lo;
+        my_pos = row - cu[lo];
+        my_pos = my_pos < 0 ? 0 : (my_pos >= P ? P - 1 : my_pos);
+        my_id = my_id < 0 ? 0 : (my_id >= V ? V - 1 : my_id);
     }
 #pragma unroll 2
     for (int r = 0; r < rpw; ++r) {
@@ -127,11 +132,7 @@ __global__ __launch_bounds__(256) void embed_ln_kernel(const char* arena, size_t
             for (int c = lane; c < nch; c += 64) { store8(out + c * 8, zero8); store8(arow + c * 8, zero8); }
             continue;
         }
-        while (seq + 1 < B && cu[seq + 1] <= row) ++seq;
-        int pos = row - cu[seq];
-        pos = pos < 0 ? 0 : (pos >= P ? P - 1 : pos);
-        int id = ids[row];
-        id = id < 0 ? 0 : (id >= V ? V - 1 : id);
+        const int id = __builtin_amdgcn_readlane(my_id, r), pos = __builtin_amdgcn_readlane(my_pos, r);
         const T* te = (const T*)(sb + tok_off) + (size_t)id * H;
         const T* pe = (const T*)(sb + pos_off) + (size_t)pos * H;
         float v[MAXC][8];
