@@ -35,7 +35,7 @@ def percentile(xs, q):
 # HBM-side bytes of one launch of the FFN-up GEMM at k_active = 8 on the burst workload, from two rocprofv3 --pmc runs
 # (FETCH_SIZE, WRITE_SIZE) scaled by the same counters on a 1 GiB copy; the summary with the commands is
 # profiles/hbm_traffic_gemm_ffn_up_c4_burst_b256.txt.  A counter run cannot be made from inside the timed process.
-FFN_UP_HBM_BYTES_PER_LAUNCH = {"read": 1.333e9, "written": 7.298e8}
+FFN_UP_HBM_BYTES_PER_LAUNCH = {"read": 9.92e8, "written": 7.298e8}
 
 
 def gemm_flops(shape, tokens, k, layers):
