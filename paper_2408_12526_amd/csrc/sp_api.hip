@@ -7,6 +7,7 @@
 #include <thread>
 #include <vector>
 
+#include "sp_dispatch.h"
 #include "sp_internal.h"
 
 namespace sp {
@@ -537,6 +538,8 @@ const char* sp_strerror(int code)
         case SP_EKACTIVE: return "k_active outside 1..K";
         case SP_ENOMEM: return "buffer smaller than required";
         case SP_EHIP: return "HIP runtime error";
+        case SP_EFULL: return "length-aware buffer storage full";
+        case SP_EEMPTY: return "length-aware buffer empty";
         default: return "unknown error code";
     }
 }

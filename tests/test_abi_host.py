@@ -20,18 +20,24 @@ def sp():
 
 
 def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "sp.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(sp_[a-z_]+)\s*\(", text)))
+    names = set()
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        if header.endswith(".h"):
+            text = open(os.path.join(ROOT, "include", header)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names |= set(re.findall(r"\b(sp_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol(sp):
     names = declared_symbols()
     assert {"sp_load_students", "sp_forward", "sp_pack", "sp_free", "sp_strerror", "sp_arena_bytes",
-            "sp_workspace_bytes", "sp_blob_floats", "sp_workspace_layout", "sp_forward_partial"} <= set(names)
+            "sp_workspace_bytes", "sp_blob_floats", "sp_workspace_layout", "sp_forward_partial", "sp_lab_create",
+            "sp_lab_push", "sp_lab_pop", "sp_ctl_create", "sp_ctl_on_buffered", "sp_ctl_on_tick",
+            "sp_dispatch_simulate"} <= set(names)
     lib = sp.raw_lib()
     for n in names:
-        assert hasattr(lib, n), f"{n} is declared in sp.h but not exported"
+        assert hasattr(lib, n), f"{n} is declared in include/ but not exported"
 
 
 def test_pack_matches_oracle_bit_for_bit(sp, oracle64):
