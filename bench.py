@@ -64,6 +64,114 @@ def last_first_work(shape, tokens, batch, k):
     return flops, k * tokens * H * 2 + weight_bytes
 
 
+def serve_leg(sp, synth, torch, dev, students, with_oracle):
+    """Length-aware buffer + student-number controller + dispatcher loop (include/sp_dispatch.h) fed with a bursty
+    synthetic arrival process, in virtual time.  The service time of a small batch is what sp_forward measures here for
+    it on this GPU (wall time, call to stream sync, p50): per k_active a straight line base + per_token * tokens fitted
+    to batches of 1-4 sequences.  Variants: fully packed small batches against the paper's batches padded to the
+    8-token bin, adaptive student number against all students always.  Groups are taken to run side by side without
+    slowing each other (the paper gives each group its own share of the GPU); a measured figure for concurrent
+    streams of this library on one GPU is reported beside it."""
+    from paper_2408_12526_amd import dispatch
+    w3 = synth.WORKLOADS[3]
+    if students is None:
+        _, blob3 = synth.make_workload(w3)
+        students = sp.Students(sp.config_from_shape(w3.shape), blob3)
+    K = w3.shape.K
+    rng = np.random.default_rng(11)
+    shapes = [(1, 8), (1, 32), (1, 64), (1, 128), (2, 64), (4, 64), (4, 128)]
+    inputs = []
+    for nseq, L in shapes:
+        lengths = np.full(nseq, L, dtype=np.int32)
+        cu = sp.sp_pack(lengths)
+        ids = synth.make_ids(rng, nseq * L, w3.shape.vocab)
+        inputs.append((nseq * L, L, torch.from_numpy(ids).to(dev), torch.from_numpy(cu).to(dev),
+                       torch.empty(nseq, w3.shape.classes, dtype=torch.float32, device=dev), students.workspace(nseq * L, nseq)))
+    base_us, per_token_ns, table = [0], [0], {}
+    for k in range(1, K + 1):
+        xs, ys = [], []
+        for tokens, L, d_ids, d_cu, logits, ws in inputs:
+            for _ in range(10):
+                students.sp_forward(d_ids, d_cu, L, k, logits, ws)
+            torch.cuda.synchronize()
+            wall = []
+            for _ in range(40):
+                t0 = time.perf_counter()
+                students.sp_forward(d_ids, d_cu, L, k, logits, ws)
+                torch.cuda.synchronize()
+                wall.append((time.perf_counter() - t0) * 1e6)
+            xs.append(tokens)
+            ys.append(percentile(wall, 50))
+        slope, icpt = np.polyfit(np.array(xs, float), np.array(ys, float), 1)
+        base_us.append(int(round(max(icpt, 1.0))))
+        per_token_ns.append(int(round(max(slope, 0.0) * 1000)))
+        table[str(k)] = {"p50_us_by_tokens": {str(x): round(y, 1) for x, y in zip(xs, ys)}}
+
+    # concurrent streams of single-sequence calls (64 tokens, k_active 1), issued round-robin by this one host thread
+    tokens, L, d_ids, d_cu, _, _ = inputs[2]
+    conc = {}
+    for g in (1, 2, 4, 8):
+        streams = [torch.cuda.Stream() for _ in range(g)]
+        bufs = [(torch.empty(1, w3.shape.classes, dtype=torch.float32, device=dev), students.workspace(tokens, 1))
+                for _ in range(g)]
+        for it in range(2):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(400):
+                lo, ws = bufs[i % g]
+                students.sp_forward(d_ids, d_cu, L, 1, lo, ws, stream=streams[i % g])
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+        conc[str(g)] = round(400 / dt)
+
+    n = 200_000
+    arng = np.random.default_rng(12)
+    arr = synth.make_arrivals(arng, n, 2000.0, 40000.0, 0.5, 0.05)
+    lengths = synth.make_lengths(arng, n, ("lognormal", 48, 0.6, 8, 256))
+    common = dict(total_students=K, slots=K, window_us=100_000, base_us=base_us, per_token_ns=per_token_ns,
+                  bin_width=8, max_len=128, max_elem=4, capacity=65536)
+    out = {}
+    for name, padded, k_min in (("packed_adaptive", False, 1), ("padded_adaptive", True, 1),
+                                ("packed_all_students", False, K), ("padded_all_students", True, K)):
+        t0 = time.perf_counter()
+        r = dispatch.simulate(arr, lengths, padded=padded, k_min=k_min, **common)
+        dt = time.perf_counter() - t0
+        ok = r.element >= 0
+        lat = (r.done_us - arr)[ok]
+        out[name] = {"p50_latency_us": float(np.percentile(lat, 50)), "p99_latency_us": float(np.percentile(lat, 99)),
+                     "max_latency_us": float(lat.max()), "refused": int(r.refused),
+                     "mean_k_active": float(r.k_used[ok].mean()), "elements": int(len(r.elem_size)),
+                     "mean_element_size": float(r.elem_size.mean()), "tokens_computed": int(r.elem_tokens.sum()),
+                     "k_changes": len(r.k_trace) - 1,
+                     "served_per_s": float(ok.sum() / ((r.done_us[ok].max() - arr[0]) / 1e6)),
+                     "host_ns_per_event": dt / (n + len(r.elem_size)) * 1e9}
+    true_tokens = int(np.minimum(lengths, 128).sum())
+    res = {"arrivals": f"{n} requests, Poisson, 2000/s with bursts of 40000/s (0.5 s quiet, 0.05 s burst), lengths "
+                       "lognormal (median 48, sigma 0.6, clipped to [8,256], the buffer clips to 128)",
+           "service_model_us": {"base_us": base_us[1:], "per_token_ns": per_token_ns[1:],
+                                "measured": "sp_forward wall p50 on this GPU, batches of 1-4 sequences, 8-512 tokens"},
+           "service_table": table, "true_tokens": true_tokens,
+           "concurrent_streams_calls_per_s": conc, "variants": out}
+    # O(1): the same loop with a shallow and a deep buffer (overload: every student kept, so the queue grows)
+    deep = {}
+    for cap in (64, 65536):
+        t0 = time.perf_counter()
+        r = dispatch.simulate(arr[:100_000] // 8, lengths[:100_000], padded=False, k_min=K, **dict(common, capacity=cap))
+        deep[str(cap)] = {"host_ns_per_event": (time.perf_counter() - t0) / (100_000 + len(r.elem_size)) * 1e9,
+                          "refused": int(r.refused)}
+    res["host_cost_vs_buffer_capacity"] = deep
+    if with_oracle:
+        from oracle import sp_dispatch_oracle as O
+        m = 20_000
+        t0 = time.perf_counter()
+        ro = O.simulate(arr[:m].tolist(), lengths[:m].tolist(), padded=False, k_min=1,
+                        **{k: (v if not isinstance(v, np.ndarray) else v.tolist()) for k, v in common.items()})
+        dt = time.perf_counter() - t0
+        res["oracle_python"] = {"host_ns_per_event": dt / (m + len(ro.elem_size)) * 1e9, "kind": "oracle",
+                                "sample": f"first {m} arrivals, packed, adaptive"}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -71,7 +179,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--latency-calls", type=int, default=300)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--only", choices=["burst", "latency"], default=None,
+    ap.add_argument("--only", choices=["burst", "latency", "serve"], default=None,
                     help="run one workload only (for profiling a single launch configuration)")
     ap.add_argument("--burst-k", default=None,
                     help="comma-separated k_active values for the burst workload (default: 8,4,2); profiles of one "
@@ -199,9 +307,14 @@ def main():
             latency[k] = {"p50_us": percentile(wall, 50), "p95_us": percentile(wall, 95),
                           "back_to_back_us": back, "weight_stream_gbs": weight_bytes / back / 1e3}
 
+    # ------------------------------------------------------------------ serving loop (host-side dispatching)
+    serve = None
+    if args.only in (None, "serve"):
+        serve = serve_leg(sp, synth, torch, dev, st3 if latency else None, not args.no_cpu_baseline)
+
     # ------------------------------------------------------------------ CPU oracle on a bounded sample
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.only != "serve":
         from oracle.sp_oracle import Oracle, OracleConfig
         orc = Oracle("f32")
         s = w4.shape
@@ -245,6 +358,7 @@ def main():
         "latency_workload": "c3_latency_b1: K=8 students, one sequence of 64 tokens, 3 classes; wall time from call "
                             "to stream sync, inputs resident",
         "phases_k8": phases,
+        "serve": serve,
     }
     if phases:
         d = phases["ffn_up"]

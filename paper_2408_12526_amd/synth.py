@@ -117,6 +117,28 @@ def make_lengths(rng: np.random.Generator, batch: int, recipe: Tuple) -> np.ndar
     raise ValueError(kind)
 
 
+def make_arrivals(rng: np.random.Generator, n: int, quiet_per_s: float, burst_per_s: float, quiet_s: float,
+                  burst_s: float) -> np.ndarray:
+    """Arrival times (integer microseconds, non-decreasing) of n requests: a Poisson process whose rate alternates
+    between quiet stretches and bursts (stand-in for the production request trace the paper replays, which is not
+    available offline: steady traffic with bursts an order of magnitude denser)."""
+    out = np.empty(n, dtype=np.float64)
+    t, i, phase_end, burst = 0.0, 0, quiet_s, False
+    while i < n:
+        rate = burst_per_s if burst else quiet_per_s
+        m = min(n - i, max(16, int(rate * (phase_end - t) * 1.2) + 16))
+        ts = t + np.cumsum(rng.exponential(1.0 / rate, size=m))
+        inside = int(np.searchsorted(ts, phase_end, side="right"))
+        out[i:i + inside] = ts[:inside]
+        i += inside
+        if inside < m or (inside and ts[inside - 1] >= phase_end):
+            t, burst = phase_end, not burst
+            phase_end = t + (burst_s if burst else quiet_s)
+        elif inside:
+            t = ts[inside - 1]
+    return np.floor(out * 1e6).astype(np.int64)
+
+
 def make_ids(rng: np.random.Generator, total: int, vocab: int) -> np.ndarray:
     return rng.integers(0, vocab, size=total).astype(np.int32)
 
