@@ -1,6 +1,7 @@
 /* Host-side dispatching of Student Parallelism: the length-aware buffer, the student-number controller and the
- * dispatcher loop that joins them.  Plain C ABI; everything here runs on the host (no device memory, no HIP call) and
- * produces the two run-time inputs of sp_forward: a packed batch of samples and k_active.
+ * dispatcher loop that joins them.  Plain C ABI; everything except sp_serve_replay (last entry) runs on the host alone
+ * (no device memory, no HIP call) and produces the two run-time inputs of sp_forward: a packed batch of samples and
+ * k_active.
  *
  * Conventions
  *   - return value 0 (SP_OK) on success, a negative code otherwise (the SP_E* codes of sp.h plus SP_EFULL and
@@ -29,6 +30,8 @@
 #define SP_DISPATCH_H
 
 #include <stdint.h>
+
+#include "sp.h"
 
 #ifdef __cplusplus
 extern "C" {
@@ -107,6 +110,34 @@ int sp_dispatch_simulate(const sp_sim_config* cfg, const int64_t* arrival_us, co
                          int64_t* dispatch_us, int64_t* done_us, int32_t* k_used, int64_t* element, int64_t* elem_tokens,
                          int32_t* elem_size, int64_t* n_elements, int64_t* trace_us, int32_t* trace_k,
                          int64_t trace_cap, int64_t* n_trace, int64_t* refused);
+
+/* ---- the same loop in real time, on the GPU: replays a list of arrivals against a loaded student group.  The
+ * calling thread is the dispatcher (the paper's master process: buffer, controller, dispatching); every student group
+ * is a worker thread of the library with its own HIP stream, pinned staging buffers, device inputs / outputs and
+ * workspace, which runs one element at a time: ids and offsets to the device, sp_forward with the k_active in force at
+ * dispatch, logits back, stream synchronisation.  A sample's latency done_us - arrival_us therefore includes both
+ * PCIe copies.  slots / k_min worker threads are started; slots / k of them take work while k students are active.
+ * Unlike sp_forward this call allocates (once, before the replay starts: device buffers of slots / k_min groups for
+ * max_elem * max_len tokens each) and blocks until the last sample is done. ---- */
+typedef struct sp_serve_config {
+    int32_t slots, k_min, k_start;  /* total_students is the loaded group's K; k_start 0: K */
+    int64_t window_us;
+    int32_t bin_width, max_len, max_elem, capacity;   /* max_len <= the students' max_pos */
+    int32_t padded;  /* 1: every sample of an element is padded with pad_id to the bin length (the paper's small batch;
+                        the padded tokens are attended to, so only the timing of this variant is meaningful) */
+    int32_t pad_id;
+} sp_serve_config;
+
+/* model: a group loaded with sp_load_students.  arrival_us [n] non-decreasing, relative to the start of the call;
+ * token_ids host [id_offsets[n]], sample i owns [id_offsets[i], id_offsets[i+1]) (its length; only the first max_len
+ * tokens are used).  Outputs [n]: dispatch_us, done_us (microseconds since the start of the call), k_used, element
+ * (index of the dispatched element, -1 if the sample was refused), logits host float32 [n][classes]; elem_size [n]
+ * (first *n_elements entries); *refused; *k_final.
+ * Errors: SP_EINVAL, SP_ESHAPE, SP_ENOMEM, SP_EHIP (a HIP call or a forward failed, or no group finished for 10 s). */
+int sp_serve_replay(const sp_model* model, const sp_serve_config* cfg, const int64_t* arrival_us,
+                    const int32_t* token_ids, const int64_t* id_offsets, int64_t n, int64_t* dispatch_us,
+                    int64_t* done_us, int32_t* k_used, int64_t* element, int32_t* elem_size, int64_t* n_elements,
+                    float* logits, int64_t* refused, int32_t* k_final);
 
 #ifdef __cplusplus
 }

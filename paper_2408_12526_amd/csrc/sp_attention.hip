@@ -1,5 +1,6 @@
 // Multi-head self-attention over a packed batch: every sequence attends to itself only,
 // over exactly its own tokens (cu_seqlens gives the boundaries); head width is 64.
+#include <atomic>
 #include <type_traits>
 
 #include "sp_internal.h"
@@ -719,7 +720,7 @@ hipError_t launch_attention_first_fold(const sp_model* M, const void* x, const v
 #define SP_FOLD(HEADS)                                                                                              \
     do {                                                                                                            \
         auto kern = attention_first_fold_kernel<HEADS>;                                                             \
-        static bool raised = false; /* the attribute is sticky for the process */                                  \
+        static std::atomic<bool> raised{false}; /* the attribute is sticky for the process */                      \
         if (smem > 48 * 1024 && !raised) {                                                                          \
             hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,      \
                                                (int)kFoldMaxSmem);                                                  \

@@ -2,6 +2,7 @@
 // student m.  The bf16 kernel runs on the matrix cores (v_mfma_f32_32x32x16_bf16, fp32
 // accumulate) with both operands staged through LDS; the fp32 kernel is a plain FMA tile
 // kernel used by the fp32 path.
+#include <atomic>
 #include <type_traits>
 
 #include "sp_internal.h"
@@ -555,11 +556,11 @@ hipError_t launch_bf16_tile(const sp_model* M, const void* A, int lda, size_t w_
     constexpr size_t smem = GemmTile<BM, BN>::smem_bytes;
     auto kern = gemm_bf16_kernel<BM, BN, EPI>;
     if (smem > 48 * 1024) {
-        static bool raised = false;   // per instantiation; the attribute is sticky for the process
-        if (!raised) {
+        static std::atomic<bool> raised{false};   // per instantiation; the attribute is sticky for the process
+        if (!raised.load(std::memory_order_acquire)) {   // (threads that race here set the same value twice)
             hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
             if (e != hipSuccess) return e;
-            raised = true;
+            raised.store(true, std::memory_order_release);
         }
     }
     const int mtiles = mrows / BM, ntiles = N / BN, total = k * ksplit * mtiles * ntiles;

@@ -163,3 +163,48 @@ def simulate(arrival_us, lengths, *, total_students, slots, k_min, window_us, ba
     m = min(nt.value, trace_cap)
     return SimResult(disp, done, k_used, element, etok[:ne.value].copy(), esize[:ne.value].copy(),
                      list(zip(tus[:m].tolist(), tk[:m].tolist())), nref.value)
+
+
+class sp_serve_config(C.Structure):
+    _fields_ = [("slots", C.c_int32), ("k_min", C.c_int32), ("k_start", C.c_int32), ("window_us", C.c_int64),
+                ("bin_width", C.c_int32), ("max_len", C.c_int32), ("max_elem", C.c_int32), ("capacity", C.c_int32),
+                ("padded", C.c_int32), ("pad_id", C.c_int32)]
+
+
+_lib.sp_serve_replay.restype = C.c_int
+_lib.sp_serve_replay.argtypes = [C.c_void_p, C.POINTER(sp_serve_config)] + [C.c_void_p] * 3 + [C.c_int64] + \
+    [C.c_void_p] * 5 + [C.POINTER(C.c_int64), C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int32)]
+
+
+@dataclass
+class ReplayResult:
+    dispatch_us: np.ndarray
+    done_us: np.ndarray
+    k_used: np.ndarray
+    element: np.ndarray
+    elem_size: np.ndarray
+    logits: np.ndarray
+    refused: int
+    k_final: int
+
+
+def serve_replay(model_handle, classes: int, arrival_us, token_ids, id_offsets, *, slots, k_min, window_us, padded=False,
+                 pad_id=0, bin_width=8, max_len=128, max_elem=4, capacity=4096, k_start=None) -> ReplayResult:
+    """sp_serve_replay of the library: real-time replay on the GPU.  model_handle: the sp_model* of a loaded group
+    (Students.handle of the sp module); token_ids int32 host array, sample i owns [id_offsets[i], id_offsets[i+1])."""
+    arr = np.ascontiguousarray(arrival_us, np.int64)
+    ids = np.ascontiguousarray(token_ids, np.int32)
+    off = np.ascontiguousarray(id_offsets, np.int64)
+    n = len(arr)
+    assert len(off) == n + 1 and off[-1] <= len(ids)
+    cfg = sp_serve_config(slots, k_min, k_start or 0, window_us, bin_width, max_len, max_elem, capacity,
+                          1 if padded else 0, pad_id)
+    disp, done = np.full(n, -1, np.int64), np.full(n, -1, np.int64)
+    k_used, element = np.zeros(n, np.int32), np.full(n, -1, np.int64)
+    esize = np.zeros(max(n, 1), np.int32)
+    logits = np.zeros((n, classes), np.float32)
+    ne, nref, kf = C.c_int64(), C.c_int64(), C.c_int32()
+    _check(_lib.sp_serve_replay(model_handle, C.byref(cfg), arr.ctypes.data, ids.ctypes.data, off.ctypes.data, n,
+                                disp.ctypes.data, done.ctypes.data, k_used.ctypes.data, element.ctypes.data,
+                                esize.ctypes.data, C.byref(ne), logits.ctypes.data, C.byref(nref), C.byref(kf)))
+    return ReplayResult(disp, done, k_used, element, esize[:ne.value].copy(), logits, nref.value, kf.value)
