@@ -160,6 +160,22 @@ def serve_leg(sp, synth, torch, dev, students, with_oracle):
         deep[str(cap)] = {"host_ns_per_event": (time.perf_counter() - t0) / (100_000 + len(r.elem_size)) * 1e9,
                           "refused": int(r.refused)}
     res["host_cost_vs_buffer_capacity"] = deep
+    # the same dispatching in real time on this GPU: worker threads of the library run sp_forward on what the
+    # dispatcher hands them (latency = arrival to logits on the host, both PCIe copies included)
+    m = 20_000
+    off = np.concatenate([[0], np.cumsum(lengths[:m])]).astype(np.int64)
+    tok = synth.make_ids(arng, int(off[-1]), w3.shape.vocab)
+    real = {}
+    for name, padded, k_min in (("packed_adaptive", False, 1), ("padded_adaptive", True, 1), ("packed_all_students", False, K)):
+        r = dispatch.serve_replay(students.handle, w3.shape.classes, arr[:m], tok, off, slots=K, k_min=k_min,
+                                  window_us=100_000, padded=padded, capacity=65536)
+        ok = r.element >= 0
+        lat = (r.done_us - arr[:m])[ok]
+        real[name] = {"p50_latency_us": float(np.percentile(lat, 50)), "p99_latency_us": float(np.percentile(lat, 99)),
+                      "max_latency_us": float(lat.max()), "refused": int(r.refused),
+                      "mean_k_active": float(r.k_used[ok].mean()), "mean_element_size": float(r.elem_size.mean()),
+                      "served_per_s": float(ok.sum() / ((r.done_us[ok].max() - arr[0]) / 1e6))}
+    res["real_time_replay"] = {"sample": f"first {m} arrivals of the same process ({arr[m - 1] / 1e6:.1f} s)", "variants": real}
     if with_oracle:
         from oracle import sp_dispatch_oracle as O
         m = 20_000

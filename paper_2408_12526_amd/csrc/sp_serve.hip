@@ -34,6 +34,7 @@ struct Worker {
     std::mutex mu;
     std::condition_variable cv;
     bool has_job = false, stop = false;
+    std::atomic<bool> flag{false};      // set with has_job / stop: lets the worker spin without the lock
     Job job;
 };
 
@@ -44,7 +45,7 @@ struct Shared {
     const int64_t* id_offsets = nullptr;
     int64_t* done_us = nullptr;
     float* logits = nullptr;
-    int device = 0, classes = 0;
+    int device = 0, classes = 0, cu_room = 0;    // cu_room: ints reserved for the offsets in front of the ids
     size_t ws_bytes = 0;
     std::chrono::steady_clock::time_point t0;
     std::mutex cq_mu;
@@ -65,10 +66,13 @@ void worker_main(Shared* S, Worker* w)
     const sp_serve_config& c = *S->cfg;
     for (;;) {
         {
+            // a short spin first: waking a sleeping thread costs more than a small forward's launches
+            for (int spin = 0; spin < 2000 && !w->flag.load(std::memory_order_acquire); ++spin) std::this_thread::yield();
             std::unique_lock<std::mutex> lk(w->mu);
             w->cv.wait(lk, [&] { return w->has_job || w->stop; });
             if (w->stop) return;
             w->has_job = false;
+            w->flag.store(false, std::memory_order_release);
         }
         const Job& j = w->job;             // the dispatcher does not touch it again before this worker reports back
         int32_t total = 0, longest = 0;
@@ -83,8 +87,8 @@ void worker_main(Shared* S, Worker* w)
             longest = out_len > longest ? out_len : longest;
         }
         int rc = SP_OK;
-        if (hipMemcpyAsync(w->d_ids, w->h_ids, sizeof(int32_t) * (size_t)total, hipMemcpyHostToDevice, w->stream) != hipSuccess ||
-            hipMemcpyAsync(w->d_cu, w->h_cu, sizeof(int32_t) * (size_t)(j.count + 1), hipMemcpyHostToDevice, w->stream) != hipSuccess)
+        // offsets and ids share one staging buffer (offsets first): one copy to the device
+        if (hipMemcpyAsync(w->d_cu, w->h_cu, sizeof(int32_t) * (size_t)(S->cu_room + total), hipMemcpyHostToDevice, w->stream) != hipSuccess)
             rc = SP_EHIP;
         if (rc == SP_OK)
             rc = sp_forward(S->model, w->d_ids, w->d_cu, j.count, total, longest, j.k, w->d_ws, S->ws_bytes, w->d_logits, w->stream);
@@ -109,10 +113,8 @@ void worker_main(Shared* S, Worker* w)
 
 void release(Worker& w)
 {
-    if (w.h_ids) (void)hipHostFree(w.h_ids);
-    if (w.h_cu) (void)hipHostFree(w.h_cu);
+    if (w.h_cu) (void)hipHostFree(w.h_cu);           // (h_ids / d_ids point into the same allocations)
     if (w.h_logits) (void)hipHostFree(w.h_logits);
-    if (w.d_ids) (void)hipFree(w.d_ids);
     if (w.d_cu) (void)hipFree(w.d_cu);
     if (w.d_logits) (void)hipFree(w.d_logits);
     if (w.d_ws) (void)hipFree(w.d_ws);
@@ -147,19 +149,19 @@ extern "C" int sp_serve_replay(const sp_model* model, const sp_serve_config* cfg
     const int nworkers = cfg->slots / cfg->k_min;
     const int32_t max_tokens = cfg->max_elem * cfg->max_len;
     S.ws_bytes = sp_workspace_bytes(&mc, max_tokens, cfg->max_elem);
+    S.cu_room = (cfg->max_elem + 1 + 63) / 64 * 64;      // keeps the ids 256-byte aligned
     std::vector<Worker> workers((size_t)nworkers);
     bool ok = hipGetDevice(&S.device) == hipSuccess && S.ws_bytes > 0;
     for (int g = 0; g < nworkers && ok; ++g) {
         Worker& w = workers[(size_t)g];
         w.index = g;
         ok = hipStreamCreateWithFlags(&w.stream, hipStreamNonBlocking) == hipSuccess &&
-             hipHostMalloc((void**)&w.h_ids, sizeof(int32_t) * (size_t)max_tokens, hipHostMallocDefault) == hipSuccess &&
-             hipHostMalloc((void**)&w.h_cu, sizeof(int32_t) * (size_t)(cfg->max_elem + 1), hipHostMallocDefault) == hipSuccess &&
+             hipHostMalloc((void**)&w.h_cu, sizeof(int32_t) * (size_t)(S.cu_room + max_tokens), hipHostMallocDefault) == hipSuccess &&
              hipHostMalloc((void**)&w.h_logits, sizeof(float) * (size_t)cfg->max_elem * mc.classes, hipHostMallocDefault) == hipSuccess &&
-             hipMalloc((void**)&w.d_ids, sizeof(int32_t) * (size_t)max_tokens) == hipSuccess &&
-             hipMalloc((void**)&w.d_cu, sizeof(int32_t) * (size_t)(cfg->max_elem + 1)) == hipSuccess &&
+             hipMalloc((void**)&w.d_cu, sizeof(int32_t) * (size_t)(S.cu_room + max_tokens)) == hipSuccess &&
              hipMalloc((void**)&w.d_logits, sizeof(float) * (size_t)cfg->max_elem * mc.classes) == hipSuccess &&
              hipMalloc(&w.d_ws, S.ws_bytes) == hipSuccess;
+        if (ok) { w.h_ids = w.h_cu + S.cu_room; w.d_ids = w.d_cu + S.cu_room; }
         if (ok) {
             try { w.job.ids.resize((size_t)cfg->max_elem); w.job.lens.resize((size_t)cfg->max_elem); }
             catch (const std::bad_alloc&) { ok = false; }
@@ -189,6 +191,7 @@ extern "C" int sp_serve_replay(const sp_model* model, const sp_serve_config* cfg
             w.job.count = count; w.job.bin_len = bin_len; w.job.k = k;
             for (int32_t i = 0; i < count; ++i) { w.job.ids[(size_t)i] = ids[i]; w.job.lens[(size_t)i] = lens[i]; }
             w.has_job = true;
+            w.flag.store(true, std::memory_order_release);
         }
         w.cv.notify_one();
         for (int32_t i = 0; i < count; ++i) { dispatch_us[ids[i]] = t; k_used[ids[i]] = k; element[ids[i]] = ne; }
@@ -258,7 +261,7 @@ extern "C" int sp_serve_replay(const sp_model* model, const sp_serve_config* cfg
     }
     // stop the workers (a worker that is still inside a forward finishes it first)
     for (auto& w : workers) {
-        { std::lock_guard<std::mutex> lk(w.mu); w.stop = true; }
+        { std::lock_guard<std::mutex> lk(w.mu); w.stop = true; w.flag.store(true, std::memory_order_release); }
         w.cv.notify_one();
     }
     for (auto& w : workers) w.th.join();
