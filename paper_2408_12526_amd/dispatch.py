@@ -1,19 +1,16 @@
 """Thin binding over the host-side dispatching ABI of libsp_mi355x.so (include/sp_dispatch.h): the length-aware
 buffer, the student-number controller and the dispatcher loop in virtual time.
 
-Argument marshalling only; the data structures and the loop are the library's C++.  No GPU and no torch are needed
-for these calls (they produce the packed batch and k_active that sp_forward consumes).
+Argument marshalling only; the data structures and the loop are the library's C++.  Apart from serve_replay no call
+here touches the GPU (they produce the packed batch and k_active that sp_forward consumes).
 """
 from __future__ import annotations
 
 import ctypes as C
-import os
 from dataclasses import dataclass
 
 import numpy as np
 
-_HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libsp_mi355x.so")
 SP_EFULL, SP_EEMPTY = -6, -7
 
 
@@ -24,9 +21,10 @@ class sp_sim_config(C.Structure):
 
 
 def _load() -> C.CDLL:
-    if not os.path.exists(LIB_PATH):
-        raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2408_12526_amd.build` (there is no fallback path)")
-    lib = C.CDLL(LIB_PATH)
+    # The library is taken from the sp module, which imports torch before loading it: the process must end up with one
+    # HIP runtime (torch's), also when this module is imported first and only the host-side calls are used.
+    from . import sp as _sp
+    lib = _sp.raw_lib()
     vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
     pi32 = C.POINTER(C.c_int32)
     lib.sp_lab_create.restype = C.c_int; lib.sp_lab_create.argtypes = [i32, i32, i32, i32, C.POINTER(vp)]
