@@ -247,7 +247,8 @@ static int run_students(const sp_model* M0, const WsLayout& W, const int32_t* id
     char *cx = w + W.cx + m0 * cH, *cq = w + W.cq + m0 * cH, *catt = w + W.catt + m0 * cH, *cu2 = w + W.cu_ + m0 * cH;
     char *cx1 = w + W.cx1 + m0 * cH, *cg = w + W.cg + m0 * cF;
     char *cqt = w + W.cqt + m0 * cHH * ab, *cxb = w + W.cxb + m0 * cHH * ab;
-    bool compact_final = false;
+    bool compact_final = false, small_head = false;
+    size_t small_head_lo = 0;
     // Calls of a few dozen tokens: split the reduction range of the two projections that are followed by a LayerNorm
     // (largest slice count that leaves every slice at least two 64-wide k-tiles).
     const size_t slice = (size_t)kSplitRows * H;
@@ -321,8 +322,15 @@ static int run_students(const sp_model* M0, const WsLayout& W, const int32_t* id
         if (split_d > 1) {
             SP_TRY(launch_gemm_splitk(M, g, F, lo + L.w2, part, mrows, H, F, k, split_d, sF, slice, s));
             SP_MARK(SP_PHASE_FFN_DOWN);
-            SP_TRY(launch_ln_reduce(M, part, split_d, slice, lo + L.b2, x1, x, rows, mrows, k, lo + L.ln2g, lo + L.ln2b, s));
-            SP_MARK(SP_PHASE_LAYERNORM);
+            if (with_head && l == c.layers - 1 && m0 == 0) {
+                // last layer of a whole forward: only the first-token rows go on, and the head rebuilds them from the
+                // slices itself
+                small_head = true;
+                small_head_lo = lo;
+            } else {
+                SP_TRY(launch_ln_reduce(M, part, split_d, slice, lo + L.b2, x1, x, rows, mrows, k, lo + L.ln2g, lo + L.ln2b, s));
+                SP_MARK(SP_PHASE_LAYERNORM);
+            }
         } else {
             SP_TRY(launch_gemm(M, g, F, lo + L.w2, lo + L.b2, u, H, x1, H, mrows, H, F, k, EPI_BIAS_RESIDUAL, sF, sH, sH,
                                s));
@@ -338,7 +346,10 @@ static int run_students(const sp_model* M0, const WsLayout& W, const int32_t* id
             // first tokens stay readable after the call)
             SP_TRY(launch_gemm(M, cx, H, L.wp_t, L.bp, cu2, H, nullptr, 0, cmrows, H, H, k, EPI_BIAS_TANH, cH, cH, 0, s));
             SP_TRY(launch_head_classify(M, cu2, B, crows, k, z, logits, s));
-        } else
+        } else if (small_head)
+            SP_TRY(launch_head_small(M, part, split_d, slice, small_head_lo + L.b2, x1, small_head_lo + L.ln2g,
+                                     small_head_lo + L.ln2b, cu, B, T, rows, k, z, zpart, logits, s));
+        else
             SP_TRY(launch_head(M, x, cu, B, T, rows, k, z, zpart, logits, s));
         SP_MARK(SP_PHASE_HEAD);
     }

@@ -253,6 +253,80 @@ __global__ __launch_bounds__(256) void gather_first_kernel(const T* __restrict__
 // sum_{n in slice} pooled[n] Wc[n][c], goes to zpart[m][slice][b][c].
 constexpr int kSeqPerWg = 8;
 
+// Pooler pre-activations of one slice of 64 outputs for up to kSeqPerWg rows held in LDS (xs[s][H], fp32):
+// red[(wave * kSeqPerWg + s) * 64 + n] = sum over the wave's quarter of the inputs i of xs[s][i] * Wp[i][slice * 64 + n].
+// A lane fetches 16 bytes (8 outputs) of a weight row, so a wave instruction covers 8 rows of the slice and the wave's
+// H / 4 rows are H / 32 instructions per lane, requested sixteen at a time (2-byte loads, one row per instruction,
+// took four times as many round trips: the pooler was the longest kernel of a single-sequence call; requesting all
+// rows before the token rows are gathered was measured slower than two batches afterwards).  The 8 lanes that share
+// an output chunk are then added with shuffles.
+template <typename T>
+struct RawRow;
+template <>
+struct RawRow<bf16> {
+    bf16x8 v;
+    __device__ void load(const bf16* p) { v = *(const bf16x8*)p; }
+    __device__ float get(int e) const { return (float)v[e]; }
+};
+template <>
+struct RawRow<float> {
+    f32x4 a, b;
+    __device__ void load(const float* p) { a = *(const f32x4*)p; b = *(const f32x4*)(p + 4); }
+    __device__ float get(int e) const { return e < 4 ? a[e] : b[e - 4]; }
+};
+
+template <typename T>
+struct PoolerWeights {
+    static constexpr int NB = sizeof(T) == 2 ? 16 : 8;       // weight rows in flight per lane
+    RawRow<T> w[NB];
+    const T* base;
+    int nj, stride;
+    __device__ void request(const T* Wp, int H, int slice, int lane, int wv)   // addresses only
+    {
+        nj = H / 32;                                          // rows per lane: the wave's H / 4 rows, 8 per instruction
+        stride = 8 * H;
+        base = Wp + (size_t)(wv * (H / 4) + (lane >> 3)) * H + slice * 64 + (lane & 7) * 8;
+    }
+    __device__ void multiply(const float* xs, float* red, int H, int nseq, int lane, int wv)
+    {
+        const int c8 = (lane & 7) * 8, rl = lane >> 3, row0 = wv * (H / 4) + rl;
+        float acc[kSeqPerWg][8];
+#pragma unroll
+        for (int s = 0; s < kSeqPerWg; ++s)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[s][e] = 0.f;
+        for (int j0 = 0; j0 < nj; j0 += NB) {
+#pragma unroll
+            for (int jj = 0; jj < NB; ++jj)
+                if (j0 + jj < nj) w[jj].load(base + (size_t)(j0 + jj) * stride);
+#pragma unroll
+            for (int jj = 0; jj < NB; ++jj)
+                if (j0 + jj < nj) {
+                    const int i = row0 + (j0 + jj) * 8;
+#pragma unroll
+                    for (int s = 0; s < kSeqPerWg; ++s)
+                        if (s < nseq) {
+                            const float xv = xs[s * H + i];
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) acc[s][e] += xv * w[jj].get(e);
+                        }
+                }
+        }
+#pragma unroll
+        for (int s = 0; s < kSeqPerWg; ++s)
+            if (s < nseq) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    float a = acc[s][e];
+                    a += __shfl_xor(a, 8);
+                    a += __shfl_xor(a, 16);
+                    a += __shfl_xor(a, 32);
+                    if (rl == 0) red[(wv * kSeqPerWg + s) * 64 + c8 + e] = a;
+                }
+            }
+    }
+};
+
 template <typename T>
 __global__ __launch_bounds__(256) void head_pool_kernel(const char* arena, size_t student_stride, size_t wp_off,
                                                         size_t bp_off, size_t wc_off, const T* __restrict__ x,
@@ -265,6 +339,9 @@ __global__ __launch_bounds__(256) void head_pool_kernel(const char* arena, size_
     const int b0 = blockIdx.x * kSeqPerWg, m = blockIdx.y, slice = blockIdx.z, nslice = gridDim.z;
     const int tid = threadIdx.x, lane = tid & 63, part = tid >> 6;
     const int nseq = (B - b0) < kSeqPerWg ? (B - b0) : kSeqPerWg;
+    const char* sb = arena + (size_t)m * student_stride;
+    PoolerWeights<T> pw;
+    pw.request((const T*)(sb + wp_off), H, slice, lane, part);
     for (int s = 0; s < nseq; ++s) {
         int r = cu ? cu[b0 + s] : b0 + s;    // packed layout: first token of the sequence; compact layout: row b
         r = r < 0 ? 0 : (r >= Tn ? Tn - 1 : r);
@@ -272,26 +349,8 @@ __global__ __launch_bounds__(256) void head_pool_kernel(const char* arena, size_
         for (int i = tid; i < H; i += 256) xs[s * H + i] = (float)src[i];
     }
     __syncthreads();
-    const char* sb = arena + (size_t)m * student_stride;
-    const T* Wp = (const T*)(sb + wp_off);
     const int n = slice * 64 + lane;
-    float acc[kSeqPerWg];
-#pragma unroll
-    for (int s = 0; s < kSeqPerWg; ++s) acc[s] = 0.f;
-    const int per = H / 4, i0 = part * per;   // this wave's share of the reduction index (a multiple of 16)
-#pragma unroll 8
-    for (int i = i0; i < i0 + per; i += 4) {     // unrolled: 32 weight loads in flight per lane
-        float w[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) w[e] = (float)Wp[(size_t)(i + e) * H + n];
-#pragma unroll
-        for (int s = 0; s < kSeqPerWg; ++s) {    // rows beyond nseq hold stale data: their sums are never used
-            const f32x4 xv = *(const f32x4*)&xs[s * H + i];
-            acc[s] += xv[0] * w[0] + xv[1] * w[1] + xv[2] * w[2] + xv[3] * w[3];
-        }
-    }
-#pragma unroll
-    for (int s = 0; s < kSeqPerWg; ++s) red[(part * kSeqPerWg + s) * 64 + lane] = acc[s];
+    pw.multiply(xs, red, H, nseq, lane, part);
     __syncthreads();
     // wave `part` finishes sequences part, part+4: fixed order over the four shares
     const float bpn = ((const float*)(sb + bp_off))[n];
@@ -337,6 +396,101 @@ __global__ __launch_bounds__(256) void head_sum_kernel(const char* arena, size_t
         float total = 0.f;
         for (int m = 0; m < k; ++m) total += zs[m][ox];
         logits[idx] = total;
+    }
+}
+
+// Stage 1 of the head for calls of a few dozen tokens (same grid and pooler as head_pool_kernel): the first-token
+// rows are rebuilt from the slices of the last split reduction: slices (ascending) + bias + residual, LayerNorm,
+// rounded to bf16: exactly what ln_reduce_kernel would have stored for these rows (the other rows of the last layer
+// reach no result, so that launch is saved).  Taking the sums of stage 2 in the workgroup that finishes last (a ticket
+// counter after a device-scope fence) was measured slower than the launch of head_sum_kernel it saves.
+__global__ __launch_bounds__(256) void head_small_kernel(const char* arena, size_t student_stride, size_t wp_off,
+                                                         size_t bp_off, size_t wc_off, size_t bc_off, size_t g_off,
+                                                         size_t b_off, size_t bias_off, const float* __restrict__ part,
+                                                         int splits, size_t slice_elems, const bf16* __restrict__ res,
+                                                         const int32_t* __restrict__ cu, int B, int Tn, int rows, int H,
+                                                         int C, float eps, float* __restrict__ zpart)
+{
+    extern __shared__ float smem[];
+    float* xs = smem;                      // [kSeqPerWg][H]
+    float* red = smem + kSeqPerWg * H;     // [4][kSeqPerWg][64]
+    const int b0 = blockIdx.x * kSeqPerWg, m = blockIdx.y, slice = blockIdx.z, nslice = gridDim.z;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int nseq = (B - b0) < kSeqPerWg ? (B - b0) : kSeqPerWg;
+    const char* sb = arena + (size_t)m * student_stride;
+    const float* bias = (const float*)(sb + bias_off);
+    const float* gam = (const float*)(sb + g_off);
+    const float* bet = (const float*)(sb + b_off);
+    PoolerWeights<bf16> pw;
+    pw.request((const bf16*)(sb + wp_off), H, slice, lane, wv);
+    // A thread owns elements tid + 256 j of a row (H <= 1024: j < 4).  Everything a row needs is requested before
+    // anything is used (a loop that loads and uses per element would pay one memory round trip per iteration).
+    constexpr int MAXJ = 4;                // hidden <= 1024 (checked by the launcher)
+    __shared__ float wsum[2][4];
+    float gj[MAXJ], bj[MAXJ], biasj[MAXJ];
+#pragma unroll
+    for (int j = 0; j < MAXJ; ++j) {
+        const int i = tid + 256 * j;
+        gj[j] = i < H ? gam[i] : 0.f;
+        bj[j] = i < H ? bet[i] : 0.f;
+        biasj[j] = i < H ? bias[i] : 0.f;
+    }
+    for (int s = 0; s < nseq; ++s) {
+        int r = cu[b0 + s];
+        r = r < 0 ? 0 : (r >= Tn ? Tn - 1 : r);
+        const bf16* rrow = res + ((size_t)m * rows + r) * H;
+        const float* prow = part + (size_t)m * splits * slice_elems + (size_t)r * H;
+        float v[MAXJ], p8[MAXJ][kSplitMax];
+#pragma unroll
+        for (int j = 0; j < MAXJ; ++j) {
+            const int i = tid + 256 * j;
+            v[j] = i < H ? (float)rrow[i] : 0.f;
+#pragma unroll
+            for (int sidx = 0; sidx < kSplitMax; ++sidx)
+                p8[j][sidx] = i < H && sidx < splits ? prow[(size_t)sidx * slice_elems + i] : 0.f;
+        }
+        float sum = 0.f;
+#pragma unroll
+        for (int j = 0; j < MAXJ; ++j) {
+            v[j] += biasj[j];
+#pragma unroll
+            for (int sidx = 0; sidx < kSplitMax; ++sidx)      // slices in ascending order
+                if (sidx < splits) v[j] += p8[j][sidx];
+            if (tid + 256 * j < H) sum += v[j];
+        }
+        sum = wave_sum(sum);
+        if (lane == 0) wsum[0][wv] = sum;
+        __syncthreads();
+        const float mean = (wsum[0][0] + wsum[0][1] + wsum[0][2] + wsum[0][3]) / (float)H;
+        float q = 0.f;
+#pragma unroll
+        for (int j = 0; j < MAXJ; ++j)
+            if (tid + 256 * j < H) { const float d = v[j] - mean; q += d * d; }
+        q = wave_sum(q);
+        if (lane == 0) wsum[1][wv] = q;
+        __syncthreads();
+        const float inv = 1.0f / sqrtf((wsum[1][0] + wsum[1][1] + wsum[1][2] + wsum[1][3]) / (float)H + eps);
+#pragma unroll
+        for (int j = 0; j < MAXJ; ++j) {
+            const int i = tid + 256 * j;
+            if (i < H) xs[s * H + i] = (float)(bf16)(gj[j] * ((v[j] - mean) * inv) + bj[j]);
+        }
+        __syncthreads();                       // wsum is rewritten for the next row; xs is read by everybody below
+    }
+    const int n = slice * 64 + lane;
+    pw.multiply(xs, red, H, nseq, lane, wv);
+    __syncthreads();
+    const float bpn = ((const float*)(sb + bp_off))[n];
+    const bf16* Wc = (const bf16*)(sb + wc_off);
+    for (int s = wv; s < nseq; s += 4) {
+        float p = bpn;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) p += red[(q * kSeqPerWg + s) * 64 + lane];
+        p = tanhf(p);
+        for (int c = 0; c < C; ++c) {
+            const float t = wave_sum(p * (float)Wc[(size_t)n * C + c]);
+            if (lane == 0) zpart[(((size_t)m * nslice + slice) * B + (b0 + s)) * C + c] = t;
+        }
     }
 }
 
@@ -470,6 +624,28 @@ hipError_t launch_gather_first(const sp_model* M, const void* x, const int32_t* 
     else
         hipLaunchKernelGGL(gather_first_kernel<float>, grid, dim3(256), 0, s, (const float*)x, cu, B, T, rows, c.hidden,
                            (float*)xc, (float*)attc, crows, cmrows);
+    return hipGetLastError();
+}
+
+hipError_t launch_head_small(const sp_model* M, const float* partials, int splits, size_t slice_elems, size_t bias_off,
+                             const void* residual, size_t g_off, size_t b_off, const int32_t* cu, int B, int T, int rows,
+                             int k, float* z, float* zpart, float* logits, hipStream_t s)
+{
+    const sp_config& c = M->cfg;
+    const ArenaLayout& L = M->L;
+    if (c.dtype != SP_DTYPE_BF16 || splits < 1 || splits > kSplitMax || c.hidden > 1024 || k > kSumStudents)
+        return hipErrorInvalidValue;
+    const int nslice = c.hidden / 64;
+    dim3 grid((B + kSeqPerWg - 1) / kSeqPerWg, k, nslice);
+    const size_t smem = (size_t)(kSeqPerWg * c.hidden + 4 * kSeqPerWg * 64) * sizeof(float);
+    hipLaunchKernelGGL(head_small_kernel, grid, dim3(256), smem, s, M->arena, L.student_stride, L.wp, L.bp, L.wc, L.bc,
+                       g_off, b_off, bias_off, partials, splits, slice_elems, (const bf16*)residual, cu, B, T, rows,
+                       c.hidden, c.classes, c.ln_eps, zpart);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int n = B * c.classes;
+    hipLaunchKernelGGL(head_sum_kernel, dim3((n + 31) / 32), dim3(256), 0, s, M->arena, L.student_stride, L.bc, zpart, B,
+                       c.classes, k, nslice, z, logits);
     return hipGetLastError();
 }
 

@@ -135,4 +135,11 @@ hipError_t launch_sum_students(const float* z, int n, int k, float* logits, hipS
 hipError_t launch_head(const sp_model* M, const void* x, const int32_t* cu, int B, int T, int rows, int k, float* z,
                        float* zpart, float* logits, hipStream_t s);
 
+// The same head for calls of a few dozen tokens: stage 1 rebuilds the first-token rows from the slices of the last split
+// reduction (+ bias + residual + LayerNorm: what launch_ln_reduce would have written), so that launch is not needed
+// for the last layer of a whole forward.  bf16 only.
+hipError_t launch_head_small(const sp_model* M, const float* partials, int splits, size_t slice_elems, size_t bias_off,
+                             const void* residual, size_t g_off, size_t b_off, const int32_t* cu, int B, int T, int rows,
+                             int k, float* z, float* zpart, float* logits, hipStream_t s);
+
 }  // namespace sp
