@@ -340,8 +340,6 @@ __global__ __launch_bounds__(256) void head_pool_kernel(const char* arena, size_
     const int tid = threadIdx.x, lane = tid & 63, part = tid >> 6;
     const int nseq = (B - b0) < kSeqPerWg ? (B - b0) : kSeqPerWg;
     const char* sb = arena + (size_t)m * student_stride;
-    PoolerWeights<T> pw;
-    pw.request((const T*)(sb + wp_off), H, slice, lane, part);
     for (int s = 0; s < nseq; ++s) {
         int r = cu ? cu[b0 + s] : b0 + s;    // packed layout: first token of the sequence; compact layout: row b
         r = r < 0 ? 0 : (r >= Tn ? Tn - 1 : r);
@@ -350,7 +348,33 @@ __global__ __launch_bounds__(256) void head_pool_kernel(const char* arena, size_
     }
     __syncthreads();
     const int n = slice * 64 + lane;
-    pw.multiply(xs, red, H, nseq, lane, part);
+    if (nseq <= 2) {
+        // one or two sequences: latency of the weight fetch is all there is, wide loads (see PoolerWeights)
+        PoolerWeights<T> pw;
+        pw.request((const T*)(sb + wp_off), H, slice, lane, part);
+        pw.multiply(xs, red, H, nseq, lane, part);
+    } else {
+        // a full group of sequences: a lane owns one output for all of them (measured faster than the wide loads,
+        // whose eight-outputs-per-lane sums need 64 accumulators and a shuffle reduction per sequence)
+        const T* Wp = (const T*)(sb + wp_off);
+        float acc[kSeqPerWg];
+#pragma unroll
+        for (int s = 0; s < kSeqPerWg; ++s) acc[s] = 0.f;
+        const int per = H / 4, i0 = part * per;   // this wave's share of the reduction index (a multiple of 16)
+#pragma unroll 8
+        for (int i = i0; i < i0 + per; i += 4) {     // unrolled: 32 weight loads in flight per lane
+            float w[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) w[e] = (float)Wp[(size_t)(i + e) * H + n];
+#pragma unroll
+            for (int s = 0; s < kSeqPerWg; ++s) {    // rows beyond nseq hold stale data: their sums are never used
+                const f32x4 xv = *(const f32x4*)&xs[s * H + i];
+                acc[s] += xv[0] * w[0] + xv[1] * w[1] + xv[2] * w[2] + xv[3] * w[3];
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < kSeqPerWg; ++s) red[(part * kSeqPerWg + s) * 64 + lane] = acc[s];
+    }
     __syncthreads();
     // wave `part` finishes sequences part, part+4: fixed order over the four shares
     const float bpn = ((const float*)(sb + bp_off))[n];
