@@ -302,6 +302,40 @@ def test_large_calls_on_other_widths(sp, oracle64, name):
     check_logits(got2[pick], want, shape, name + " all-token last layer")
 
 
+BOUNDARY_TOKENS = [63, 64, 65, 127, 128, 129, 255, 256, 257, 1023, 1024, 1025, 2047, 2048, 2049]
+
+
+@pytest.mark.parametrize("total", BOUNDARY_TOKENS)
+def test_call_sizes_at_every_path_boundary(sp, oracle64, total):
+    """The forward changes its launch plan with the size of the call: split reductions and the fused head up to 128
+    token rows, 64 / 128 / 256-row projection tiles, the first-token last layer from 1024 tokens, two groups of
+    students and the long-call LayerNorm from 2048.  One call just below, at and just above each boundary, against the
+    oracle (a sample of the sequences for the large ones), with k_active below and at K."""
+    shape = synth.StudentShape(K=3, layers=2, hidden=256, heads=4, ffn=1024, vocab=800, max_pos=160, classes=3,
+                               dtype="bf16")
+    rng = np.random.default_rng(1000 + total)
+    lengths = []
+    left = total
+    while left > 0:
+        n = int(min(left, rng.integers(1, 150)))
+        lengths.append(n)
+        left -= n
+    lengths = np.array(lengths, dtype=np.int32)
+    assert lengths.sum() == total
+    ids = synth.make_ids(rng, total, shape.vocab)
+    blob = synth.make_weights(rng, shape, std=0.02, ln_random=True, qk_std=float(np.sqrt(1.5 / shape.hidden)))
+    st = sp.Students(sp.config_from_shape(shape), blob)
+    d_ids, d_cu, cu = gpu_inputs(lengths, ids, sp)
+    pick = np.arange(len(lengths)) if len(lengths) <= 8 else np.sort(rng.choice(len(lengths), size=8, replace=False))
+    sub_ids = np.concatenate([ids[cu[b]:cu[b + 1]] for b in pick])
+    sub_cu = np.concatenate([[0], np.cumsum(lengths[pick])]).astype(np.int32)
+    ow = oracle_weights(blob, shape)
+    for k in (2, 3):
+        got = st.sp_forward(d_ids, d_cu, int(lengths.max()), k).cpu().numpy().astype(np.float64)
+        want = oracle64.forward(ocfg(shape), ow, sub_ids, sub_cu, k)
+        check_logits(got[pick], want, shape, f"{total} tokens, k_active={k}")
+
+
 # ---- the five workloads ----------------------------------------------------------------------------
 
 _cache = {}
