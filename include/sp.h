@@ -143,12 +143,28 @@ const char* sp_strerror(int code);
  * length is < 1 or the total exceeds INT32_MAX. */
 int sp_pack(const int32_t* lengths_host, int32_t batch, int32_t* cu_seqlens_host);
 
+/* Contents check of the device-resident inputs of a forward, for callers that cannot vouch for them (sp_forward
+ * itself never inspects them: that would need a synchronisation; it clamps on the device instead).  One small kernel
+ * on hip_stream, then a synchronous copy of one word: this call blocks.  *problems_host receives a bit set:
+ *   SP_BAD_ID       a token id outside 0..V-1
+ *   SP_BAD_CU0      cu_seqlens[0] != 0
+ *   SP_BAD_ORDER    an offset not larger than its predecessor (a sequence of length < 1)
+ *   SP_BAD_LENGTH   a sequence longer than max_seqlen
+ *   SP_BAD_TOTAL    cu_seqlens[batch] != total_tokens
+ * scratch: device, >= 4 bytes, 4-byte aligned (any part of a workspace will do; its first word is overwritten).
+ * Errors: SP_EINVAL, SP_ESHAPE (batch < 1, total_tokens < batch, max_seqlen outside 1..P), SP_EHIP. */
+enum { SP_BAD_ID = 1, SP_BAD_CU0 = 2, SP_BAD_ORDER = 4, SP_BAD_LENGTH = 8, SP_BAD_TOTAL = 16 };
+int sp_check_inputs(const sp_model* model, const int32_t* token_ids, const int32_t* cu_seqlens, int32_t batch,
+                    int32_t total_tokens, int32_t max_seqlen, void* scratch, void* hip_stream,
+                    int32_t* problems_host);
+
 /* Byte offsets, inside a workspace laid out for (total_tokens, batch), of the
  * intermediate activations a forward leaves behind; for tests and profiling.
  * Each activation tensor is [k_active][rows][width] with `rows` >= total_tokens
  * (token-tile padded) in the model's activation type (float or bf16), row-major.
- *   x    [rows][H]  hidden state entering the next layer (after the last layer:
- *                   the final states)
+ *   x    [rows][H]  hidden state entering the next layer (after the last layer of a
+ *                   partial forward: the final states; a whole forward forms the
+ *                   final states of the first-token rows only where it can)
  *   qkv  [rows][3H] query | key | value projections of the last layer run; in bf16
  *                   mode the value slice is not written: the values are kept
  *                   transposed for the attention kernel, in

@@ -555,6 +555,23 @@ const char* sp_strerror(int code)
     }
 }
 
+int sp_check_inputs(const sp_model* model, const int32_t* token_ids, const int32_t* cu_seqlens, int32_t batch,
+                    int32_t total_tokens, int32_t max_seqlen, void* scratch, void* hip_stream, int32_t* problems_host)
+{
+    if (!model || !token_ids || !cu_seqlens || !scratch || !problems_host || ((uintptr_t)scratch & 3)) return SP_EINVAL;
+    if (batch < 1 || total_tokens < batch || max_seqlen < 1 || max_seqlen > model->cfg.max_pos) return SP_ESHAPE;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (sp::launch_check_inputs(token_ids, cu_seqlens, batch, total_tokens, max_seqlen, model->cfg.vocab,
+                                (unsigned*)scratch, s) != hipSuccess)
+        return SP_EHIP;
+    unsigned flags = 0;
+    if (hipMemcpyAsync(&flags, scratch, sizeof flags, hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess)
+        return SP_EHIP;
+    *problems_host = (int32_t)flags;
+    return SP_OK;
+}
+
 int sp_pack(const int32_t* lengths_host, int32_t batch, int32_t* cu_seqlens_host)
 {
     if (!lengths_host || !cu_seqlens_host) return SP_EINVAL;

@@ -613,6 +613,42 @@ hipError_t launch_layernorm(const sp_model* M, const void* u, void* out, int row
     return hipGetLastError();
 }
 
+// Contents check of a forward's inputs (sp_check_inputs): every thread looks at a strided share of the ids and of the
+// offsets and ORs what it finds into one word.
+__global__ void clear_word_kernel(unsigned* w) { *w = 0u; }
+
+__global__ __launch_bounds__(256) void check_inputs_kernel(const int32_t* __restrict__ ids,
+                                                           const int32_t* __restrict__ cu, int B, int Tn, int max_seqlen,
+                                                           int V, unsigned* flags)
+{
+    unsigned bad = 0;
+    const int stride = gridDim.x * blockDim.x, first = blockIdx.x * blockDim.x + threadIdx.x;
+    for (int i = first; i < Tn; i += stride) {
+        const int id = ids[i];
+        if (id < 0 || id >= V) bad |= SP_BAD_ID;
+    }
+    for (int b = first; b < B; b += stride) {
+        const int a = cu[b], e = cu[b + 1];
+        if (e <= a) bad |= SP_BAD_ORDER;
+        else if (e - a > max_seqlen) bad |= SP_BAD_LENGTH;
+    }
+    if (first == 0) {
+        if (cu[0] != 0) bad |= SP_BAD_CU0;
+        if (cu[B] != Tn) bad |= SP_BAD_TOTAL;
+    }
+    if (bad) atomicOr(flags, bad);
+}
+
+hipError_t launch_check_inputs(const int32_t* ids, const int32_t* cu, int B, int T, int max_seqlen, int vocab,
+                               unsigned* flags, hipStream_t s)
+{
+    hipLaunchKernelGGL(clear_word_kernel, dim3(1), dim3(1), 0, s, flags);
+    const int blocks = (T + 255) / 256 < 1024 ? (T + 255) / 256 : 1024;
+    hipLaunchKernelGGL(check_inputs_kernel, dim3(blocks < 1 ? 1 : blocks), dim3(256), 0, s, ids, cu, B, T, max_seqlen,
+                       vocab, flags);
+    return hipGetLastError();
+}
+
 hipError_t launch_sum_students(const float* z, int n, int k, float* logits, hipStream_t s)
 {
     hipLaunchKernelGGL(sum_students_kernel, dim3((n + 255) / 256), dim3(256), 0, s, z, n, k, logits);

@@ -128,6 +128,10 @@ hipError_t launch_attention_first_fold(const sp_model* M, const void* x, const v
 hipError_t launch_head_classify(const sp_model* M, const void* pooled, int B, int crows, int k, float* z, float* logits,
                                 hipStream_t s);
 
+// flags[0] |= SP_BAD_* bits for the inputs of a forward (flags[0] is cleared first, on the same stream).
+hipError_t launch_check_inputs(const int32_t* ids, const int32_t* cu, int B, int T, int max_seqlen, int vocab,
+                               unsigned* flags, hipStream_t s);
+
 // logits[i] = sum_{m<k} z[m][i], m ascending (i < n).
 hipError_t launch_sum_students(const float* z, int n, int k, float* logits, hipStream_t s);
 

@@ -17,6 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsp_mi355x.so")
 
 SP_DTYPE_FP32, SP_DTYPE_BF16 = 0, 1
+SP_BAD_ID, SP_BAD_CU0, SP_BAD_ORDER, SP_BAD_LENGTH, SP_BAD_TOTAL = 1, 2, 4, 8, 16
 PHASES = ("embed", "qkv", "attention", "oproj", "layernorm", "ffn_up", "ffn_down", "head", "last_first")
 
 
@@ -52,6 +53,8 @@ def _load() -> C.CDLL:
     lib.sp_free.restype = None; lib.sp_free.argtypes = [vp]
     lib.sp_strerror.restype = C.c_char_p; lib.sp_strerror.argtypes = [C.c_int]
     lib.sp_pack.restype = C.c_int; lib.sp_pack.argtypes = [vp, i32, vp]
+    lib.sp_check_inputs.restype = C.c_int
+    lib.sp_check_inputs.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, C.POINTER(C.c_int32)]
     lib.sp_workspace_layout.restype = C.c_int
     lib.sp_workspace_layout.argtypes = [cfgp, i32, i32, C.POINTER(sp_ws_layout)]
     return lib
@@ -149,6 +152,15 @@ class Students:
         _check(_lib.sp_forward(self.handle, token_ids.data_ptr(), cu_seqlens.data_ptr(), batch, total, max_seqlen,
                                k_active, ws.data_ptr(), ws.numel(), logits_out.data_ptr(), _stream_ptr(stream)))
         return logits_out
+
+    def sp_check_inputs(self, token_ids: torch.Tensor, cu_seqlens: torch.Tensor, max_seqlen: int, stream=None) -> int:
+        """Bit set of SP_BAD_* problems found in the device-resident inputs of a forward (0: none).  Blocks."""
+        scratch = torch.empty(64, dtype=torch.int32, device=self.device)
+        out = C.c_int32()
+        _check(_lib.sp_check_inputs(self.handle, token_ids.data_ptr(), cu_seqlens.data_ptr(), cu_seqlens.numel() - 1,
+                                    token_ids.numel(), max_seqlen, scratch.data_ptr(), _stream_ptr(stream),
+                                    C.byref(out)))
+        return out.value
 
     def sp_forward_profiled(self, token_ids, cu_seqlens, max_seqlen, k_active, logits_out=None, workspace=None,
                             stream=None) -> dict:

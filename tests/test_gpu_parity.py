@@ -496,3 +496,29 @@ def test_error_codes(sp):
     with pytest.raises(sp.SpError) as e:
         sp.Students(bad, np.zeros(sp.sp_blob_floats(bad), np.float32))
     assert e.value.code == -2
+
+
+def test_input_contents_check(sp):
+    """sp_check_inputs flags what sp_forward cannot see without a synchronisation: ids outside the vocabulary,
+    offsets that do not start at 0, do not increase, describe a sequence longer than max_seqlen, or do not end at the
+    token count."""
+    shape = synth.StudentShape(K=1, layers=1, hidden=128, heads=2, ffn=128, vocab=50, max_pos=64, classes=2, dtype="bf16")
+    rng = np.random.default_rng(3)
+    st = sp.Students(sp.config_from_shape(shape), synth.make_weights(rng, shape))
+    lengths = np.array([5, 30, 1, 64, 17], dtype=np.int32)
+    ids = synth.make_ids(rng, int(lengths.sum()), shape.vocab)
+    d_ids, d_cu, cu = gpu_inputs(lengths, ids, sp)
+    assert st.sp_check_inputs(d_ids, d_cu, 64) == 0
+    assert st.sp_check_inputs(d_ids, d_cu, 63) == sp.SP_BAD_LENGTH
+    bad = d_ids.clone(); bad[40] = shape.vocab
+    assert st.sp_check_inputs(bad, d_cu, 64) == sp.SP_BAD_ID
+    bad[3] = -1
+    assert st.sp_check_inputs(bad, d_cu, 64) == sp.SP_BAD_ID
+    c = d_cu.clone(); c[0] = 1
+    assert st.sp_check_inputs(d_ids, c, 64) & sp.SP_BAD_CU0
+    c = d_cu.clone(); c[2] = c[1]                          # an empty sequence
+    assert st.sp_check_inputs(d_ids, c, 64) == sp.SP_BAD_ORDER
+    c = d_cu.clone(); c[-1] += 1                           # last sequence 18 tokens, one more than there are ids
+    assert st.sp_check_inputs(d_ids, c, 64) == sp.SP_BAD_TOTAL
+    with pytest.raises(sp.SpError):
+        st.sp_check_inputs(d_ids, d_cu, 65)                # max_seqlen beyond the position table
