@@ -118,7 +118,10 @@ int sp_dispatch_simulate(const sp_sim_config* cfg, const int64_t* arrival_us, co
  * dispatch, logits back, stream synchronisation.  A sample's latency done_us - arrival_us therefore includes both
  * PCIe copies.  slots / k_min worker threads are started; slots / k of them take work while k students are active.
  * Unlike sp_forward this call allocates (once, before the replay starts: device buffers of slots / k_min groups for
- * max_elem * max_len tokens each) and blocks until the last sample is done. ---- */
+ * max_elem * max_len tokens each) and blocks until the last sample is done.
+ * The HIP runtime maps a process's streams onto GPU_MAX_HW_QUEUES hardware queues (default 4; read once, at the
+ * process's first HIP call): groups that share a queue serialise their launches, so a process that serves more than
+ * four groups should start with that variable set to the number of groups (8 measured well, 16 worse). ---- */
 typedef struct sp_serve_config {
     int32_t slots, k_min, k_start;  /* total_students is the loaded group's K; k_start 0: K */
     int64_t window_us;
