@@ -5,7 +5,7 @@
 #include <chrono>
 #include <condition_variable>
 #include <cstring>
-#include <deque>
+#include <memory>
 #include <mutex>
 #include <new>
 #include <thread>
@@ -50,7 +50,7 @@ struct Shared {
     std::chrono::steady_clock::time_point t0;
     std::mutex cq_mu;
     std::condition_variable cq_cv;
-    std::deque<int> cq;                  // workers that finished an element
+    std::vector<int> cq;                 // workers that finished an element (room for all of them reserved up front)
     std::atomic<int> cq_count{0};
     std::atomic<int> error{0};
 };
@@ -150,7 +150,14 @@ extern "C" int sp_serve_replay(const sp_model* model, const sp_serve_config* cfg
     const int32_t max_tokens = cfg->max_elem * cfg->max_len;
     S.ws_bytes = sp_workspace_bytes(&mc, max_tokens, cfg->max_elem);
     S.cu_room = (cfg->max_elem + 1 + 63) / 64 * 64;      // keeps the ids 256-byte aligned
-    std::vector<Worker> workers((size_t)nworkers);
+    std::unique_ptr<Worker[]> wstore(new (std::nothrow) Worker[(size_t)nworkers]);
+    if (!wstore) { sp_lab_free(buf); sp_ctl_free(ctl); return SP_ENOMEM; }
+    struct WorkerRange {
+        Worker *b, *e;
+        Worker* begin() const { return b; }
+        Worker* end() const { return e; }
+        Worker& operator[](size_t i) const { return b[i]; }
+    } workers{wstore.get(), wstore.get() + nworkers};
     bool ok = hipGetDevice(&S.device) == hipSuccess && S.ws_bytes > 0;
     for (int g = 0; g < nworkers && ok; ++g) {
         Worker& w = workers[(size_t)g];
@@ -173,9 +180,27 @@ extern "C" int sp_serve_replay(const sp_model* model, const sp_serve_config* cfg
         return SP_EHIP;
     }
     S.t0 = std::chrono::steady_clock::now();
-    for (auto& w : workers) w.th = std::thread(worker_main, &S, &w);
+    std::vector<int> fin, idle;
+    std::vector<int64_t> eid;
+    std::vector<int32_t> elen;
+    try {
+        fin.reserve((size_t)nworkers);
+        idle.reserve((size_t)nworkers);
+        S.cq.reserve((size_t)nworkers);
+        eid.resize((size_t)cfg->max_elem);
+        elen.resize((size_t)cfg->max_elem);
+        for (auto& w : workers) w.th = std::thread(worker_main, &S, &w);
+    } catch (...) {                                     // no memory or no thread: stop what was started
+        for (auto& w : workers) {
+            { std::lock_guard<std::mutex> lk(w.mu); w.stop = true; w.flag.store(true, std::memory_order_release); }
+            w.cv.notify_one();
+            if (w.th.joinable()) w.th.join();
+            release(w);
+        }
+        sp_lab_free(buf); sp_ctl_free(ctl);
+        return SP_ENOMEM;
+    }
 
-    std::vector<int> idle;
     for (int g = nworkers - 1; g >= 0; --g) idle.push_back(g);
     int busy = 0;
     int64_t ne = 0, nref = 0, last_progress = 0;
@@ -198,8 +223,6 @@ extern "C" int sp_serve_replay(const sp_model* model, const sp_serve_config* cfg
         elem_size[ne++] = count;
         ++busy;
     };
-    std::vector<int64_t> eid((size_t)cfg->max_elem);
-    std::vector<int32_t> elen((size_t)cfg->max_elem);
     auto drain = [&] {
         while (sp_lab_elements(buf) > 0 && busy < groups()) {
             int32_t bin, bl, cnt;
@@ -212,10 +235,9 @@ extern "C" int sp_serve_replay(const sp_model* model, const sp_serve_config* cfg
     while ((i < n || busy > 0) && S.error.load() == 0) {
         // completions first
         if (S.cq_count.load() > 0) {
-            std::vector<int> fin;
             {
                 std::lock_guard<std::mutex> lk(S.cq_mu);
-                fin.assign(S.cq.begin(), S.cq.end());
+                fin.assign(S.cq.begin(), S.cq.end());   // at most one entry per worker: within the reserved room
                 S.cq.clear();
                 S.cq_count.store(0);
             }
