@@ -460,11 +460,17 @@ int sp_load_students(const sp_config* cfg, const float* host_weights, size_t nfl
     int rc = SP_OK;
     for (int m0 = 0; m0 < K && rc == SP_OK; m0 += group) {
         const int n = m0 + group <= K ? group : K - m0;
-        std::vector<std::thread> th;
+        std::thread th[4];                  // (group <= 4); a thread that cannot be started is replaced by a plain call
+        for (int i = 0; i < n; ++i) {
+            try {
+                th[i] = std::thread(fill_student, std::cref(*cfg), std::cref(L), host_weights + (size_t)(m0 + i) * per,
+                                    stage + (size_t)i * L.student_stride);
+            } catch (...) {
+                fill_student(*cfg, L, host_weights + (size_t)(m0 + i) * per, stage + (size_t)i * L.student_stride);
+            }
+        }
         for (int i = 0; i < n; ++i)
-            th.emplace_back(fill_student, std::cref(*cfg), std::cref(L), host_weights + (size_t)(m0 + i) * per,
-                            stage + (size_t)i * L.student_stride);
-        for (auto& t : th) t.join();
+            if (th[i].joinable()) th[i].join();
         if (hipMemcpyAsync((char*)device_arena + (size_t)m0 * L.student_stride, stage, (size_t)n * L.student_stride,
                            hipMemcpyHostToDevice, s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess)
             rc = SP_EHIP;
