@@ -10,6 +10,10 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # The tests load the library that is built; only when there is none (a fresh checkout) is it built here.
+    from paper_2408_12526_amd import build as hip_build
+    if not os.path.exists(hip_build.LIB):
+        hip_build.build(verbose=False)
 
 
 @pytest.fixture(scope="session")
