@@ -219,6 +219,9 @@ def main():
         sys.exit(2)
 
     import torch
+    from paper_2408_12526_amd import build as hip_build
+    if not os.path.exists(hip_build.LIB):      # loads what is built; builds only when there is nothing
+        hip_build.build(verbose=False)
     from paper_2408_12526_amd import sp, synth
 
     if not torch.cuda.is_available():
