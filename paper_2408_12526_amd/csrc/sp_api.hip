@@ -90,8 +90,9 @@ WsLayout make_ws_layout(const sp_config& c, int total_tokens, int batch)
     W.g = take(K * rows * F * ab);
     W.z = take(K * (size_t)batch * c.classes * 4);
     W.zpart = take(K * (size_t)(H / 64) * batch * c.classes * 4);
-    // compact buffers for the first-token rows of the last layer
-    const size_t crows = align_up((size_t)batch, kRowPad);
+    // compact buffers for the first-token rows of the last layer (never used by calls of fewer than
+    // kFirstOnlyMinTokens tokens: those get none)
+    const size_t crows = total_tokens >= kFirstOnlyMinTokens ? align_up((size_t)batch, kRowPad) : 0;
     W.cx = take(K * crows * H * ab);
     W.cq = take(K * crows * H * ab);
     W.catt = take(K * crows * H * ab);
@@ -237,7 +238,7 @@ static int run_students(const sp_model* M0, const WsLayout& W, const int32_t* id
     SP_MARK(SP_PHASE_EMBED);
     // Last layer on the first-token rows only (see sp_config.last_layer_all_tokens).  Not used by the partial
     // forwards of the tests unless they stop before the last layer.
-    const bool first_only = !c.last_layer_all_tokens && with_head && T >= 1024 &&
+    const bool first_only = !c.last_layer_all_tokens && with_head && T >= kFirstOnlyMinTokens &&
                             attention_first_fold_supported(c, max_seqlen);
     const int crows = W.crows;
     const int ctile = B > 256 ? 256 : (B > 64 ? 128 : 64);

@@ -21,6 +21,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kRowPad = 256;  // activation rows per student are padded to a multiple of this
 constexpr int kSplitMax = 8;  // slices of a split reduction (small calls only)
 constexpr int kSplitRows = 128;   // most token rows a call may compute and still take the split path
+constexpr int kFirstOnlyMinTokens = 1024;   // smallest call whose last layer runs on the first-token rows only
 
 // Byte offsets of every tensor inside one student's slab of the weight arena.
 // The encoder matrices are stored transposed with respect to the host blob,

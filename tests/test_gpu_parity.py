@@ -355,23 +355,39 @@ def loaded(sp, n):
     return _cache[n]
 
 
-def run_workload(sp, oracle, n, sample=None):
+_terms = {}
+
+
+def oracle_terms(oracle, n, w, ow, batch, cu):
+    """Per-student classifier outputs [K][B][C] of workload n from one oracle run with all K students (kept for the
+    next test on the same workload: the large ones take the oracle tens of seconds)."""
+    key = (n, oracle.kind)
+    if key not in _terms:
+        _terms.clear()
+        print(f"{w.name}: oracle ({oracle.kind}) on all {len(batch.lengths)} sequences, {int(cu[-1])} tokens, "
+              f"{w.shape.K} students", flush=True)
+        _terms[key] = oracle.forward(ocfg(w.shape), ow, batch.ids, cu, w.shape.K, want_terms=True)[1]
+    return _terms[key]
+
+
+def run_workload(sp, oracle, n):
+    """Every logit of workload n, for each of its k_active values, against the oracle.  The oracle runs once with all
+    K students and hands out the per-student terms; its logits for k_active are their sum in student order (what its
+    own forward does: pinned by test_prefix_sums_and_tail_pruning)."""
     w, batch, ow, st = loaded(sp, n)
     d_ids, d_cu, cu = gpu_inputs(batch.lengths, batch.ids, sp)
-    B = len(batch.lengths)
-    pick = np.arange(B) if sample is None or sample >= B else np.sort(
-        np.random.default_rng(5).choice(B, size=sample, replace=False))
-    # the oracle runs the sampled sequences as a batch of their own (samples are independent)
-    sub_ids = np.concatenate([batch.ids[cu[b]:cu[b + 1]] for b in pick])
-    sub_cu = np.concatenate([[0], np.cumsum(batch.lengths[pick])]).astype(np.int32)
+    B, mx = len(batch.lengths), int(batch.lengths.max())
+    terms = oracle_terms(oracle, n, w, ow, batch, cu)
     errs = {}
-    prev = None
     for k in sorted(w.k_actives):
-        got = st.sp_forward(d_ids, d_cu, int(batch.lengths.max()), k).cpu().numpy().astype(np.float64)
-        want = oracle.forward(ocfg(w.shape), ow, sub_ids, sub_cu, k)
-        errs[k] = check_logits(got[pick], want, w.shape, f"{w.name} k_active={k}")
+        got = st.sp_forward(d_ids, d_cu, mx, k).cpu().numpy().astype(np.float64)
+        want = np.zeros_like(terms[0])
+        for m in range(k):
+            want = want + terms[m]
+        assert got.shape == want.shape == (B, w.shape.classes)
         assert np.abs(want).max() > 1e-2
-        prev = got
+        errs[k] = check_logits(got, want, w.shape, f"{w.name} k_active={k}, all {B} sequences")
+        print(f"{w.name} k_active={k}: all {B} sequences compared, error {errs[k]:.3e}", flush=True)
     return errs
 
 
@@ -381,20 +397,58 @@ def test_config1_tiny_fp32(sp, oracle64, oracle32):
     assert max(errs.values()) < 1e-4    # fp32 arithmetic does far better than the 1e-3 gate
 
 
-def test_config2_base_width_b32(sp, oracle64):
-    run_workload(sp, oracle64, 2, sample=6)
+def test_config2_base_width_b32_every_sequence(sp, oracle64):
+    run_workload(sp, oracle64, 2)
 
 
 def test_config3_latency_b1(sp, oracle64):
     run_workload(sp, oracle64, 3)
 
 
-def test_config4_burst_b256_sampled(sp, oracle64):
-    run_workload(sp, oracle64, 4, sample=6)
+def test_config4_burst_b256_every_sequence(sp, oracle64):
+    """All 256 sequences (58 token tiles of 256 rows: the last block of the token-tile-blocked projection order is a
+    partial one, and the last tile is padded)."""
+    run_workload(sp, oracle64, 4)
 
 
-def test_config5_large_width_b64_sampled(sp, oracle64):
-    run_workload(sp, oracle64, 5, sample=2)
+def test_config4_burst_b256_all_token_last_layer_every_sequence(sp, oracle64):
+    """The stock variant (every token through the last layer as well) at full size: the second layer's large-tile
+    projections, attention kernels and LayerNorm on all 14722 rows."""
+    w, batch, ow, _ = loaded(sp, 4)
+    _, blob = synth.make_workload(w)
+    st = sp.Students(sp.config_from_shape(w.shape, last_layer_all_tokens=True), blob)
+    d_ids, d_cu, cu = gpu_inputs(batch.lengths, batch.ids, sp)
+    got = st.sp_forward(d_ids, d_cu, int(batch.lengths.max()), w.shape.K).cpu().numpy().astype(np.float64)
+    st.close()
+    want = oracle_terms(oracle64, 4, w, ow, batch, cu).sum(0)     # (fp64: the order of the sum is immaterial here)
+    check_logits(got, want, w.shape, "c4 all-token last layer, all sequences")
+
+
+def test_config5_large_width_b64_every_sequence(sp, oracle64):
+    """All 64 sequences (64 to 512 tokens, hidden 1024, 16 heads: every attention path at that width, sequences of
+    more than 256 tokens included, 74 token tiles)."""
+    run_workload(sp, oracle64, 5)
+
+
+def test_partial_last_block_of_the_token_tile_order(sp, oracle64):
+    """A small shape that reaches the partial last block of the large projection tile's order: hidden 512 (six
+    256-wide feature tiles in the query/key/value projection, eight in the FFN up-projection) and 11 token tiles of
+    256 rows (blocks of five: 5 + 5 + 1), every sequence against the oracle, both last-layer variants."""
+    shape = synth.StudentShape(K=2, layers=2, hidden=512, heads=8, ffn=2048, vocab=1000, max_pos=128, classes=3,
+                               dtype="bf16")
+    rng = np.random.default_rng(41)
+    lengths = rng.integers(20, 101, size=42).astype(np.int32)
+    total = int(lengths.sum())
+    assert 2560 < total <= 2816, total          # 11 token tiles
+    ids = synth.make_ids(rng, total, shape.vocab)
+    blob = synth.make_weights(rng, shape, std=0.02, ln_random=True, qk_std=float(np.sqrt(1.5 / shape.hidden)))
+    d_ids, d_cu, cu = gpu_inputs(lengths, ids, sp)
+    want = oracle64.forward(ocfg(shape), oracle_weights(blob, shape), ids, cu, shape.K)
+    for all_tokens in (False, True):
+        st = sp.Students(sp.config_from_shape(shape, last_layer_all_tokens=all_tokens), blob)
+        got = st.sp_forward(d_ids, d_cu, int(lengths.max()), shape.K).cpu().numpy().astype(np.float64)
+        check_logits(got, want, shape, f"11 token tiles, all_tokens={all_tokens}")
+        st.close()
 
 
 # ---- properties that hold at any size ----------------------------------------------------------------

@@ -416,3 +416,46 @@ def test_taps_compose_to_the_forward(oracle64):
     np.testing.assert_allclose(t["qkv"][0][:, H:2 * H], t["x0"] @ v["l0.Wk"].astype(np.float64) + v["l0.bk"], atol=1e-12)
     np.testing.assert_allclose(t["att"][0], oracle64.attention(t["qkv"][0][:, :H], t["qkv"][0][:, H:2 * H],
                                                                t["qkv"][0][:, 2 * H:], SMALL.heads), atol=1e-13)
+
+
+def test_every_tap_matches_the_library_bert_layer_by_layer(oracle64):
+    """Every intermediate the oracle can hand out (embedding output, the three projections, attention output, the
+    state after each LayerNorm, the GELU output) against the same tensors inside the library's BERT, taken with
+    forward hooks on one unpadded sequence: a tap that is mislabeled, taken at the wrong point or of the wrong layer
+    fails here."""
+    lengths, ids, blob = small_case(seed=15)
+    cu = oracle64.pack(lengths)
+    m, b = 2, 2
+    t = oracle64.taps(ocfg(SMALL), blob, ids, cu, m, b)
+    model = hf_student(SMALL, synth.student_views(blob, SMALL, m))
+    seen = {}
+
+    def keep(name):
+        def hook(_mod, _inp, out):
+            seen[name] = (out[0] if isinstance(out, tuple) else out)[0].detach().numpy()
+        return hook
+
+    model.bert.embeddings.register_forward_hook(keep("x0"))
+    for l, lay in enumerate(model.bert.encoder.layer):
+        lay.attention.self.query.register_forward_hook(keep(f"q{l}"))
+        lay.attention.self.key.register_forward_hook(keep(f"k{l}"))
+        lay.attention.self.value.register_forward_hook(keep(f"v{l}"))
+        lay.attention.self.register_forward_hook(keep(f"att{l}"))
+        lay.attention.output.register_forward_hook(keep(f"x1{l}"))
+        lay.intermediate.register_forward_hook(keep(f"g{l}"))
+        lay.output.register_forward_hook(keep(f"x2{l}"))
+    seq = ids[cu[b]:cu[b + 1]].astype(np.int64)
+    with torch.no_grad():
+        z = model(input_ids=torch.tensor(seq)[None]).logits[0].numpy()
+    H = SMALL.hidden
+    np.testing.assert_allclose(t["x0"], seen["x0"], atol=1e-11)
+    for l in range(SMALL.layers):
+        np.testing.assert_allclose(t["qkv"][l][:, :H], seen[f"q{l}"], atol=1e-10)
+        np.testing.assert_allclose(t["qkv"][l][:, H:2 * H], seen[f"k{l}"], atol=1e-10)
+        np.testing.assert_allclose(t["qkv"][l][:, 2 * H:], seen[f"v{l}"], atol=1e-10)
+        np.testing.assert_allclose(t["att"][l], seen[f"att{l}"], atol=1e-10)
+        np.testing.assert_allclose(t["x1"][l], seen[f"x1{l}"], atol=1e-10)
+        np.testing.assert_allclose(t["g"][l], seen[f"g{l}"], atol=1e-10)
+        np.testing.assert_allclose(t["x2"][l], seen[f"x2{l}"], atol=1e-10)
+        assert np.abs(seen[f"g{l}"]).max() > 0.05 and np.abs(seen[f"att{l}"]).max() > 0.05
+    np.testing.assert_allclose(t["z"], z, atol=1e-10)
