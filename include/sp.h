@@ -220,6 +220,12 @@ int sp_forward_profiled(const sp_model* model, const int32_t* token_ids, const i
                         void* workspace, size_t workspace_bytes, float* logits_out, void* hip_stream,
                         float* phase_ms_host);
 
+/* y[i] = GELU(x[i]) exactly as the epilogue of the bf16 FFN up-projection evaluates it (exact erf form through a
+ * fitted complementary error function, fp32 arithmetic), before the rounding to bf16; x_device, y_device: device
+ * float32 [n], 1 <= n <= 2^31.  For the test that bounds its distance from the erf definition.
+ * Errors: SP_EINVAL, SP_ESHAPE, SP_EHIP. */
+int sp_probe_gelu(const float* x_device, float* y_device, int64_t n, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

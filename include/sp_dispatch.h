@@ -24,7 +24,12 @@
  *       per such sample, never below k_min;
  *   D6  the buffer-empty window restarts whenever the buffer is non-empty and after every increase;
  *   D7  groups(k) = floor(slots / k), slots = student instances that run concurrently;
- *   D8  events of the same microsecond: completions first, then arrivals in input order.
+ *   D8  events of the same microsecond: completions first, then arrivals in input order;
+ *   D9  an element in flight counts as one occupied group whatever student number it was dispatched with: after a
+ *       decrease, a new element is admitted while fewer than floor(slots / k_now) elements run, although the older
+ *       ones still hold k_old students each until they finish (the paper says the groups "release" their tail
+ *       students at once; the service times of the loop in virtual time are optimistic by that much during the
+ *       transition).
  */
 #ifndef SP_DISPATCH_H
 #define SP_DISPATCH_H

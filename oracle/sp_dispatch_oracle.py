@@ -30,6 +30,9 @@ Readings where the paper is silent (the native code takes the same ones):
       profiling result the paper calls the optimal student number sharing a GPU, times the GPUs).
   D8  events at the same microsecond: completions first (a group freed at t takes a sample arriving at t), then
       arrivals in input order.
+  D9  an element in flight counts as one occupied group whatever student number it was dispatched with: after a
+      decrease a new element is admitted while fewer than floor(slots / k_now) elements run, although older ones still
+      hold k_old students each until they finish (optimistic during the transition).
 """
 from __future__ import annotations
 

@@ -193,19 +193,19 @@ static void fill_student(const sp_config& c, const ArenaLayout& L, const float* 
 
 // Optional per-phase timing: an event is recorded after every launch and tagged with its phase.
 struct PhaseTimer {
-    hipEvent_t ev[64];
-    int phase[64];
+    std::vector<hipEvent_t> ev;      // grows with the launch count (a dozen per layer)
+    std::vector<int> phase;
     int n = 0;
     bool ok = true;
     void mark(int ph, hipStream_t s)
     {
-        if (n >= 64) { ok = false; return; }
-        if (hipEventCreate(&ev[n]) != hipSuccess) { ok = false; return; }
-        phase[n] = ph;
-        if (hipEventRecord(ev[n], s) != hipSuccess) ok = false;
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) { ok = false; return; }
+        try { ev.push_back(e); phase.push_back(ph); } catch (...) { (void)hipEventDestroy(e); ok = false; return; }
         ++n;
+        if (hipEventRecord(e, s) != hipSuccess) ok = false;
     }
-    void release() { for (int i = 0; i < n; ++i) (void)hipEventDestroy(ev[i]); n = 0; }
+    void release() { for (int i = 0; i < n; ++i) (void)hipEventDestroy(ev[i]); ev.clear(); phase.clear(); n = 0; }
 };
 
 // The forward of students [m0, m0 + k) of the model (k >= 1), all of it enqueued on stream s.  Every buffer of the
@@ -532,6 +532,13 @@ int sp_forward_profiled(const sp_model* model, const int32_t* token_ids, const i
         }
     pt.release();
     return rc;
+}
+
+int sp_probe_gelu(const float* x_device, float* y_device, int64_t n, void* hip_stream)
+{
+    if (!x_device || !y_device) return SP_EINVAL;
+    if (n < 1 || n > ((int64_t)1 << 31)) return SP_ESHAPE;
+    return launch_gelu_probe(x_device, y_device, (long)n, (hipStream_t)hip_stream) == hipSuccess ? SP_OK : SP_EHIP;
 }
 
 void sp_free(sp_model* model)

@@ -16,15 +16,16 @@ __device__ inline float gelu_erf(float u) { return 0.5f * u * (1.0f + erff(u * 0
 // GELU (erf form) for outputs that are rounded to bf16 afterwards, written with the complementary error function:
 //   gelu(x) = x (1 + erf(x / sqrt 2)) / 2 = max(x, 0) - |x| erfc(|x| / sqrt 2) / 2,
 //   log2 erfc(z) = z Q(z) on [0, 4.3], Q a degree-5 minimax fit (weighted for the absolute error of gelu);
-//   erfc(4.3) = 1.2e-9, so z is clamped there.
+//   erfc(4.3) = 1.2e-9, so |x| is clamped at 4.3 sqrt 2 (in the erfc term only: beyond it the term stays below 4e-9
+//   instead of growing with |x|).
 // Evaluated in fp32 the result is within 3.2e-7 of the exact function for every x (0.03 bf16 ulp at most where
 // |gelu| > 1e-3).  One quarter-rate instruction (exp2) and eleven full-rate ones: the epilogue of the FFN
 // up-projection is bound by these vector instructions while the matrix cores wait (libm's erff costs several times
 // more; the rational-exponential formula 7.1.26 of Abramowitz & Stegun needs a reciprocal as well).
 __device__ inline float gelu_erf_fast(float x)
 {
-    const float ax = __builtin_fabsf(x);
-    const float z = __builtin_fminf(ax * 0.70710678118654752f, 4.3f);
+    const float ax = __builtin_fminf(__builtin_fabsf(x), 6.0811f);
+    const float z = ax * 0.70710678118654752f;
     float q = __builtin_fmaf(2.393906887e-04f, z, -4.185345790e-03f);
     q = __builtin_fmaf(q, z, 3.190982192e-02f);
     q = __builtin_fmaf(q, z, -1.505803052e-01f);
@@ -606,7 +607,21 @@ hipError_t launch_f32(const sp_model* M, const void* A, int lda, size_t w_off, s
     return hipGetLastError();
 }
 
+// y[i] = the GELU of the bf16 epilogue evaluated on x[i], before any rounding to bf16 (test aid)
+__global__ void gelu_probe_kernel(const float* __restrict__ x, float* __restrict__ y, long n)
+{
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) y[i] = gelu_erf_fast(x[i]);
+}
+
 }  // namespace
+
+hipError_t launch_gelu_probe(const float* x, float* y, long n, hipStream_t s)
+{
+    if (n < 1) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(gelu_probe_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, x, y, n);
+    return hipGetLastError();
+}
 
 hipError_t launch_gemm_splitk(const sp_model* M, const void* A, int lda, size_t w_off, float* partials, int mrows, int N,
                               int Kd, int k, int splits, size_t a_student_stride, size_t slice_elems, hipStream_t s)

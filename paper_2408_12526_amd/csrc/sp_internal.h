@@ -88,6 +88,9 @@ hipError_t launch_gemm(const sp_model* M, const void* A, int lda, size_t w_off, 
                        size_t a_student_stride, size_t o_student_stride, size_t r_student_stride, hipStream_t s,
                        void* out2 = nullptr, int n_split = 0, int ld2 = 0, size_t o2_student_stride = 0);
 
+// y[i] = GELU as the bf16 FFN up-projection's epilogue evaluates it, in fp32 (i < n).  Test aid.
+hipError_t launch_gelu_probe(const float* x, float* y, long n, hipStream_t s);
+
 // Split reduction for calls of a few dozen tokens, where one workgroup per 64x64 output tile walking the whole
 // reduction range is a long serial chain: partials[m][s][row][0..N) = A[m][row][s*Kd/splits ..) . W^T (fp32, no bias),
 // s < splits; slice_elems = elements between consecutive slices (>= mrows * N).  bf16 path only.

@@ -50,6 +50,7 @@ def _load() -> C.CDLL:
     lib.sp_forward_partial.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, sz, vp]
     lib.sp_forward_profiled.restype = C.c_int
     lib.sp_forward_profiled.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, sz, vp, vp, vp]
+    lib.sp_probe_gelu.restype = C.c_int; lib.sp_probe_gelu.argtypes = [vp, vp, C.c_int64, vp]
     lib.sp_free.restype = None; lib.sp_free.argtypes = [vp]
     lib.sp_strerror.restype = C.c_char_p; lib.sp_strerror.argtypes = [C.c_int]
     lib.sp_pack.restype = C.c_int; lib.sp_pack.argtypes = [vp, i32, vp]
@@ -97,6 +98,14 @@ def sp_arena_bytes(cfg: sp_config) -> int:
 
 def sp_workspace_bytes(cfg: sp_config, max_tokens: int, max_batch: int) -> int:
     return int(_lib.sp_workspace_bytes(C.byref(cfg), max_tokens, max_batch))
+
+
+def sp_probe_gelu(x: torch.Tensor) -> torch.Tensor:
+    """The bf16 path's GELU evaluated in fp32 on a float32 device tensor (test aid)."""
+    assert x.dtype == torch.float32 and x.is_cuda and x.is_contiguous()
+    y = torch.empty_like(x)
+    _check(_lib.sp_probe_gelu(x.data_ptr(), y.data_ptr(), x.numel(), _stream_ptr(None)))
+    return y
 
 
 def sp_pack(lengths) -> np.ndarray:

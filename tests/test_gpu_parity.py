@@ -344,50 +344,50 @@ def test_call_sizes_at_every_path_boundary(sp, oracle64, total):
 _cache = {}
 
 
-def loaded(sp, n):
+def loaded(sp, n, **cfg_kw):
     """Students + inputs of workload n, kept for the module (weights are large)."""
-    if n not in _cache:
+    key = (n, tuple(sorted(cfg_kw.items())))
+    if key not in _cache:
         _cache.clear()
         w = synth.WORKLOADS[n]
         batch, blob = synth.make_workload(w)
-        st = sp.Students(sp.config_from_shape(w.shape), blob)
-        _cache[n] = (w, batch, oracle_weights(blob, w.shape), st)
-    return _cache[n]
+        st = sp.Students(sp.config_from_shape(w.shape, **cfg_kw), blob)
+        _cache[key] = (w, batch, oracle_weights(blob, w.shape), st)
+    return _cache[key]
 
 
-_terms = {}
+def part_range(lengths, part, nparts):
+    """Sequences [lo, hi) of part `part` when the batch is cut into `nparts` contiguous runs of about equal token
+    counts (the parts together cover every sequence exactly once)."""
+    cum = np.concatenate([[0], np.cumsum(lengths.astype(np.int64))])
+    cuts = [int(np.searchsorted(cum, cum[-1] * i / nparts)) for i in range(nparts + 1)]
+    cuts[0], cuts[-1] = 0, len(lengths)
+    return cuts[part], cuts[part + 1]
 
 
-def oracle_terms(oracle, n, w, ow, batch, cu):
-    """Per-student classifier outputs [K][B][C] of workload n from one oracle run with all K students (kept for the
-    next test on the same workload: the large ones take the oracle tens of seconds)."""
-    key = (n, oracle.kind)
-    if key not in _terms:
-        _terms.clear()
-        print(f"{w.name}: oracle ({oracle.kind}) on all {len(batch.lengths)} sequences, {int(cu[-1])} tokens, "
-              f"{w.shape.K} students", flush=True)
-        _terms[key] = oracle.forward(ocfg(w.shape), ow, batch.ids, cu, w.shape.K, want_terms=True)[1]
-    return _terms[key]
-
-
-def run_workload(sp, oracle, n):
-    """Every logit of workload n, for each of its k_active values, against the oracle.  The oracle runs once with all
-    K students and hands out the per-student terms; its logits for k_active are their sum in student order (what its
-    own forward does: pinned by test_prefix_sums_and_tail_pruning)."""
-    w, batch, ow, st = loaded(sp, n)
+def run_workload(sp, oracle, n, part=0, nparts=1, **cfg_kw):
+    """Every logit of the sequences in one part of workload n (all of it by default), for each of its k_active
+    values, against the oracle.  The GPU always runs the whole batch; the oracle runs the part's sequences as a batch
+    of their own (samples are independent: pinned by test_each_sample_is_independent_of_its_batch) once with all K
+    students and hands out the per-student terms; its logits for k_active are their sum in student order (what its
+    own forward does: pinned by test_prefix_sums_and_tail_pruning).  Large workloads are cut into parts so that no
+    single test keeps the oracle busy for minutes."""
+    w, batch, ow, st = loaded(sp, n, **cfg_kw)
     d_ids, d_cu, cu = gpu_inputs(batch.lengths, batch.ids, sp)
-    B, mx = len(batch.lengths), int(batch.lengths.max())
-    terms = oracle_terms(oracle, n, w, ow, batch, cu)
+    mx = int(batch.lengths.max())
+    lo, hi = part_range(batch.lengths, part, nparts)
+    assert hi > lo
+    sub_cu = (cu[lo:hi + 1] - cu[lo]).astype(np.int32)
+    _, terms = oracle.forward(ocfg(w.shape), ow, batch.ids[cu[lo]:cu[hi]], sub_cu, w.shape.K, want_terms=True)
     errs = {}
     for k in sorted(w.k_actives):
         got = st.sp_forward(d_ids, d_cu, mx, k).cpu().numpy().astype(np.float64)
         want = np.zeros_like(terms[0])
         for m in range(k):
             want = want + terms[m]
-        assert got.shape == want.shape == (B, w.shape.classes)
+        assert got.shape == (len(batch.lengths), w.shape.classes) and want.shape == (hi - lo, w.shape.classes)
         assert np.abs(want).max() > 1e-2
-        errs[k] = check_logits(got, want, w.shape, f"{w.name} k_active={k}, all {B} sequences")
-        print(f"{w.name} k_active={k}: all {B} sequences compared, error {errs[k]:.3e}", flush=True)
+        errs[k] = check_logits(got[lo:hi], want, w.shape, f"{w.name} k_active={k}, sequences {lo}..{hi - 1}")
     return errs
 
 
@@ -405,29 +405,25 @@ def test_config3_latency_b1(sp, oracle64):
     run_workload(sp, oracle64, 3)
 
 
-def test_config4_burst_b256_every_sequence(sp, oracle64):
-    """All 256 sequences (58 token tiles of 256 rows: the last block of the token-tile-blocked projection order is a
-    partial one, and the last tile is padded)."""
-    run_workload(sp, oracle64, 4)
+@pytest.mark.parametrize("part", range(3))
+def test_config4_burst_b256_every_sequence(sp, oracle64, part):
+    """All 256 sequences, in three parts (58 token tiles of 256 rows: the last block of the token-tile-blocked
+    projection order is a partial one, and the last tile is padded)."""
+    run_workload(sp, oracle64, 4, part, 3)
 
 
-def test_config4_burst_b256_all_token_last_layer_every_sequence(sp, oracle64):
+@pytest.mark.parametrize("part", range(3))
+def test_config4_burst_b256_all_token_last_layer_every_sequence(sp, oracle64, part):
     """The stock variant (every token through the last layer as well) at full size: the second layer's large-tile
     projections, attention kernels and LayerNorm on all 14722 rows."""
-    w, batch, ow, _ = loaded(sp, 4)
-    _, blob = synth.make_workload(w)
-    st = sp.Students(sp.config_from_shape(w.shape, last_layer_all_tokens=True), blob)
-    d_ids, d_cu, cu = gpu_inputs(batch.lengths, batch.ids, sp)
-    got = st.sp_forward(d_ids, d_cu, int(batch.lengths.max()), w.shape.K).cpu().numpy().astype(np.float64)
-    st.close()
-    want = oracle_terms(oracle64, 4, w, ow, batch, cu).sum(0)     # (fp64: the order of the sum is immaterial here)
-    check_logits(got, want, w.shape, "c4 all-token last layer, all sequences")
+    run_workload(sp, oracle64, 4, part, 3, last_layer_all_tokens=True)
 
 
-def test_config5_large_width_b64_every_sequence(sp, oracle64):
-    """All 64 sequences (64 to 512 tokens, hidden 1024, 16 heads: every attention path at that width, sequences of
-    more than 256 tokens included, 74 token tiles)."""
-    run_workload(sp, oracle64, 5)
+@pytest.mark.parametrize("part", range(6))
+def test_config5_large_width_b64_every_sequence(sp, oracle64, part):
+    """All 64 sequences, in six parts (64 to 512 tokens, hidden 1024, 16 heads: every attention path at that width,
+    sequences of more than 256 tokens included, 74 token tiles)."""
+    run_workload(sp, oracle64, 5, part, 6)
 
 
 def test_partial_last_block_of_the_token_tile_order(sp, oracle64):
@@ -579,3 +575,61 @@ def test_input_contents_check(sp):
     assert st.sp_check_inputs(d_ids, c, 64) == sp.SP_BAD_TOTAL
     with pytest.raises(sp.SpError):
         st.sp_check_inputs(d_ids, d_cu, 65)                # max_seqlen beyond the position table
+
+
+# ---- pieces that the stage tolerance cannot resolve ------------------------------------------------------
+
+def test_gelu_of_the_bf16_epilogue_is_the_erf_form(sp):
+    """The bf16 FFN up-projection evaluates GELU through a fitted complementary error function.  In fp32, before the
+    rounding to bf16, it must stay within 5e-7 of x (1 + erf(x / sqrt 2)) / 2 everywhere (a dense grid over the range
+    in which the function is not yet x or 0 to fp32 accuracy, plus the tails and the special points); the
+    tanh approximation of the same function, which this reading rejects, is up to 5e-4 away."""
+    import math
+    grid = np.concatenate([np.linspace(-12, 12, 2_000_001), np.linspace(-1e-3, 1e-3, 20_001),
+                           [0.0, -0.0, 1.0, -1.0, 30.0, -30.0, 1e4, -1e4, 6.0811, -6.0811]]).astype(np.float32)
+    got = sp.sp_probe_gelu(torch.from_numpy(grid).cuda()).cpu().numpy().astype(np.float64)
+    x = grid.astype(np.float64)
+    want = 0.5 * x * (1.0 + np.vectorize(math.erf)(x / math.sqrt(2.0)))
+    err = np.abs(got - want)
+    assert err.max() <= 5e-7, f"max |gelu_fast - gelu_erf| = {err.max():.3e} at x = {x[err.argmax()]}"
+    assert got[np.flatnonzero(grid == 0.0)].max() == 0.0
+    tanh_form = 0.5 * x * (1.0 + np.tanh(math.sqrt(2.0 / math.pi) * (x + 0.044715 * x ** 3)))
+    assert np.abs(tanh_form - want).max() > 1e-4 > 100 * err.max()       # the test can tell the two forms apart
+
+
+def test_two_threads_issue_large_calls_on_one_model(sp):
+    """Calls of >= 2048 tokens fork to the model's second stream and join again; two host threads issuing such calls
+    on one model at the same time (own stream, own workspace, own output each) must both get the single-threaded
+    logits bit for bit, every time."""
+    import threading
+    w, batch, _, st = loaded(sp, 4)
+    d_ids, d_cu, cu = gpu_inputs(batch.lengths, batch.ids, sp)
+    T, B, mx = int(cu[-1]), len(batch.lengths), int(batch.lengths.max())
+    ref = {k: st.sp_forward(d_ids, d_cu, mx, k).clone() for k in (8, 3)}
+    torch.cuda.synchronize()
+    need = sp.sp_workspace_bytes(st.cfg, T, B)
+    results, errors = {}, []
+
+    def worker(i, k):
+        try:
+            stream = torch.cuda.Stream()
+            ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+            out = torch.empty(B, w.shape.classes, dtype=torch.float32, device="cuda")
+            bad = 0
+            for _ in range(6):
+                out.zero_()
+                stream.wait_stream(torch.cuda.current_stream())
+                st.sp_forward(d_ids, d_cu, mx, k, out, ws, stream=stream)
+                stream.synchronize()
+                bad += int(not torch.equal(out, ref[k]))
+            results[i] = bad
+        except Exception as e:          # surfaced below: an exception in a thread would otherwise be lost
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(0, 8)), threading.Thread(target=worker, args=(1, 3))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    assert results == {0: 0, 1: 0}, results
