@@ -32,16 +32,43 @@ os.environ.setdefault("GPU_MAX_HW_QUEUES", "8")
 # published MI355X peaks used for the roofline fractions
 PEAK_BF16_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
+PEAK_FP32_TFLOPS = 157.3
 
 
 def percentile(xs, q):
     return float(np.percentile(np.asarray(xs), q))
 
 
-# HBM-side bytes of one launch of the FFN-up GEMM at k_active = 8 on the burst workload, from two rocprofv3 --pmc runs
-# (FETCH_SIZE, WRITE_SIZE) scaled by the same counters on a 1 GiB copy; the summary with the commands is
-# profiles/hbm_traffic_gemm_ffn_up_c4_burst_b256.txt.  A counter run cannot be made from inside the timed process.
-FFN_UP_HBM_BYTES_PER_LAUNCH = {"read": 9.92e8, "written": 7.298e8}
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "hbm_traffic_gemm_ffn_up_c4_burst_b256.txt")
+KERNEL_SOURCES = ("sp_gemm.hip", "sp_api.hip", "sp_internal.h")
+
+
+def kernel_build_id():
+    """Identifier of the sources the dominant kernel and its launch plan are built from (first 16 hex digits of the
+    SHA-256 over them): the counter summaries under profiles/ record the one they were taken with."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2408_12526_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def tracked_traffic():
+    """HBM-side bytes of one launch of the dominant kernel (FFN up-projection, burst workload, k_active = 8), read
+    from the tracked rocprofv3 counter summary: its line `traffic_json: {...}` holds the calibrated FETCH_SIZE /
+    WRITE_SIZE bytes per launch and the build identifier of the sources it was measured with (a counter run cannot
+    be made from inside the timed process).  None if the summary is missing or has no such line."""
+    try:
+        with open(TRAFFIC_PROFILE) as f:
+            for line in f:
+                if line.startswith("traffic_json:"):
+                    d = json.loads(line[len("traffic_json:"):])
+                    d["matches_this_build"] = d.get("build_id") == kernel_build_id()
+                    return d
+    except (OSError, ValueError):
+        pass
+    return None
 
 
 def gemm_flops(shape, tokens, k, layers):
@@ -68,6 +95,91 @@ def last_first_work(shape, tokens, batch, k):
                  + 2 * batch * H * H + 4 * batch * H * F)   # output projection, feed-forward
     weight_bytes = k * (4 * H * H + 2 * H * F) * 2
     return flops, k * tokens * H * 2 + weight_bytes
+
+
+def first_only_runs(shape, tokens, max_len):
+    """Whether sp_forward computes the last layer for the first-token rows only (sp_config.last_layer_all_tokens = 0)."""
+    return shape.dtype == "bf16" and tokens >= 1024 and shape.heads % 4 == 0 and shape.heads <= 16 and max_len <= 512
+
+
+def executed_flops(shape, lengths, k):
+    """Flops one forward executes (projections on the real tokens, attention, the first-token last layer where it
+    runs, pooler and classifier), and the weight bytes it has to stream at least once."""
+    T, B = int(lengths.sum()), len(lengths)
+    H, F = shape.hidden, shape.ffn
+    wb = 2 if shape.dtype == "bf16" else 4
+    fo = first_only_runs(shape, T, int(lengths.max()))
+    full = shape.layers - 1 if fo else shape.layers
+    flops = sum(gemm_flops(shape, T, k, full).values()) + attention_flops(shape, lengths, k, full)
+    if fo:
+        flops += last_first_work(shape, T, B, k)[0]
+    flops += k * B * (2 * H * H + 2 * H * shape.classes)
+    weights = k * (shape.layers * (4 * H * H + 2 * H * F) + H * H + H * shape.classes) * wb
+    return flops, weights, fo
+
+
+def per_config_table(sp, synth, torch, dev, calls_small, calls_large, warm):
+    """One row per (workload, k_active): wall time per call (call to stream sync) and device time per call (HIP events
+    on the launch stream), p50 and p95 each, sequences/s = batch / wall p50, executed flops and the fraction of the
+    roofline that bounds the call: bf16 matrix-core peak for the large bf16 calls, HBM weight streaming for batch 1,
+    fp32 vector peak for the tiny fp32 workload (whose calls are launch-bound: the fraction says so)."""
+    rows = []
+    paper_student = synth.Workload(
+        "paper_2L256D_b256", synth.StudentShape(K=3, layers=2, hidden=256, heads=4, ffn=1024, vocab=30522, max_pos=512,
+                                                classes=2), 256, ("lognormal", 48.0, 0.6, 8, 256), (1, 3))
+    todo = [(synth.WORKLOADS[n], None) for n in (1, 2, 3, 4, 5)] + [(paper_student, "the paper's own student shape "
+            "(Table 2: 2 layers, 256 wide; 1 student and the 3-student ensemble), burst-like batch of 256")]
+    for w, note in todo:
+        batch, blob = synth.make_workload(w)
+        cu = sp.sp_pack(batch.lengths)
+        T, B, mx = int(cu[-1]), len(batch.lengths), int(batch.lengths.max())
+        st = sp.Students(sp.config_from_shape(w.shape), blob)
+        del blob
+        d_ids, d_cu = torch.from_numpy(batch.ids).to(dev), torch.from_numpy(cu).to(dev)
+        logits = torch.empty(B, w.shape.classes, dtype=torch.float32, device=dev)
+        ws = st.workspace(T, B)
+        calls = calls_large if T >= 4096 else calls_small
+        for k in sorted(w.k_actives, reverse=True):
+            for _ in range(warm):
+                st.sp_forward(d_ids, d_cu, mx, k, logits, ws)
+            torch.cuda.synchronize()
+            wall, devt = [], []
+            for _ in range(calls):
+                t0 = time.perf_counter()
+                st.sp_forward(d_ids, d_cu, mx, k, logits, ws)
+                torch.cuda.synchronize()
+                wall.append((time.perf_counter() - t0) * 1e6)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            for _ in range(calls):
+                e0.record()
+                st.sp_forward(d_ids, d_cu, mx, k, logits, ws)
+                e1.record()
+                e1.synchronize()
+                devt.append(e0.elapsed_time(e1) * 1e3)
+            flops, wbytes, fo = executed_flops(w.shape, batch.lengths, k)
+            p50 = percentile(wall, 50)
+            d50 = percentile(devt, 50)
+            row = {"workload": w.name, "k_active": k, "batch": B, "tokens": T, "dtype": w.shape.dtype, "calls": calls,
+                   "wall_us_p50": p50, "wall_us_p95": percentile(wall, 95), "device_us_p50": d50,
+                   "device_us_p95": percentile(devt, 95), "sequences_per_s": B / p50 * 1e6,
+                   "executed_flops": flops, "weight_bytes": wbytes,
+                   "last_layer": "first-token rows only" if fo else "every token"}
+            if T < 1024:        # small calls: weight streaming (and launches) bound them, not arithmetic
+                row.update(bound="hbm", achieved=wbytes / d50 / 1e3, peak=PEAK_HBM_GBS, unit="GB/s (weights streamed once)",
+                           frac=wbytes / d50 / 1e3 / PEAK_HBM_GBS)
+            elif w.shape.dtype == "bf16":
+                row.update(bound="mfma", achieved=flops / d50 / 1e6, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s (executed)",
+                           frac=flops / d50 / 1e6 / PEAK_BF16_TFLOPS)
+            else:
+                row.update(bound="alu", achieved=flops / d50 / 1e6, peak=PEAK_FP32_TFLOPS, unit="TFLOP/s (fp32 vector)",
+                           frac=flops / d50 / 1e6 / PEAK_FP32_TFLOPS)
+            if note:
+                row["note"] = note
+            rows.append(row)
+        st.close()
+        del st, ws
+        torch.cuda.empty_cache()
+    return rows
 
 
 def serve_leg(sp, synth, torch, dev, students, with_oracle):
@@ -202,7 +314,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--latency-calls", type=int, default=300)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--only", choices=["burst", "latency", "serve"], default=None,
+    ap.add_argument("--config-calls", type=int, default=200,
+                    help="timed calls per (workload, k_active) of the per-config table for calls of >= 4096 tokens "
+                         "(after --config-warmup untimed ones); smaller calls are timed 5 x as often")
+    ap.add_argument("--config-warmup", type=int, default=100)
+    ap.add_argument("--only", choices=["burst", "latency", "serve", "configs"], default=None,
                     help="run one workload only (for profiling a single launch configuration)")
     ap.add_argument("--burst-k", default=None,
                     help="comma-separated k_active values for the burst workload (default: 8,4,2); profiles of one "
@@ -333,6 +449,14 @@ def main():
             latency[k] = {"p50_us": percentile(wall, 50), "p95_us": percentile(wall, 95),
                           "back_to_back_us": back, "weight_stream_gbs": weight_bytes / back / 1e3}
 
+    # ------------------------------------------------------------------ every workload, one row per k_active
+    per_config = None
+    if args.only in (None, "configs"):
+        if args.only == "configs":
+            del st4
+        torch.cuda.empty_cache()
+        per_config = per_config_table(sp, synth, torch, dev, 5 * args.config_calls, args.config_calls, args.config_warmup)
+
     # ------------------------------------------------------------------ serving loop (host-side dispatching)
     serve = None
     if args.only in (None, "serve"):
@@ -340,7 +464,7 @@ def main():
 
     # ------------------------------------------------------------------ CPU oracle on a bounded sample
     cpu = None
-    if not args.no_cpu_baseline and args.only != "serve":
+    if not args.no_cpu_baseline and args.only not in ("serve", "configs"):
         from oracle.sp_oracle import Oracle, OracleConfig
         orc = Oracle("f32")
         s = w4.shape
@@ -384,18 +508,28 @@ def main():
         "latency_workload": "c3_latency_b1: K=8 students, one sequence of 64 tokens, 3 classes; wall time from call "
                             "to stream sync, inputs resident",
         "phases_k8": phases,
+        "per_config": per_config,
+        "per_config_protocol": f"{args.config_warmup} warm-up calls, then {args.config_calls} timed calls (5 x as many for "
+                               "calls below 4096 tokens) wall time call -> stream sync, and as many with HIP events "
+                               "around the call on the launch stream; inputs resident; sequences_per_s = batch / wall p50; "
+                               "the paper's latencies (Table 2: 2.8 ms avg for one 2L256D student on RTX 3090s) include "
+                               "queueing, PCIe and the cross-GPU gather, these do not",
         "serve": serve,
     }
     if phases:
         d = phases["ffn_up"]
         # the ffn_up phase is exactly one launch of this kernel per step (HIP events around it, on the launch stream)
+        tr = tracked_traffic()
+        fresh = bool(tr and tr.get("matches_this_build"))
         rec["roofline"] = {"kernel": "gemm_bf16_kernel<256,256,BIAS_GELU> (FFN up-projection + GELU, all-token layer)",
                            "bound": "mfma",
                            "achieved": d["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": d["frac"],
-                           "traffic": FFN_UP_HBM_BYTES_PER_LAUNCH["read"] + FFN_UP_HBM_BYTES_PER_LAUNCH["written"],
+                           "traffic": (tr["read_bytes"] + tr["written_bytes"]) if tr else None,
                            "traffic_unit": "bytes beyond L2 per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)",
-                           "traffic_read": FFN_UP_HBM_BYTES_PER_LAUNCH["read"],
-                           "traffic_written": FFN_UP_HBM_BYTES_PER_LAUNCH["written"],
+                           "traffic_read": tr["read_bytes"] if tr else None,
+                           "traffic_written": tr["written_bytes"] if tr else None,
+                           "traffic_source": os.path.relpath(TRAFFIC_PROFILE, ROOT) if tr else None,
+                           "traffic_measured_on_this_build": fresh, "build_id": kernel_build_id(),
                            "algorithmic_bytes": 8 * 14848 * (H + F) * 2 + 8 * H * F * 2,
                            "algorithmic_flops": gf["ffn_up"], "launch_ms": d["ms"]}
     rec["cpu_baseline"] = cpu
