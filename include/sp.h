@@ -34,7 +34,9 @@ enum {
     SP_ESHAPE = -2,   /* batch < 1, total_tokens < batch, max_seqlen > max_pos, unsupported head width ... */
     SP_EKACTIVE = -3, /* k_active outside 1..K */
     SP_ENOMEM = -4,   /* weight blob, arena or workspace smaller than required */
-    SP_EHIP = -5      /* a HIP runtime call failed */
+    SP_EHIP = -5,     /* a HIP runtime call failed */
+    /* -6, -7: the length-aware buffer's codes (sp_dispatch.h) */
+    SP_ETOOBIG = -8   /* sp_forward_static: the call needs more workspace than the library's static array holds */
 };
 
 enum { SP_DTYPE_FP32 = 0, SP_DTYPE_BF16 = 1 };
@@ -130,6 +132,27 @@ int sp_load_students(const sp_config* cfg, const float* host_weights, size_t nfl
 int sp_forward(const sp_model* model, const int32_t* token_ids, const int32_t* cu_seqlens,
                int32_t batch, int32_t total_tokens, int32_t max_seqlen, int32_t k_active,
                void* workspace, size_t workspace_bytes, float* logits_out, void* hip_stream);
+
+/* sp_forward for callers that cannot allocate device memory and have no workspace to pass: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The workspace is a static device array inside the
+ * library, SP_STATIC_SCRATCH_MIB MiB per GPU (part of the library's device image: each GPU the library runs on holds
+ * it until the process ends); the call itself allocates nothing, frees nothing and calls no allocating routine.  It
+ * enqueues exactly the kernels sp_forward would, so the logits are bit-identical to sp_forward's.
+ *   - the model's GPU must be the current device;
+ *   - arguments as for sp_forward, without the workspace; inputs and logits_out are still the caller's;
+ *   - a call that needs more than the array holds (sp_workspace_bytes(cfg, total_tokens, batch) >
+ *     sp_static_scratch_bytes(): for the 8-student hidden-768 group that is any call of more than 256 tokens)
+ *     returns SP_ETOOBIG and enqueues nothing;
+ *   - every call on a GPU, from any model, stream or thread, uses that GPU's one array, which keeps the previous
+ *     call's contents (nothing in it has to start at zero: a forward writes every row it reads).  Calls that can
+ *     overlap in time on one GPU race on it: order them (one stream, or events), or use sp_forward with a
+ *     workspace per call.
+ * Errors: those of sp_forward, and SP_ETOOBIG. */
+#define SP_STATIC_SCRATCH_MIB 64
+size_t sp_static_scratch_bytes(void);
+int sp_forward_static(const sp_model* model, const int32_t* token_ids, const int32_t* cu_seqlens,
+                      int32_t batch, int32_t total_tokens, int32_t max_seqlen, int32_t k_active,
+                      float* logits_out, void* hip_stream);
 
 /* Releases the host handle only; the arena stays the caller's. */
 void sp_free(sp_model* model);

@@ -402,6 +402,32 @@ static int run_forward(const sp_model* M, const int32_t* ids, const int32_t* cu,
     return SP_OK;
 }
 
+// ---- workspace for callers that cannot allocate ---------------------------------------------------
+// One array per GPU, part of the library's device image: every GPU the library runs on holds it until the process
+// ends.  In host code the array's name is only a stand-in for the symbol; the device address is looked up once per
+// device and everything on the host (kernel arguments included) goes through that pointer.
+constexpr size_t kStaticScratchBytes = (size_t)SP_STATIC_SCRATCH_MIB << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static std::mutex scratch_mu;
+static void* scratch_ptr[kMaxDevices];      // per device; null until looked up
+
+// The current device's copy of the array (looked up on the first request for that device).
+static int static_scratch(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return SP_EHIP;
+    if (dev < 0 || dev >= kMaxDevices) return SP_EINVAL;
+    std::lock_guard<std::mutex> hold(scratch_mu);
+    if (!scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return SP_EHIP;
+        scratch_ptr[dev] = p;
+    }
+    *out = scratch_ptr[dev];
+    return SP_OK;
+}
+
 }  // namespace sp
 
 using namespace sp;
@@ -491,8 +517,28 @@ int sp_load_students(const sp_config* cfg, const float* host_weights, size_t nfl
     } else {
         m->aux = nullptr;
     }
+    // this device's copy of the static workspace (sp_forward_static): looked up now, with the device current, so
+    // that the calls themselves do nothing but enqueue kernels
+    void* unused = nullptr;
+    (void)static_scratch(&unused);
     *out = m;
     return SP_OK;
+}
+
+size_t sp_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int sp_forward_static(const sp_model* model, const int32_t* token_ids, const int32_t* cu_seqlens, int32_t batch,
+                      int32_t total_tokens, int32_t max_seqlen, int32_t k_active, float* logits_out, void* hip_stream)
+{
+    if (!model) return SP_EINVAL;
+    if (batch < 1 || total_tokens < batch) return SP_ESHAPE;
+    // too large for the static array: refuse before anything is enqueued
+    if (make_ws_layout(model->cfg, total_tokens, batch).end > kStaticScratchBytes) return SP_ETOOBIG;
+    void* ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc != SP_OK) return rc;
+    return run_forward(model, token_ids, cu_seqlens, batch, total_tokens, max_seqlen, k_active, model->cfg.layers,
+                       true, ws, kStaticScratchBytes, logits_out, (hipStream_t)hip_stream);
 }
 
 int sp_forward(const sp_model* model, const int32_t* token_ids, const int32_t* cu_seqlens, int32_t batch,
@@ -563,6 +609,7 @@ const char* sp_strerror(int code)
         case SP_EKACTIVE: return "k_active outside 1..K";
         case SP_ENOMEM: return "buffer smaller than required";
         case SP_EHIP: return "HIP runtime error";
+        case SP_ETOOBIG: return "call too large for the library's static workspace (use sp_forward with a workspace of your own)";
         case SP_EFULL: return "length-aware buffer storage full";
         case SP_EEMPTY: return "length-aware buffer empty";
         default: return "unknown error code";

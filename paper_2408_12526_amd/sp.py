@@ -46,6 +46,9 @@ def _load() -> C.CDLL:
     lib.sp_load_students.argtypes = [cfgp, vp, sz, vp, sz, vp, C.POINTER(vp)]
     lib.sp_forward.restype = C.c_int
     lib.sp_forward.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, sz, vp, vp]
+    lib.sp_forward_static.restype = C.c_int
+    lib.sp_forward_static.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp]
+    lib.sp_static_scratch_bytes.restype = sz; lib.sp_static_scratch_bytes.argtypes = []
     lib.sp_forward_partial.restype = C.c_int
     lib.sp_forward_partial.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, sz, vp]
     lib.sp_forward_profiled.restype = C.c_int
@@ -98,6 +101,10 @@ def sp_arena_bytes(cfg: sp_config) -> int:
 
 def sp_workspace_bytes(cfg: sp_config, max_tokens: int, max_batch: int) -> int:
     return int(_lib.sp_workspace_bytes(C.byref(cfg), max_tokens, max_batch))
+
+
+def sp_static_scratch_bytes() -> int:
+    return int(_lib.sp_static_scratch_bytes())
 
 
 def sp_probe_gelu(x: torch.Tensor) -> torch.Tensor:
@@ -160,6 +167,17 @@ class Students:
         ws = workspace if workspace is not None else self.workspace(total, batch)
         _check(_lib.sp_forward(self.handle, token_ids.data_ptr(), cu_seqlens.data_ptr(), batch, total, max_seqlen,
                                k_active, ws.data_ptr(), ws.numel(), logits_out.data_ptr(), _stream_ptr(stream)))
+        return logits_out
+
+    def sp_forward_static(self, token_ids: torch.Tensor, cu_seqlens: torch.Tensor, max_seqlen: int, k_active: int,
+                          logits_out: torch.Tensor, stream=None):
+        """sp_forward on the library's static workspace: nothing is allocated (logits_out must be given)."""
+        assert token_ids.dtype == torch.int32 and cu_seqlens.dtype == torch.int32
+        assert token_ids.is_cuda and cu_seqlens.is_cuda and token_ids.is_contiguous() and cu_seqlens.is_contiguous()
+        assert logits_out.dtype == torch.float32 and logits_out.is_cuda and logits_out.is_contiguous()
+        batch, total = cu_seqlens.numel() - 1, token_ids.numel()
+        _check(_lib.sp_forward_static(self.handle, token_ids.data_ptr(), cu_seqlens.data_ptr(), batch, total, max_seqlen,
+                                      k_active, logits_out.data_ptr(), _stream_ptr(stream)))
         return logits_out
 
     def sp_check_inputs(self, token_ids: torch.Tensor, cu_seqlens: torch.Tensor, max_seqlen: int, stream=None) -> int:
