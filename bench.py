@@ -97,6 +97,40 @@ def last_first_work(shape, tokens, batch, k):
     return flops, k * tokens * H * 2 + weight_bytes
 
 
+def smi_sample():
+    """Package power (W) and shader clock (MHz) as amd-smi reports them right now, or None (best effort: the tool may
+    be missing or refuse an ordinary user)."""
+    import subprocess
+    try:
+        out = subprocess.run(["amd-smi", "metric", "-g", "0", "--power", "--clock", "--json"], capture_output=True,
+                             text=True, timeout=20).stdout
+        d = json.loads(out)
+        d = d[0] if isinstance(d, list) else (d.get("gpu_data", [d])[0] if isinstance(d, dict) else d)
+        power = d.get("power", {}).get("socket_power", {})
+        clock = d.get("clock", {})
+        gfx = [v.get("clk", {}).get("value") for k, v in clock.items() if k.startswith("gfx") and isinstance(v, dict)]
+        gfx = [g for g in gfx if isinstance(g, (int, float))]
+        return {"socket_power_w": power.get("value") if isinstance(power, dict) else power,
+                "gfx_clock_mhz_mean": sum(gfx) / len(gfx) if gfx else None,
+                "gfx_clock_mhz_max": max(gfx) if gfx else None}
+    except Exception:
+        return None
+
+
+def sampled_while(fn_busy, seconds):
+    """Run fn_busy() repeatedly on this thread for about `seconds` while a helper thread takes one amd-smi sample in
+    the middle of it."""
+    import threading
+    box = {}
+    th = threading.Thread(target=lambda: (time.sleep(seconds * 0.3), box.update(s=smi_sample())))
+    th.start()
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds or th.is_alive():
+        fn_busy()
+    th.join()
+    return box.get("s")
+
+
 def first_only_runs(shape, tokens, max_len):
     """Whether sp_forward computes the last layer for the first-token rows only (sp_config.last_layer_all_tokens = 0)."""
     return shape.dtype == "bf16" and tokens >= 1024 and shape.heads % 4 == 0 and shape.heads <= 16 and max_len <= 512
@@ -413,6 +447,20 @@ def main():
         phases["gemm_phase_total"] = {"ms": gemm_ms, "bound": "mfma", "tflops": sum(gf.values()) / gemm_ms / 1e9,
                                       "frac": sum(gf.values()) / gemm_ms / 1e9 / PEAK_BF16_TFLOPS}
         phases["sum_ms"] = sum(acc.values())
+        # what the matrix cores sustain on this machine with nothing in the way (register operands, no memory traffic):
+        # the ceiling the projection phase is measured against besides the published peak
+        ceiling = {"operands_0_or_1_tflops": sp.sp_probe_mfma_rate(0, 150),
+                   "operands_random_tflops": sp.sp_probe_mfma_rate(1, 150)}
+        phases["mfma_loop_ceiling"] = dict(
+            ceiling, note="v_mfma_f32_32x32x16_bf16 on register operands, 16 accumulator blocks per wave, one wave per "
+                          "SIMD, all compute units; random mantissas are what weights and activations look like",
+            gemm_phase_frac_of_random_ceiling=phases["gemm_phase_total"]["tflops"] / ceiling["operands_random_tflops"])
+
+        def busy():
+            for _ in range(20):
+                st4.sp_forward(d_ids4, d_cu4, mx4, 8, logits4, ws4)
+            torch.cuda.synchronize()
+        phases["power_clock_during_burst_k8"] = sampled_while(busy, 1.5)
         # the stock variant (every token through the whole last layer), for reference
         st4a = sp.Students(sp.config_from_shape(w4.shape, last_layer_all_tokens=True, single_stream=args.single_stream),
                            blob4)

@@ -249,6 +249,18 @@ int sp_forward_profiled(const sp_model* model, const int32_t* token_ids, const i
  * Errors: SP_EINVAL, SP_ESHAPE, SP_EHIP. */
 int sp_probe_gelu(const float* x_device, float* y_device, int64_t n, void* hip_stream);
 
+/* What the matrix cores of the current GPU sustain on bf16 operands with nothing else in the way: a loop of the
+ * 32x32x16 bf16 matrix instruction on register operands (no memory traffic, sixteen accumulator blocks per wave, one
+ * wave per SIMD, every compute unit busy), run for about `milliseconds` (1..2000) after an untimed stretch that lets
+ * the clock settle.  operand_kind 0: every element 0 or 1; 1: uniform in (-1, 1) with full mantissas, which is what
+ * weights and activations look like and what the package power limit prices.  *tflops_host receives the rate.
+ * The projection kernels' fractions of the published peak are quoted next to this measured ceiling.  Creates and
+ * destroys two events and blocks until the run has finished: a measurement aid.
+ *   scratch_device  device, >= 4 bytes, 4-byte aligned (practically never written)
+ * Errors: SP_EINVAL, SP_ESHAPE, SP_EHIP. */
+int sp_probe_mfma_rate(int32_t operand_kind, int32_t milliseconds, void* scratch_device, void* hip_stream,
+                       float* tflops_host);
+
 #ifdef __cplusplus
 }
 #endif

@@ -366,6 +366,12 @@ static int run_students(const sp_model* M0, const WsLayout& W, const int32_t* id
 // of phase and fill each other's gaps (measured about 3 % on the burst workload; starting the second group late,
 // after the first group's first projection, measured no better).  The logits are summed over all
 // students in ascending order after the join, so the result does not depend on the grouping.
+static int two_groups_min_tokens()
+{
+    static const int v = [] { const char* e = getenv("SP_TWO_GROUPS_MIN_TOKENS"); return e ? atoi(e) : 8192; }();
+    return v;
+}
+
 static int run_forward(const sp_model* M, const int32_t* ids, const int32_t* cu, int B, int T, int max_seqlen, int k,
                        int stop_layers, bool with_head, void* ws, size_t ws_bytes, float* logits, hipStream_t s,
                        PhaseTimer* pt = nullptr)
@@ -380,7 +386,7 @@ static int run_forward(const sp_model* M, const int32_t* ids, const int32_t* cu,
     if (ws_bytes < W.end) return SP_ENOMEM;
     char* w = (char*)ws;
 
-    const bool two_groups = with_head && !pt && k >= 2 && T >= 2048 && !c.single_stream && M->aux;
+    const bool two_groups = with_head && !pt && k >= 2 && T >= two_groups_min_tokens() && !c.single_stream && M->aux;
     if (!two_groups)
         return run_students(M, W, ids, cu, B, T, max_seqlen, 0, k, stop_layers, with_head, w, logits, s, pt);
 

@@ -1,0 +1,97 @@
+// Measurement aid: what the matrix cores of this GPU sustain on bf16 data when nothing else is in the way.
+// A loop of v_mfma_f32_32x32x16_bf16 on register operands (no memory traffic at all, sixteen independent
+// accumulator blocks per wave, one wave per SIMD, every compute unit busy) is the ceiling any bf16 projection kernel
+// on this part is measured against.  The rate depends on the operand values: small integers toggle few multiplier
+// bits, random mantissas (what activations and weights look like) toggle many, and the package power limit then
+// lowers the clock.
+#include "sp_internal.h"
+
+namespace sp {
+
+namespace {
+
+__device__ inline unsigned mix(unsigned h)
+{
+    h ^= h >> 15; h *= 2246822519u; h ^= h >> 13; h *= 3266489917u; h ^= h >> 16;
+    return h;
+}
+
+// operand_kind 0: every element 0 or 1; 1: uniform in (-1, 1) with full bf16 mantissas
+__global__ __launch_bounds__(256, 1) void mfma_rate_kernel(int iters, int operand_kind, float* sink)
+{
+    bf16x8 a[4], b[4];
+    const unsigned id = (blockIdx.x * 256u + threadIdx.x) * 64u;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const unsigned ha = mix(id + i * 8 + e), hb = mix(id + 32 + i * 8 + e);
+            a[i][e] = operand_kind ? (bf16)(((int)(ha & 0xffff) - 32768) * (1.0f / 32768.f)) : (bf16)(float)(ha & 1);
+            b[i][e] = operand_kind ? (bf16)(((int)(hb & 0xffff) - 32768) * (1.0f / 32768.f)) : (bf16)(float)(hb & 1);
+        }
+    f32x16 acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[i * 4 + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i * 4 + j], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s += acc[i][e];
+    if (s == 123456.789f) sink[0] = s;          // keeps the loop alive; practically never true
+}
+
+}  // namespace
+
+}  // namespace sp
+
+extern "C" int sp_probe_mfma_rate(int32_t operand_kind, int32_t milliseconds, void* scratch_device, void* hip_stream,
+                                  float* tflops_host)
+{
+    using namespace sp;
+    if (!scratch_device || !tflops_host || ((uintptr_t)scratch_device & 3)) return SP_EINVAL;
+    if (operand_kind < 0 || operand_kind > 1 || milliseconds < 1 || milliseconds > 2000) return SP_ESHAPE;
+    hipStream_t s = (hipStream_t)hip_stream;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+        return SP_EHIP;
+    const int grid = cus * 4, iters = 2000;        // about half a millisecond per launch
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (hipEventCreate(&e0) != hipSuccess) return SP_EHIP;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return SP_EHIP; }
+    int rc = SP_OK;
+    auto run = [&](int launches, float* ms) {
+        if (hipEventRecord(e0, s) != hipSuccess) return false;
+        for (int i = 0; i < launches; ++i)
+            hipLaunchKernelGGL(mfma_rate_kernel, dim3(grid), dim3(256), 0, s, iters, operand_kind, (float*)scratch_device);
+        if (hipGetLastError() != hipSuccess || hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess)
+            return false;
+        return hipEventElapsedTime(ms, e0, e1) == hipSuccess;
+    };
+    float ms = 0.f;
+    // the clock needs tens of milliseconds of load to settle: an untimed stretch first, then the timed one
+    if (!run(8, &ms)) rc = SP_EHIP;
+    if (rc == SP_OK) {
+        const float per = ms / 8.f;
+        int warm = (int)(60.f / (per > 0.01f ? per : 0.01f)), timed = (int)((float)milliseconds / (per > 0.01f ? per : 0.01f));
+        warm = warm < 1 ? 1 : (warm > 4000 ? 4000 : warm);
+        timed = timed < 1 ? 1 : (timed > 4000 ? 4000 : timed);
+        if (!run(warm, &ms) || !run(timed, &ms)) rc = SP_EHIP;
+        else {
+            const double flops = (double)timed * grid * 4.0 * iters * 16.0 * (2.0 * 32 * 32 * 16);
+            *tflops_host = (float)(flops / (ms * 1e-3) / 1e12);
+        }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return rc;
+}

@@ -54,6 +54,8 @@ def _load() -> C.CDLL:
     lib.sp_forward_profiled.restype = C.c_int
     lib.sp_forward_profiled.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, sz, vp, vp, vp]
     lib.sp_probe_gelu.restype = C.c_int; lib.sp_probe_gelu.argtypes = [vp, vp, C.c_int64, vp]
+    lib.sp_probe_mfma_rate.restype = C.c_int
+    lib.sp_probe_mfma_rate.argtypes = [i32, i32, vp, vp, C.POINTER(C.c_float)]
     lib.sp_free.restype = None; lib.sp_free.argtypes = [vp]
     lib.sp_strerror.restype = C.c_char_p; lib.sp_strerror.argtypes = [C.c_int]
     lib.sp_pack.restype = C.c_int; lib.sp_pack.argtypes = [vp, i32, vp]
@@ -113,6 +115,14 @@ def sp_probe_gelu(x: torch.Tensor) -> torch.Tensor:
     y = torch.empty_like(x)
     _check(_lib.sp_probe_gelu(x.data_ptr(), y.data_ptr(), x.numel(), _stream_ptr(None)))
     return y
+
+
+def sp_probe_mfma_rate(operand_kind: int, milliseconds: int = 200) -> float:
+    """Sustained TFLOP/s of a pure bf16 matrix-instruction loop (0: operands in {0, 1}; 1: random mantissas)."""
+    scratch = torch.zeros(16, dtype=torch.float32, device="cuda")
+    out = C.c_float()
+    _check(_lib.sp_probe_mfma_rate(operand_kind, milliseconds, scratch.data_ptr(), _stream_ptr(None), C.byref(out)))
+    return float(out.value)
 
 
 def sp_pack(lengths) -> np.ndarray:
