@@ -39,7 +39,7 @@ enum {
     SP_ETOOBIG = -8   /* sp_forward_static: the call needs more workspace than the library's static array holds */
 };
 
-enum { SP_DTYPE_FP32 = 0, SP_DTYPE_BF16 = 1 };
+enum { SP_DTYPE_FP32 = 0, SP_DTYPE_BF16 = 1, SP_DTYPE_FP8 = 2 };
 
 /* Shape of the student group.  All students share one architecture (Section 3.1:
  * homogeneous students so that none is a straggler). */
@@ -54,7 +54,16 @@ typedef struct {
     int32_t classes;  /* C, 1..16 */
     int32_t dtype;    /* SP_DTYPE_FP32: fp32 storage and arithmetic;
                          SP_DTYPE_BF16: bf16 weights and activations, fp32 accumulation,
-                         LayerNorm statistics, softmax, GELU, pooling and logits */
+                         LayerNorm statistics, softmax, GELU, pooling and logits;
+                         SP_DTYPE_FP8: quantised students (Section 2, Related Work: the method is orthogonal
+                         to quantisation, every student can be quantised).  The bf16 path, except that in calls
+                         of >= 2048 token rows the query/key/value, FFN-up and FFN-down projections of every
+                         all-token layer run on fp8 (OCP e4m3) operands: weights quantised at load with one
+                         fp32 scale per output feature (max |w| -> 448), activations quantised by the kernel
+                         that produces them as e4m3(16 * value) (one fixed power-of-two scale per tensor; the
+                         FFN activations exist only in fp8), fp32 accumulation, same epilogues.  The attention
+                         output projection, attention itself, the first-token last layer, the head and all
+                         smaller calls stay bf16 (the arena keeps both copies of the three matrices). */
     float ln_eps;     /* LayerNorm epsilon (BERT: 1e-12) */
     int32_t last_layer_all_tokens;
                       /* Only the first token of each sequence feeds the head (the pooled representation of
@@ -207,6 +216,10 @@ typedef struct {
     int32_t act_bytes; /* 4 or 2 */
     size_t first_q, first_att;
     int32_t first_rows;
+    /* SP_DTYPE_FP8 only (0 otherwise), written by calls of >= 2048 token rows: e4m3 codes of 16 * value, one byte
+     * per element, [k_active][rows][width]: xq, x1q copies of x and x1 (width H); gq is GELU(FFN up-projection)
+     * (width F; such calls do not write `g`). */
+    size_t xq, x1q, gq;
 } sp_ws_layout;
 int sp_workspace_layout(const sp_config* cfg, int32_t total_tokens, int32_t batch, sp_ws_layout* out);
 
@@ -248,6 +261,12 @@ int sp_forward_profiled(const sp_model* model, const int32_t* token_ids, const i
  * float32 [n], 1 <= n <= 2^31.  For the test that bounds its distance from the erf definition.
  * Errors: SP_EINVAL, SP_ESHAPE, SP_EHIP. */
 int sp_probe_gelu(const float* x_device, float* y_device, int64_t n, void* hip_stream);
+
+/* codes_host[i] = the OCP e4m3 code (sign, 4 exponent bits with bias 7, 3 mantissa bits; no infinities, largest
+ * finite value 448) the weight loader of SP_DTYPE_FP8 gives x_host[i]: round to nearest even, saturating; NaN -> 0x7f.
+ * Host arrays of n elements; runs on the host.  For the test that pins the loader's rounding.
+ * Errors: SP_EINVAL, SP_ESHAPE (n < 0). */
+int sp_probe_e4m3(const float* x_host, int64_t n, uint8_t* codes_host);
 
 /* What the matrix cores of the current GPU sustain on bf16 operands with nothing else in the way: a loop of the
  * 32x32x16 bf16 matrix instruction on register operands (no memory traffic, sixteen accumulator blocks per wave, one

@@ -1,5 +1,6 @@
 // C ABI of libsp_mi355x.so: argument checks, weight upload, workspace carve-up
 // and the order in which the kernels of one forward pass are enqueued.
+#include <cmath>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -20,7 +21,7 @@ static bool config_ok(const sp_config* c)
     if (c->K < 1 || c->layers < 1 || c->hidden < 1 || c->heads < 1 || c->ffn < 1 || c->vocab < 1 || c->max_pos < 1 ||
         c->classes < 1)
         return false;
-    if (c->dtype != SP_DTYPE_FP32 && c->dtype != SP_DTYPE_BF16) return false;
+    if (c->dtype != SP_DTYPE_FP32 && c->dtype != SP_DTYPE_BF16 && c->dtype != SP_DTYPE_FP8) return false;
     if (!(c->ln_eps >= 0.f)) return false;
     return true;
 }
@@ -37,7 +38,8 @@ static bool config_supported(const sp_config& c)
 ArenaLayout make_arena_layout(const sp_config& c)
 {
     const size_t H = c.hidden, F = c.ffn, C = c.classes;
-    const size_t wb = c.dtype == SP_DTYPE_BF16 ? 2 : 4;  // bytes per matrix / table element
+    const size_t wb = bf16_path(c) ? 2 : 4;  // bytes per matrix / table element
+    const size_t q8 = c.dtype == SP_DTYPE_FP8 ? 1 : 0;     // fp8 copies of three matrices
     ArenaLayout L{};
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
@@ -61,6 +63,14 @@ ArenaLayout make_arena_layout(const sp_config& c)
         L.ln2g = take(H * 4) - base;
         L.ln2b = take(H * 4) - base;
         L.wk_io = take(H * H * wb) - base;
+        if (q8) {
+            L.wqkv8 = take(3 * H * H) - base;
+            L.sqkv = take(3 * H * 4) - base;
+            L.w18 = take(F * H) - base;
+            L.s1 = take(F * 4) - base;
+            L.w28 = take(H * F) - base;
+            L.s2 = take(H * 4) - base;
+        }
         L.layer_stride = o - base;
         o = base + L.layer_stride * (size_t)c.layers;
     }
@@ -76,7 +86,7 @@ ArenaLayout make_arena_layout(const sp_config& c)
 WsLayout make_ws_layout(const sp_config& c, int total_tokens, int batch)
 {
     WsLayout W{};
-    const size_t ab = c.dtype == SP_DTYPE_BF16 ? 2 : 4;
+    const size_t ab = bf16_path(c) ? 2 : 4;
     const size_t rows = align_up((size_t)total_tokens, kRowPad);
     const size_t K = c.K, H = c.hidden, F = c.ffn;
     size_t o = 0;
@@ -103,6 +113,11 @@ WsLayout make_ws_layout(const sp_config& c, int total_tokens, int batch)
     W.cxb = take(K * crows * (size_t)c.heads * H * ab);
     W.part = take(K * (size_t)kSplitMax * kSplitRows * H * 4);
     W.lpart = take(2 * (size_t)batch * c.classes * 4);
+    if (c.dtype == SP_DTYPE_FP8 && rows >= (size_t)kFp8MinRows) {
+        W.xq = take(K * rows * H);
+        W.x1q = take(K * rows * H);
+        W.gq = take(K * rows * F);
+    }
     W.crows = (int)crows;
     W.end = o;
     W.rows = (int)rows;
@@ -126,6 +141,47 @@ static inline uint16_t f32_to_bf16_rne(float f)
     if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);  // NaN stays NaN
     u += 0x7fffu + ((u >> 16) & 1u);
     return (uint16_t)(u >> 16);
+}
+
+// OCP e4m3 (4 exponent bits, bias 7, 3 mantissa bits, no infinities, largest finite value 448): round to nearest
+// even, saturating.
+static inline uint8_t f32_to_e4m3(float f)
+{
+    const uint8_t sign = std::signbit(f) ? 0x80 : 0;
+    const float a = std::fabs(f);
+    if (a != a) return (uint8_t)(sign | 0x7f);
+    if (a >= 448.f) return (uint8_t)(sign | 0x7e);
+    if (a < 0.015625f) {                                   // below 2^-6: multiples of 2^-9
+        const int q = (int)std::nearbyint(a * 512.f);     // 0..8 (8 = the smallest normal number)
+        return (uint8_t)(sign | q);
+    }
+    int e;
+    const float mant = std::frexp(a, &e);                  // a = mant * 2^e, mant in [0.5, 1)
+    int q = (int)std::nearbyint((mant * 2.f - 1.f) * 8.f); // 0..8
+    int ex = e - 1;                                        // a = (1 + q / 8) * 2^ex
+    if (q == 8) { q = 0; ++ex; }
+    const int code = ((ex + 7) << 3) | q;
+    return (uint8_t)(sign | (code > 0x7e ? 0x7e : code));
+}
+
+// dst8[o][i] = e4m3(src[i][o] / scale[o]), scale[o] = max_i |src[i][o]| / 448 (1 for an all-zero column);
+// src is [n_in][n_out]
+static void quantize_transposed(uint8_t* dst8, float* scale, const float* src, size_t n_in, size_t n_out)
+{
+    std::vector<float> amax(n_out, 0.f);
+    for (size_t i = 0; i < n_in; ++i)
+        for (size_t o = 0; o < n_out; ++o) {
+            const float a = std::fabs(src[i * n_out + o]);
+            if (a > amax[o]) amax[o] = a;
+        }
+    for (size_t o = 0; o < n_out; ++o) scale[o] = amax[o] > 0.f ? amax[o] / 448.f : 1.f;
+    const size_t T = 32;
+    for (size_t i0 = 0; i0 < n_in; i0 += T)
+        for (size_t o0 = 0; o0 < n_out; o0 += T) {
+            const size_t i1 = i0 + T < n_in ? i0 + T : n_in, o1 = o0 + T < n_out ? o0 + T : n_out;
+            for (size_t o = o0; o < o1; ++o)
+                for (size_t i = i0; i < i1; ++i) dst8[o * n_in + i] = f32_to_e4m3(src[i * n_out + o] / scale[o]);
+        }
 }
 
 struct Writer {
@@ -159,8 +215,9 @@ struct Writer {
 
 static void fill_student(const sp_config& c, const ArenaLayout& L, const float* src, char* dst)
 {
-    const size_t H = c.hidden, F = c.ffn, C = c.classes, wb = c.dtype == SP_DTYPE_BF16 ? 2 : 4;
-    Writer w{c.dtype == SP_DTYPE_BF16};
+    const size_t H = c.hidden, F = c.ffn, C = c.classes, wb = bf16_path(c) ? 2 : 4;
+    const bool q8 = c.dtype == SP_DTYPE_FP8;
+    Writer w{bf16_path(c)};
     const float* p = src;
     w.copy(dst + L.tok, p, (size_t)c.vocab * H); p += (size_t)c.vocab * H;
     w.copy(dst + L.pos, p, (size_t)c.max_pos * H); p += (size_t)c.max_pos * H;
@@ -170,6 +227,7 @@ static void fill_student(const sp_config& c, const ArenaLayout& L, const float* 
         char* lb = dst + L.layer0 + (size_t)l * L.layer_stride;
         for (int part = 0; part < 3; ++part) {  // Wq bq Wk bk Wv bv -> rows [part*H, part*H+H) of the fused matrix
             if (part == 1) w.copy(lb + L.wk_io, p, H * H);
+            if (q8) quantize_transposed((uint8_t*)(lb + L.wqkv8) + (size_t)part * H * H, (float*)(lb + L.sqkv) + part * H, p, H, H);
             w.transpose(lb + L.wqkv + (size_t)part * H * H * wb, p, H, H); p += H * H;
             memcpy(lb + L.bqkv + (size_t)part * H * 4, p, H * 4); p += H;
         }
@@ -177,8 +235,10 @@ static void fill_student(const sp_config& c, const ArenaLayout& L, const float* 
         memcpy(lb + L.bo, p, H * 4); p += H;
         memcpy(lb + L.ln1g, p, H * 4); p += H;
         memcpy(lb + L.ln1b, p, H * 4); p += H;
+        if (q8) quantize_transposed((uint8_t*)(lb + L.w18), (float*)(lb + L.s1), p, H, F);
         w.transpose(lb + L.w1, p, H, F); p += H * F;
         memcpy(lb + L.b1, p, F * 4); p += F;
+        if (q8) quantize_transposed((uint8_t*)(lb + L.w28), (float*)(lb + L.s2), p, F, H);
         w.transpose(lb + L.w2, p, F, H); p += F * H;
         memcpy(lb + L.b2, p, H * 4); p += H;
         memcpy(lb + L.ln2g, p, H * 4); p += H;
@@ -233,8 +293,13 @@ static int run_students(const sp_model* M0, const WsLayout& W, const int32_t* id
 
 #define SP_TRY(expr) do { if ((expr) != hipSuccess) return SP_EHIP; } while (0)
 #define SP_MARK(ph) do { if (pt) pt->mark(ph, s); } while (0)
+    // quantised students: the three large projections of the all-token layers on fp8 operands (large calls only)
+    const bool fp8 = c.dtype == SP_DTYPE_FP8 && mrows % 256 == 0 && mrows >= kFp8MinRows && W.xq;
+    const size_t qH = (size_t)rows * H, qF = (size_t)rows * F;       // bytes per student of the fp8 buffers
+    char *xq = fp8 ? w + W.xq + m0 * qH : nullptr, *x1q = fp8 ? w + W.x1q + m0 * qH : nullptr;
+    char* gq = fp8 ? w + W.gq + m0 * qF : nullptr;
     SP_MARK(-1);
-    SP_TRY(launch_embed_ln(M, ids, cu, B, T, rows, mrows, k, x, att, s));
+    SP_TRY(launch_embed_ln(M, ids, cu, B, T, rows, mrows, k, x, att, s, xq, kActQuantScale));
     SP_MARK(SP_PHASE_EMBED);
     // Last layer on the first-token rows only (see sp_config.last_layer_all_tokens).  Not used by the partial
     // forwards of the tests unless they stop before the last layer.
@@ -255,7 +320,7 @@ static int run_students(const sp_model* M0, const WsLayout& W, const int32_t* id
     const size_t slice = (size_t)kSplitRows * H;
     float* part = (float*)(w + W.part) + (size_t)m0 * kSplitMax * slice;
     int split_o = 1, split_d = 1;
-    if (c.dtype == SP_DTYPE_BF16 && mrows <= kSplitRows) {
+    if (bf16_path(c) && mrows <= kSplitRows) {
         for (int sp = kSplitMax; sp > 1; --sp) {
             if (split_o == 1 && (H / 64) % sp == 0 && H / 64 / sp >= 2) split_o = sp;
             if (split_d == 1 && (F / 64) % sp == 0 && F / 64 / sp >= 2) split_d = sp;
@@ -294,7 +359,10 @@ static int run_students(const sp_model* M0, const WsLayout& W, const int32_t* id
             compact_final = true;
             continue;
         }
-        if (c.dtype == SP_DTYPE_BF16)
+        if (fp8)
+            SP_TRY(launch_gemm_fp8(M, xq, H, lo + L.wqkv8, lo + L.sqkv, lo + L.bqkv, kActQuantScale, qkv, 3 * H, nullptr, 0,
+                                   mrows, 3 * H, H, k, EPI_QKV, qH, s3H, 0, s, vt, 2 * H, rows, sH, 1.f));
+        else if (bf16_path(c))
             SP_TRY(launch_gemm(M, x, H, lo + L.wqkv, lo + L.bqkv, qkv, 3 * H, nullptr, 0, mrows, 3 * H, H, k, EPI_QKV,
                                sH, s3H, 0, s, vt, 2 * H, rows, sH));
         else
@@ -314,11 +382,15 @@ static int run_students(const sp_model* M0, const WsLayout& W, const int32_t* id
             SP_TRY(launch_gemm(M, att, H, lo + L.wo, lo + L.bo, u, H, x, H, mrows, H, H, k, EPI_BIAS_RESIDUAL, sH, sH, sH,
                                s));
             SP_MARK(SP_PHASE_OPROJ);
-            SP_TRY(launch_layernorm(M, u, x1, rows, mrows, k, lo + L.ln1g, lo + L.ln1b, s));
+            SP_TRY(launch_layernorm(M, u, x1, rows, mrows, k, lo + L.ln1g, lo + L.ln1b, s, x1q, kActQuantScale));
             SP_MARK(SP_PHASE_LAYERNORM);
         }
-        SP_TRY(launch_gemm(M, x1, H, lo + L.w1, lo + L.b1, g, F, nullptr, 0, mrows, F, H, k, EPI_BIAS_GELU, sH, sF, 0,
-                           s));
+        if (fp8)
+            SP_TRY(launch_gemm_fp8(M, x1q, H, lo + L.w18, lo + L.s1, lo + L.b1, kActQuantScale, gq, F, nullptr, 0, mrows, F,
+                                   H, k, EPI_BIAS_GELU, qH, qF, 0, s, nullptr, 0, 0, 0, kActQuantScale));
+        else
+            SP_TRY(launch_gemm(M, x1, H, lo + L.w1, lo + L.b1, g, F, nullptr, 0, mrows, F, H, k, EPI_BIAS_GELU, sH, sF, 0,
+                               s));
         SP_MARK(SP_PHASE_FFN_UP);
         if (split_d > 1) {
             SP_TRY(launch_gemm_splitk(M, g, F, lo + L.w2, part, mrows, H, F, k, split_d, sF, slice, s));
@@ -333,10 +405,14 @@ static int run_students(const sp_model* M0, const WsLayout& W, const int32_t* id
                 SP_MARK(SP_PHASE_LAYERNORM);
             }
         } else {
-            SP_TRY(launch_gemm(M, g, F, lo + L.w2, lo + L.b2, u, H, x1, H, mrows, H, F, k, EPI_BIAS_RESIDUAL, sF, sH, sH,
-                               s));
+            if (fp8)
+                SP_TRY(launch_gemm_fp8(M, gq, F, lo + L.w28, lo + L.s2, lo + L.b2, kActQuantScale, u, H, x1, H, mrows, H, F,
+                                       k, EPI_BIAS_RESIDUAL, qF, sH, sH, s, nullptr, 0, 0, 0, 1.f));
+            else
+                SP_TRY(launch_gemm(M, g, F, lo + L.w2, lo + L.b2, u, H, x1, H, mrows, H, F, k, EPI_BIAS_RESIDUAL, sF, sH,
+                                   sH, s));
             SP_MARK(SP_PHASE_FFN_DOWN);
-            SP_TRY(launch_layernorm(M, u, x, rows, mrows, k, lo + L.ln2g, lo + L.ln2b, s));
+            SP_TRY(launch_layernorm(M, u, x, rows, mrows, k, lo + L.ln2g, lo + L.ln2b, s, xq, kActQuantScale));
             SP_MARK(SP_PHASE_LAYERNORM);
         }
     }
@@ -466,6 +542,7 @@ int sp_workspace_layout(const sp_config* cfg, int32_t total_tokens, int32_t batc
     out->x = W.x; out->qkv = W.qkv; out->vt = W.vt; out->att = W.att; out->x1 = W.x1; out->g = W.g; out->z = W.z;
     out->rows = W.rows; out->act_bytes = W.act_bytes;
     out->first_q = W.cq; out->first_att = W.catt; out->first_rows = W.crows;
+    out->xq = W.xq; out->x1q = W.x1q; out->gq = W.gq;
     return SP_OK;
 }
 
@@ -584,6 +661,14 @@ int sp_forward_profiled(const sp_model* model, const int32_t* token_ids, const i
         }
     pt.release();
     return rc;
+}
+
+int sp_probe_e4m3(const float* x_host, int64_t n, uint8_t* codes_host)
+{
+    if (!x_host || !codes_host) return SP_EINVAL;
+    if (n < 0) return SP_ESHAPE;
+    for (int64_t i = 0; i < n; ++i) codes_host[i] = f32_to_e4m3(x_host[i]);
+    return SP_OK;
 }
 
 int sp_probe_gelu(const float* x_device, float* y_device, int64_t n, void* hip_stream)

@@ -649,7 +649,7 @@ hipError_t launch_attention(const sp_model* M, const void* qkv, const void* vt, 
 {
     const sp_config& c = M->cfg;
     if (c.hidden / c.heads != kD) return hipErrorInvalidValue;
-    if (c.dtype == SP_DTYPE_BF16) {
+    if (bf16_path(c)) {
         // Sequences of up to 128 tokens: one wave per (sequence, head); longer ones: one workgroup per (sequence,
         // head, 128 queries) sharing the key/value tiles.  Each kernel skips the other's sequences.  (Giving the long
         // sequences of a serving batch to the per-wave kernel as well was measured slower: a 256-token sequence is 72
@@ -681,7 +681,7 @@ hipError_t launch_head_gemm(const sp_model* M, const void* A, size_t a_ss, size_
                             size_t o_hs, int ldo, int mrows, int N, int Kd, int k, hipStream_t s)
 {
     const sp_config& c = M->cfg;
-    if (c.dtype != SP_DTYPE_BF16 || mrows % 32 || N % 32 || Kd % 16 || lda % 8 || ldw % 8 || ldo % 8 || a_hs % 8 ||
+    if (!bf16_path(c) || mrows % 32 || N % 32 || Kd % 16 || lda % 8 || ldw % 8 || ldo % 8 || a_hs % 8 ||
         w_hs % 8 || o_hs % 8)
         return hipErrorInvalidValue;
     const int mtiles = mrows / 32;
@@ -703,7 +703,7 @@ hipError_t launch_head_gemm(const sp_model* M, const void* A, size_t a_ss, size_
 
 bool attention_first_fold_supported(const sp_config& c, int max_seqlen)
 {
-    return c.dtype == SP_DTYPE_BF16 && c.hidden / c.heads == kD && c.heads % 4 == 0 && c.heads <= 16 &&
+    return bf16_path(c) && c.hidden / c.heads == kD && c.heads % 4 == 0 && c.heads <= 16 &&
            max_seqlen <= kFoldMaxLen;
 }
 

@@ -42,9 +42,22 @@ __device__ inline void store8(bf16* p, const float (&v)[8])
 // LayerNorm of one row held across a wave as v[chunk][8]; chunk c of lane l covers
 // elements 8*(l + 64c) .. +7.  Two passes over registers: mean, then centred variance.
 // gamma and beta are held the same way (a wave keeps them for all the rows it normalises).
+// eight values -> eight fp8 (e4m3) codes of v * qscale, saturating, packed in 8 bytes
+__device__ inline void store8_fp8(unsigned char* p, const float (&v)[8], float qscale)
+{
+    int lo = 0, hi = 0;
+    lo = __builtin_amdgcn_cvt_pk_fp8_f32(v[0] * qscale, v[1] * qscale, lo, false);
+    lo = __builtin_amdgcn_cvt_pk_fp8_f32(v[2] * qscale, v[3] * qscale, lo, true);
+    hi = __builtin_amdgcn_cvt_pk_fp8_f32(v[4] * qscale, v[5] * qscale, hi, false);
+    hi = __builtin_amdgcn_cvt_pk_fp8_f32(v[6] * qscale, v[7] * qscale, hi, true);
+    *(int2*)p = int2{lo, hi};
+}
+
+// qout (may be null): the same row once more as fp8 codes of value * qscale, for the fp8 projections
 template <typename T, int MAXC>
 __device__ inline void ln_row_store(float (&v)[MAXC][8], int nch, int lane, int H, const float (&gg)[MAXC][8],
-                                    const float (&bb)[MAXC][8], float eps, T* out)
+                                    const float (&bb)[MAXC][8], float eps, T* out, unsigned char* qout = nullptr,
+                                    float qscale = 1.f)
 {
     float s = 0.f;
 #pragma unroll
@@ -68,6 +81,7 @@ __device__ inline void ln_row_store(float (&v)[MAXC][8], int nch, int lane, int 
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[e] = gg[i][e] * ((v[i][e] - mean) * inv) + bb[i][e];
             store8(out + c * 8, o);
+            if (qout) store8_fp8(qout + c * 8, o, qscale);
         }
     }
 }
@@ -94,7 +108,8 @@ __global__ __launch_bounds__(256) void embed_ln_kernel(const char* arena, size_t
                                                        const int32_t* __restrict__ ids,
                                                        const int32_t* __restrict__ cu, int B, int Tn, int rows,
                                                        int mrows, int H, int V, int P, float eps, T* __restrict__ x,
-                                                       T* __restrict__ att, int rpw)
+                                                       T* __restrict__ att, int rpw, unsigned char* __restrict__ xq,
+                                                       float qscale)
 {
     const int m = blockIdx.y, lane = threadIdx.x & 63;
     const int row0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * rpw;
@@ -130,6 +145,8 @@ __global__ __launch_bounds__(256) void embed_ln_kernel(const char* arena, size_t
             const float zero8[8] = {0, 0, 0, 0, 0, 0, 0, 0};
             T* arow = att + ((size_t)m * rows + row) * H;
             for (int c = lane; c < nch; c += 64) { store8(out + c * 8, zero8); store8(arow + c * 8, zero8); }
+            if (xq)
+                for (int c = lane; c < nch; c += 64) *(int2*)(xq + ((size_t)m * rows + row) * H + c * 8) = int2{0, 0};
             continue;
         }
         const int id = __builtin_amdgcn_readlane(my_id, r), pos = __builtin_amdgcn_readlane(my_pos, r);
@@ -147,14 +164,15 @@ __global__ __launch_bounds__(256) void embed_ln_kernel(const char* arena, size_t
                 for (int e = 0; e < 8; ++e) v[i][e] = a[e] + p8[e];
             }
         }
-        ln_row_store<T, MAXC>(v, nch, lane, H, gg, bb, eps, out);
+        ln_row_store<T, MAXC>(v, nch, lane, H, gg, bb, eps, out, xq ? xq + ((size_t)m * rows + row) * H : nullptr, qscale);
     }
 }
 
 template <typename T, int MAXC>
 __global__ __launch_bounds__(256) void layernorm_kernel(const char* arena, size_t student_stride, size_t g_off,
                                                         size_t b_off, const T* __restrict__ u, T* __restrict__ out,
-                                                        int rows, int mrows, int H, float eps, int rpw)
+                                                        int rows, int mrows, int H, float eps, int rpw,
+                                                        unsigned char* __restrict__ outq, float qscale)
 {
     const int m = blockIdx.y, lane = threadIdx.x & 63;
     const int row0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * rpw;
@@ -174,7 +192,8 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const char* arena, size_
             const int c = lane + 64 * i;
             if (c < nch) load8(in + c * 8, v[i]);
         }
-        ln_row_store<T, MAXC>(v, nch, lane, H, gg, bb, eps, out + ((size_t)m * rows + row) * H);
+        ln_row_store<T, MAXC>(v, nch, lane, H, gg, bb, eps, out + ((size_t)m * rows + row) * H,
+                              outq ? outq + ((size_t)m * rows + row) * H : nullptr, qscale);
     }
 }
 
@@ -564,14 +583,14 @@ hipError_t launch_head_classify(const sp_model* M, const void* pooled, int B, in
                                 hipStream_t s)
 {
     const sp_config& c = M->cfg;
-    if (c.dtype != SP_DTYPE_BF16 || k > 64) return hipErrorInvalidValue;
+    if (!bf16_path(c) || k > 64) return hipErrorInvalidValue;
     hipLaunchKernelGGL(head_classify_kernel<bf16>, dim3(B), dim3(256), 0, s, M->arena, M->L.student_stride, M->L.wc,
                        M->L.bc, (const bf16*)pooled, B, crows, c.hidden, c.classes, k, z, logits);
     return hipGetLastError();
 }
 
 hipError_t launch_embed_ln(const sp_model* M, const int32_t* ids, const int32_t* cu, int B, int T, int rows, int mrows,
-                           int k, void* x, void* att, hipStream_t s)
+                           int k, void* x, void* att, hipStream_t s, void* xq, float qscale)
 {
     const sp_config& c = M->cfg;
     const ArenaLayout& L = M->L;
@@ -581,10 +600,10 @@ hipError_t launch_embed_ln(const sp_model* M, const int32_t* ids, const int32_t*
 #define SP_EMBED(T, MAXC)                                                                                          \
     hipLaunchKernelGGL((embed_ln_kernel<T, MAXC>), grid, dim3(256), 0, s, M->arena, L.student_stride, L.tok, L.pos, \
                        L.emb_g, L.emb_b, ids, cu, B, T_, rows, mrows, c.hidden, c.vocab, c.max_pos, c.ln_eps, (T*)x, \
-                       (T*)att, rpw)
+                       (T*)att, rpw, (unsigned char*)xq, qscale)
     const int T_ = T;
     if (maxc > kMaxChunks) return hipErrorInvalidValue;
-    if (c.dtype == SP_DTYPE_BF16) {
+    if (bf16_path(c)) {
         if (maxc <= 1) SP_EMBED(bf16, 1); else if (maxc == 2) SP_EMBED(bf16, 2); else SP_EMBED(bf16, 4);
     } else {
         if (maxc <= 1) SP_EMBED(float, 1); else if (maxc == 2) SP_EMBED(float, 2); else SP_EMBED(float, 4);
@@ -594,7 +613,7 @@ hipError_t launch_embed_ln(const sp_model* M, const int32_t* ids, const int32_t*
 }
 
 hipError_t launch_layernorm(const sp_model* M, const void* u, void* out, int rows, int mrows, int k, size_t g_off,
-                            size_t b_off, hipStream_t s)
+                            size_t b_off, hipStream_t s, void* outq, float qscale)
 {
     const sp_config& c = M->cfg;
     const int rpw = rows_per_wave(mrows, k);
@@ -603,8 +622,8 @@ hipError_t launch_layernorm(const sp_model* M, const void* u, void* out, int row
     if (maxc > kMaxChunks) return hipErrorInvalidValue;
 #define SP_LN(T, MAXC)                                                                                              \
     hipLaunchKernelGGL((layernorm_kernel<T, MAXC>), grid, dim3(256), 0, s, M->arena, M->L.student_stride, g_off,    \
-                       b_off, (const T*)u, (T*)out, rows, mrows, c.hidden, c.ln_eps, rpw)
-    if (c.dtype == SP_DTYPE_BF16) {
+                       b_off, (const T*)u, (T*)out, rows, mrows, c.hidden, c.ln_eps, rpw, (unsigned char*)outq, qscale)
+    if (bf16_path(c)) {
         if (maxc <= 1) SP_LN(bf16, 1); else if (maxc == 2) SP_LN(bf16, 2); else SP_LN(bf16, 4);
     } else {
         if (maxc <= 1) SP_LN(float, 1); else if (maxc == 2) SP_LN(float, 2); else SP_LN(float, 4);
@@ -660,7 +679,7 @@ hipError_t launch_ln_reduce(const sp_model* M, const float* partials, int splits
                             hipStream_t s)
 {
     const sp_config& c = M->cfg;
-    if (c.dtype != SP_DTYPE_BF16 || splits < 1 || splits > kSplitMax) return hipErrorInvalidValue;
+    if (!bf16_path(c) || splits < 1 || splits > kSplitMax) return hipErrorInvalidValue;
     dim3 grid((mrows + 3) / 4, k);
     const int maxc = (c.hidden / 8 + 63) / 64;
     if (maxc > kMaxChunks) return hipErrorInvalidValue;
@@ -678,7 +697,7 @@ hipError_t launch_gather_first(const sp_model* M, const void* x, const int32_t* 
 {
     const sp_config& c = M->cfg;
     dim3 grid((cmrows + 3) / 4, k);
-    if (c.dtype == SP_DTYPE_BF16)
+    if (bf16_path(c))
         hipLaunchKernelGGL(gather_first_kernel<bf16>, grid, dim3(256), 0, s, (const bf16*)x, cu, B, T, rows, c.hidden,
                            (bf16*)xc, (bf16*)attc, crows, cmrows);
     else
@@ -693,7 +712,7 @@ hipError_t launch_head_small(const sp_model* M, const float* partials, int split
 {
     const sp_config& c = M->cfg;
     const ArenaLayout& L = M->L;
-    if (c.dtype != SP_DTYPE_BF16 || splits < 1 || splits > kSplitMax || c.hidden > 1024 || k > kSumStudents)
+    if (!bf16_path(c) || splits < 1 || splits > kSplitMax || c.hidden > 1024 || k > kSumStudents)
         return hipErrorInvalidValue;
     const int nslice = c.hidden / 64;
     dim3 grid((B + kSeqPerWg - 1) / kSeqPerWg, k, nslice);
@@ -717,7 +736,7 @@ hipError_t launch_head(const sp_model* M, const void* x, const int32_t* cu, int 
     const int nslice = c.hidden / 64;
     dim3 grid((B + kSeqPerWg - 1) / kSeqPerWg, k, nslice);
     const size_t smem = (size_t)(kSeqPerWg * c.hidden + 4 * kSeqPerWg * 64) * sizeof(float);
-    if (c.dtype == SP_DTYPE_BF16)
+    if (bf16_path(c))
         hipLaunchKernelGGL(head_pool_kernel<bf16>, grid, dim3(256), smem, s, M->arena, L.student_stride, L.wp, L.bp,
                            L.wc, (const bf16*)x, cu, B, T, rows, c.hidden, c.classes, zpart);
     else

@@ -13,28 +13,6 @@ namespace {
 
 __device__ inline float gelu_erf(float u) { return 0.5f * u * (1.0f + erff(u * 0.70710678118654752f)); }
 
-// GELU (erf form) for outputs that are rounded to bf16 afterwards, written with the complementary error function:
-//   gelu(x) = x (1 + erf(x / sqrt 2)) / 2 = max(x, 0) - |x| erfc(|x| / sqrt 2) / 2,
-//   log2 erfc(z) = z Q(z) on [0, 4.3], Q a degree-5 minimax fit (weighted for the absolute error of gelu);
-//   erfc(4.3) = 1.2e-9, so |x| is clamped at 4.3 sqrt 2 (in the erfc term only: beyond it the term stays below 4e-9
-//   instead of growing with |x|).
-// Evaluated in fp32 the result is within 3.2e-7 of the exact function for every x (0.03 bf16 ulp at most where
-// |gelu| > 1e-3).  One quarter-rate instruction (exp2) and eleven full-rate ones: the epilogue of the FFN
-// up-projection is bound by these vector instructions while the matrix cores wait (libm's erff costs several times
-// more; the rational-exponential formula 7.1.26 of Abramowitz & Stegun needs a reciprocal as well).
-__device__ inline float gelu_erf_fast(float x)
-{
-    const float ax = __builtin_fminf(__builtin_fabsf(x), 6.0811f);
-    const float z = ax * 0.70710678118654752f;
-    float q = __builtin_fmaf(2.393906887e-04f, z, -4.185345790e-03f);
-    q = __builtin_fmaf(q, z, 3.190982192e-02f);
-    q = __builtin_fmaf(q, z, -1.505803052e-01f);
-    q = __builtin_fmaf(q, z, -9.178313831e-01f);
-    q = __builtin_fmaf(q, z, -1.627967815e+00f);
-    const float e = __builtin_amdgcn_exp2f(q * z);
-    return __builtin_fmaf(-0.5f * ax, e, __builtin_fmaxf(x, 0.0f));
-}
-
 // -------------------------------------------------------------------------------------
 // bf16 MFMA kernel (v_mfma_f32_32x32x16_bf16), 256 threads = 2 x 2 waves, tile BM tokens x BN features.
 //
@@ -64,21 +42,6 @@ __device__ inline float gelu_erf_fast(float x)
 //   * the accumulators start from the bias values, which are the first loads of the kernel (sixteen dependent
 //     global loads in the epilogue cost several microseconds per tile, and so the adds disappear as well).
 // -------------------------------------------------------------------------------------
-typedef __attribute__((address_space(3))) void lds_void;
-typedef __attribute__((address_space(1))) const void gbl_void;
-
-template <int N>
-__device__ inline void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
-
-// Workgroup barrier that waits for this wave's LDS traffic only.  (__syncthreads() also waits for every
-// outstanding global load, which would serialise the loads that are deliberately left in flight across it.)
-__device__ inline void barrier_lds()
-{
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-}
-
 template <int BM, int BN>
 struct GemmTile {
     static constexpr int BK = 64, NS = 2, STEPS = 4, LSPREAD = 2;
@@ -633,7 +596,7 @@ hipError_t launch_gelu_probe(const float* x, float* y, long n, hipStream_t s)
 hipError_t launch_gemm_splitk(const sp_model* M, const void* A, int lda, size_t w_off, float* partials, int mrows, int N,
                               int Kd, int k, int splits, size_t a_student_stride, size_t slice_elems, hipStream_t s)
 {
-    if (M->cfg.dtype != SP_DTYPE_BF16 || splits < 1 || mrows % 64 || N % 64 || Kd % (64 * splits) || Kd / splits < 128 ||
+    if (!bf16_path(M->cfg) || splits < 1 || mrows % 64 || N % 64 || Kd % (64 * splits) || Kd / splits < 128 ||
         slice_elems < (size_t)mrows * N)
         return hipErrorInvalidValue;
     return launch_bf16_tile<64, 64, EPI_PARTIAL>(M, A, lda, w_off, 0, partials, N, nullptr, 0, mrows, N, Kd / splits, k,
@@ -647,10 +610,10 @@ hipError_t launch_gemm(const sp_model* M, const void* A, int lda, size_t w_off, 
 {
     // shapes the kernels assume; config_supported() guarantees them for every model that loads
     if (mrows % 64 || N % 64 || Kd % 128 || (epi == EPI_BIAS_RESIDUAL && !residual)) return hipErrorInvalidValue;
-    if (epi == EPI_QKV && (M->cfg.dtype != SP_DTYPE_BF16 || !out2 || n_split % 64 || ld2 % 8)) return hipErrorInvalidValue;
+    if (epi == EPI_QKV && (!bf16_path(M->cfg) || !out2 || n_split % 64 || ld2 % 8)) return hipErrorInvalidValue;
 #define SP_ARGS M, A, lda, w_off, b_off, out, ldo, residual, ldr, mrows, N, Kd, k, a_student_stride, \
                 o_student_stride, r_student_stride, s
-    if (M->cfg.dtype == SP_DTYPE_BF16) {
+    if (bf16_path(M->cfg)) {
         switch (epi) {
             case EPI_BIAS: return launch_bf16<EPI_BIAS>(SP_ARGS, nullptr, 0, 0, 0);
             case EPI_BIAS_GELU: return launch_bf16<EPI_BIAS_GELU>(SP_ARGS, nullptr, 0, 0, 0);

@@ -12,16 +12,66 @@
 
 namespace sp {
 
+// SP_DTYPE_FP8 is the bf16 path with fp8 copies of three projection matrices: everything that asks "bf16 or fp32
+// storage" treats the two alike.
+inline bool bf16_path(const sp_config& c) { return c.dtype != SP_DTYPE_FP32; }
+
 typedef __bf16 bf16;
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
+#if defined(__HIPCC__)
+// ---- device helpers shared by the projection kernels ---------------------------------------------
+// GELU (erf form) for outputs that are rounded to bf16 afterwards, written with the complementary error function:
+//   gelu(x) = x (1 + erf(x / sqrt 2)) / 2 = max(x, 0) - |x| erfc(|x| / sqrt 2) / 2,
+//   log2 erfc(z) = z Q(z) on [0, 4.3], Q a degree-5 minimax fit (weighted for the absolute error of gelu);
+//   erfc(4.3) = 1.2e-9, so |x| is clamped at 4.3 sqrt 2 (in the erfc term only: beyond it the term stays below 4e-9
+//   instead of growing with |x|).
+// Evaluated in fp32 the result is within 3.2e-7 of the exact function for every x (0.03 bf16 ulp at most where
+// |gelu| > 1e-3).  One quarter-rate instruction (exp2) and eleven full-rate ones: the epilogue of the FFN
+// up-projection is bound by these vector instructions while the matrix cores wait (libm's erff costs several times
+// more; the rational-exponential formula 7.1.26 of Abramowitz & Stegun needs a reciprocal as well).
+__device__ inline float gelu_erf_fast(float x)
+{
+    const float ax = __builtin_fminf(__builtin_fabsf(x), 6.0811f);
+    const float z = ax * 0.70710678118654752f;
+    float q = __builtin_fmaf(2.393906887e-04f, z, -4.185345790e-03f);
+    q = __builtin_fmaf(q, z, 3.190982192e-02f);
+    q = __builtin_fmaf(q, z, -1.505803052e-01f);
+    q = __builtin_fmaf(q, z, -9.178313831e-01f);
+    q = __builtin_fmaf(q, z, -1.627967815e+00f);
+    const float e = __builtin_amdgcn_exp2f(q * z);
+    return __builtin_fmaf(-0.5f * ax, e, __builtin_fmaxf(x, 0.0f));
+}
+
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void gbl_void;
+
+template <int N>
+__device__ inline void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
+// Workgroup barrier that waits for this wave's LDS traffic only.  (__syncthreads() also waits for every
+// outstanding global load, which would serialise the loads that are deliberately left in flight across it.)
+__device__ inline void barrier_lds()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+#endif  // __HIPCC__
+
 constexpr int kRowPad = 256;  // activation rows per student are padded to a multiple of this
 constexpr int kSplitMax = 8;  // slices of a split reduction (small calls only)
 constexpr int kSplitRows = 128;   // most token rows a call may compute and still take the split path
 constexpr int kFirstOnlyMinTokens = 1024;   // smallest call whose last layer runs on the first-token rows only
+// fp8 projections: activations are quantised as e4m3(value * kActQuantScale) by the kernel that produces them
+// (LayerNorm outputs and GELU outputs are of order one: 448 / 16 = 28 before saturation, 2^-6 / 16 = 1e-3 before the
+// subnormal range), and only calls that compute at least kFp8MinRows rows use them
+constexpr float kActQuantScale = 16.f;
+constexpr int kFp8MinRows = 2048;
 
 // Byte offsets of every tensor inside one student's slab of the weight arena.
 // The encoder matrices are stored transposed with respect to the host blob,
@@ -33,6 +83,9 @@ struct ArenaLayout {
     // relative to the start of a layer
     size_t wqkv, bqkv, wo, bo, ln1g, ln1b, w1, b1, w2, b2, ln2g, ln2b;
     size_t wk_io;                  // the key projection once more, [in][out] as in the host blob (folded first-token queries)
+    // SP_DTYPE_FP8 only (0 otherwise), relative to the start of a layer: the fused q|k|v, FFN-up and FFN-down
+    // matrices once more as e4m3 codes, [out][in] bytes, and their per-output-feature scales (fp32)
+    size_t wqkv8, sqkv, w18, s1, w28, s2;
     size_t wp, wp_t, bp, wc, bc;   // wp: [in][out] (column-parallel head kernel); wp_t: [out][in] (GEMM operand)
     size_t student_stride;
 };
@@ -46,6 +99,7 @@ struct WsLayout {
     size_t cqt, cxb;                     // folded queries / weighted mean rows: [K][crows][heads][H]
     size_t part;                         // fp32 partial sums of split reductions: [K][kSplitMax][kSplitRows][H]
     size_t lpart;                        // per-group logit sums when two groups of students run side by side: [2][B][C]
+    size_t xq, x1q, gq;                  // SP_DTYPE_FP8 only: fp8 copies of x and x1 ([K][rows][H] bytes), fp8 g ([K][rows][F])
     int rows, crows;
     int act_bytes;
 };
@@ -69,12 +123,13 @@ namespace sp {
 
 // X[m][row][:] = LN(tok[id[row]] + pos[row - cu[seq(row)]]) for row < T; zero rows up to `rows`.
 // Rows T..mrows of x and of att are zeroed.
+// xq (may be null): the rows once more as fp8 (e4m3) codes of value * qscale, [m][rows][H] bytes.
 hipError_t launch_embed_ln(const sp_model* M, const int32_t* ids, const int32_t* cu, int B, int T, int rows,
-                           int mrows, int k, void* x, void* att, hipStream_t s);
+                           int mrows, int k, void* x, void* att, hipStream_t s, void* xq = nullptr, float qscale = 1.f);
 
 // out[m][row][:] = LN(u[m][row][:]; g, b); g/b are byte offsets into the student slab.
 hipError_t launch_layernorm(const sp_model* M, const void* u, void* out, int rows, int mrows, int k, size_t g_off,
-                            size_t b_off, hipStream_t s);
+                            size_t b_off, hipStream_t s, void* outq = nullptr, float qscale = 1.f);
 
 // EPI_QKV (bf16 path only): bias; output columns >= n_split (the value projection) are written transposed,
 // out2[m][column - n_split][row], so that attention reads key-contiguous value tiles.
@@ -87,6 +142,16 @@ hipError_t launch_gemm(const sp_model* M, const void* A, int lda, size_t w_off, 
                        const void* residual, int ldr, int mrows, int N, int Kd, int k, Epilogue epi,
                        size_t a_student_stride, size_t o_student_stride, size_t r_student_stride, hipStream_t s,
                        void* out2 = nullptr, int n_split = 0, int ld2 = 0, size_t o2_student_stride = 0);
+
+// The same projection on fp8 operands (SP_DTYPE_FP8; 256 x 256 tile only: mrows and N multiples of 256, Kd of 128).
+// A8: e4m3 codes of activation * a_qscale, [m][row][lda] bytes; weights at w_off (e4m3, [N][Kd] bytes) with fp32
+// scales at s_off; epi is EPI_QKV (bf16 out, value third transposed into out2), EPI_BIAS_GELU (out: e4m3 codes of
+// gelu(.) * out_qscale, ldo bytes per row) or EPI_BIAS_RESIDUAL (bf16 out).  Student strides in bytes.
+hipError_t launch_gemm_fp8(const sp_model* M, const void* A8, int lda, size_t w_off, size_t s_off, size_t b_off,
+                           float a_qscale, void* out, int ldo, const void* residual, int ldr, int mrows, int N, int Kd,
+                           int k, Epilogue epi, size_t a_student_stride, size_t o_student_stride,
+                           size_t r_student_stride, hipStream_t s, void* out2, int n_split, int ld2,
+                           size_t o2_student_stride, float out_qscale);
 
 // y[i] = GELU as the bf16 FFN up-projection's epilogue evaluates it, in fp32 (i < n).  Test aid.
 hipError_t launch_gelu_probe(const float* x, float* y, long n, hipStream_t s);

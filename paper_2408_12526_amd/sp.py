@@ -16,7 +16,8 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsp_mi355x.so")
 
-SP_DTYPE_FP32, SP_DTYPE_BF16 = 0, 1
+SP_DTYPE_FP32, SP_DTYPE_BF16, SP_DTYPE_FP8 = 0, 1, 2
+ACT_QUANT_SCALE = 16.0      # fp8 activations hold e4m3(16 * value)
 SP_BAD_ID, SP_BAD_CU0, SP_BAD_ORDER, SP_BAD_LENGTH, SP_BAD_TOTAL = 1, 2, 4, 8, 16
 PHASES = ("embed", "qkv", "attention", "oproj", "layernorm", "ffn_up", "ffn_down", "head", "last_first")
 
@@ -30,7 +31,7 @@ class sp_config(C.Structure):
 class sp_ws_layout(C.Structure):
     _fields_ = [(n, C.c_size_t) for n in ("x", "qkv", "vt", "att", "x1", "g", "z")] + [
         ("rows", C.c_int32), ("act_bytes", C.c_int32), ("first_q", C.c_size_t), ("first_att", C.c_size_t),
-        ("first_rows", C.c_int32)]
+        ("first_rows", C.c_int32), ("xq", C.c_size_t), ("x1q", C.c_size_t), ("gq", C.c_size_t)]
 
 
 def _load() -> C.CDLL:
@@ -54,6 +55,7 @@ def _load() -> C.CDLL:
     lib.sp_forward_profiled.restype = C.c_int
     lib.sp_forward_profiled.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, sz, vp, vp, vp]
     lib.sp_probe_gelu.restype = C.c_int; lib.sp_probe_gelu.argtypes = [vp, vp, C.c_int64, vp]
+    lib.sp_probe_e4m3.restype = C.c_int; lib.sp_probe_e4m3.argtypes = [vp, C.c_int64, vp]
     lib.sp_probe_mfma_rate.restype = C.c_int
     lib.sp_probe_mfma_rate.argtypes = [i32, i32, vp, vp, C.POINTER(C.c_float)]
     lib.sp_free.restype = None; lib.sp_free.argtypes = [vp]
@@ -83,7 +85,7 @@ def _check(rc: int) -> None:
 def make_config(K, layers, hidden, heads, ffn, vocab, max_pos, classes, dtype="bf16", ln_eps=1e-12,
                 last_layer_all_tokens=False, single_stream=False) -> sp_config:
     return sp_config(K, layers, hidden, heads, ffn, vocab, max_pos, classes,
-                     SP_DTYPE_BF16 if dtype == "bf16" else SP_DTYPE_FP32, ln_eps, 1 if last_layer_all_tokens else 0,
+                     {"bf16": SP_DTYPE_BF16, "fp8": SP_DTYPE_FP8, "fp32": SP_DTYPE_FP32}[dtype], ln_eps, 1 if last_layer_all_tokens else 0,
                      1 if single_stream else 0)
 
 
@@ -115,6 +117,14 @@ def sp_probe_gelu(x: torch.Tensor) -> torch.Tensor:
     y = torch.empty_like(x)
     _check(_lib.sp_probe_gelu(x.data_ptr(), y.data_ptr(), x.numel(), _stream_ptr(None)))
     return y
+
+
+def sp_probe_e4m3(x: np.ndarray) -> np.ndarray:
+    """e4m3 codes (uint8) the fp8 weight loader gives the float32 values x (host only)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.size, dtype=np.uint8)
+    _check(_lib.sp_probe_e4m3(x.ctypes.data, x.size, out.ctypes.data))
+    return out.reshape(x.shape)
 
 
 def sp_probe_mfma_rate(operand_kind: int, milliseconds: int = 200) -> float:
@@ -234,6 +244,11 @@ class Students:
             n = k_active * lay.first_rows * H
             t = ws[off:off + n * lay.act_bytes].view(dt).view(k_active, lay.first_rows, H)
             return t[:, :batch].double().cpu().numpy()
+        if name in ("xq", "x1q", "gq"):              # fp8 activations: e4m3 codes of 16 * value, [k][rows][width] bytes
+            width, off = (F if name == "gq" else H), getattr(lay, name)
+            n = k_active * lay.rows * width
+            t = ws[off:off + n].view(torch.float8_e4m3fn).view(k_active, lay.rows, width)
+            return (t[:, :total_tokens].float().double() / ACT_QUANT_SCALE).cpu().numpy()
         width = {"x": H, "qkv": 3 * H, "att": H, "x1": H, "g": F}[name]
         off = getattr(lay, name)
         dt = torch.bfloat16 if lay.act_bytes == 2 else torch.float32

@@ -80,3 +80,27 @@ def test_argument_errors_without_touching_a_gpu(sp):
     assert lib.sp_load_students(C.byref(cfg), None, 0, None, 0, None, C.byref(out)) == -1
     assert b"k_active" in lib.sp_strerror(-3)
     assert lib.sp_strerror(-99) is not None
+
+
+def test_e4m3_encoder_matches_the_library_conversion_bit_for_bit(sp):
+    """The fp8 weight loader's float32 -> e4m3 rounding (host code) against torch's float8_e4m3fn conversion: every
+    code exactly, on a dense sweep of the whole finite range including the subnormal codes, exact ties, both signs
+    and the saturation point (the loader never produces magnitudes above 448: it scales each row so that its largest
+    weight is 448)."""
+    import numpy as np
+    import torch
+    rng = np.random.default_rng(5)
+    codes = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).float().numpy()
+    finite = np.sort(codes[np.isfinite(codes)])
+    mids = (finite[1:] + finite[:-1]) / 2                      # exact ties between neighbouring codes
+    x = np.concatenate([finite, mids, np.nextafter(mids, np.inf).astype(np.float32),
+                        np.nextafter(mids, -np.inf).astype(np.float32),
+                        rng.uniform(-448, 448, 200_000), rng.normal(0, 1, 200_000), rng.normal(0, 0.01, 100_000),
+                        rng.uniform(-2.0 ** -6, 2.0 ** -6, 100_000), [0.0, -0.0, 448.0, -448.0, 2.0 ** -9, 2.0 ** -10,
+                                                                       1.5 * 2.0 ** -10, 2.0 ** -11]]).astype(np.float32)
+    got = sp.sp_probe_e4m3(x)
+    want = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    bad = np.flatnonzero(got != want)
+    # (-0.0 and +0.0: both conversions keep the sign bit)
+    assert bad.size == 0, f"{bad.size} codes differ, first at x = {x[bad[0]]!r}: {got[bad[0]]:#x} vs {want[bad[0]]:#x}"
+    assert sp.sp_probe_e4m3(np.array([1e9, -1e9, 464.0], np.float32)).tolist() == [0x7e, 0xfe, 0x7e]   # saturating
