@@ -33,6 +33,7 @@ os.environ.setdefault("GPU_MAX_HW_QUEUES", "8")
 PEAK_BF16_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 PEAK_FP32_TFLOPS = 157.3
+PEAK_FP8_TFLOPS = 5000.0
 
 
 def percentile(xs, q):
@@ -461,6 +462,30 @@ def main():
                 st4.sp_forward(d_ids4, d_cu4, mx4, 8, logits4, ws4)
             torch.cuda.synchronize()
         phases["power_clock_during_burst_k8"] = sampled_while(busy, 1.5)
+        # quantised students (SP_DTYPE_FP8) on the same batch: step time and the three fp8 projection launches
+        import dataclasses
+        shape8 = dataclasses.replace(w4.shape, dtype="fp8")
+        st8 = sp.Students(sp.config_from_shape(shape8, single_stream=args.single_stream), blob4)
+        ws8 = st8.workspace(T4, B4)
+        sec8 = timed_steps(st8, d_ids4, d_cu4, mx4, 8, logits4, ws8, args.steps, args.warmup)
+        acc8 = {n: 0.0 for n in sp.PHASES}
+        for _ in range(args.steps):
+            for n, v in st8.sp_forward_profiled(d_ids4, d_cu4, mx4, 8, logits4, ws8).items():
+                acc8[n] += v / args.steps
+        fp8_ceiling = {"operands_0_or_1_tflops": sp.sp_probe_mfma_rate(2, 150),
+                       "operands_random_tflops": sp.sp_probe_mfma_rate(3, 150)}
+        fp8_rec = {"ms_per_step": sec8 * 1e3, "sequences_per_s": B4 / sec8,
+                   "what": "SP_DTYPE_FP8: q|k|v, FFN-up and FFN-down projections of the all-token layer on e4m3 operands "
+                           "(fp32 accumulate), everything else as in the bf16 mode; logits within 1e-1 of the oracle on "
+                           "de-quantised weights instead of 3e-2",
+                   "phases": {n: {"ms": acc8[n], "bound": "mfma", "tflops": gf[n] / acc8[n] / 1e9,
+                                  "frac": gf[n] / acc8[n] / 1e9 / PEAK_FP8_TFLOPS, "peak": PEAK_FP8_TFLOPS}
+                              for n in ("qkv", "ffn_up", "ffn_down")},
+                   "other_phases_ms": {n: acc8[n] for n in sp.PHASES if n not in ("qkv", "ffn_up", "ffn_down")},
+                   "mfma_loop_ceiling_fp8": fp8_ceiling}
+        phases["quantised_students_fp8_k8"] = fp8_rec
+        st8.close()
+        del st8, ws8
         # the stock variant (every token through the whole last layer), for reference
         st4a = sp.Students(sp.config_from_shape(w4.shape, last_layer_all_tokens=True, single_stream=args.single_stream),
                            blob4)

@@ -272,7 +272,8 @@ int sp_probe_e4m3(const float* x_host, int64_t n, uint8_t* codes_host);
  * 32x32x16 bf16 matrix instruction on register operands (no memory traffic, sixteen accumulator blocks per wave, one
  * wave per SIMD, every compute unit busy), run for about `milliseconds` (1..2000) after an untimed stretch that lets
  * the clock settle.  operand_kind 0: every element 0 or 1; 1: uniform in (-1, 1) with full mantissas, which is what
- * weights and activations look like and what the package power limit prices.  *tflops_host receives the rate.
+ * weights and activations look like and what the package power limit prices; 2 and 3: the same two kinds of data
+ * for the fp8 (e4m3) 32x32x64 instruction of the quantised students' projections.  *tflops_host receives the rate.
  * The projection kernels' fractions of the published peak are quoted next to this measured ceiling.  Creates and
  * destroys two events and blocks until the run has finished: a measurement aid.
  *   scratch_device  device, >= 4 bytes, 4-byte aligned (practically never written)

@@ -49,6 +49,44 @@ __global__ __launch_bounds__(256, 1) void mfma_rate_kernel(int iters, int operan
     if (s == 123456.789f) sink[0] = s;          // keeps the loop alive; practically never true
 }
 
+typedef int v8i __attribute__((ext_vector_type(8)));
+
+// the same loop on fp8 (e4m3) operands: v_mfma_f32_32x32x64_f8f6f4, 64 reduction elements per instruction.
+// operand_kind 2: every element 0 or 1 (codes 0x00 / 0x38); 3: random codes with full mantissas, magnitudes below 2
+__global__ __launch_bounds__(256, 1) void mfma_fp8_rate_kernel(int iters, int operand_kind, float* sink)
+{
+    v8i a[4], b[4];
+    const unsigned id = (blockIdx.x * 256u + threadIdx.x) * 64u;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const unsigned ha = mix(id + i * 8 + e), hb = mix(id + 32 + i * 8 + e);
+            // random: sign and mantissa bits free, exponent field 0..7 (bit 6 clear): |value| < 2
+            a[i][e] = operand_kind == 3 ? (int)(ha & 0xbfbfbfbfu) : (int)(((ha & 0x01010101u) * 0x38u));
+            b[i][e] = operand_kind == 3 ? (int)(hb & 0xbfbfbfbfu) : (int)(((hb & 0x01010101u) * 0x38u));
+        }
+    f32x16 acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[i * 4 + j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[j], acc[i * 4 + j], 0, 0, 0,
+                                                                                 0x7f7f7f7f, 0, 0x7f7f7f7f);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s += acc[i][e];
+    if (s == 123456.789f) sink[0] = s;
+}
+
 }  // namespace
 
 }  // namespace sp
@@ -58,7 +96,7 @@ extern "C" int sp_probe_mfma_rate(int32_t operand_kind, int32_t milliseconds, vo
 {
     using namespace sp;
     if (!scratch_device || !tflops_host || ((uintptr_t)scratch_device & 3)) return SP_EINVAL;
-    if (operand_kind < 0 || operand_kind > 1 || milliseconds < 1 || milliseconds > 2000) return SP_ESHAPE;
+    if (operand_kind < 0 || operand_kind > 3 || milliseconds < 1 || milliseconds > 2000) return SP_ESHAPE;
     hipStream_t s = (hipStream_t)hip_stream;
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess ||
@@ -71,8 +109,12 @@ extern "C" int sp_probe_mfma_rate(int32_t operand_kind, int32_t milliseconds, vo
     int rc = SP_OK;
     auto run = [&](int launches, float* ms) {
         if (hipEventRecord(e0, s) != hipSuccess) return false;
-        for (int i = 0; i < launches; ++i)
-            hipLaunchKernelGGL(mfma_rate_kernel, dim3(grid), dim3(256), 0, s, iters, operand_kind, (float*)scratch_device);
+        for (int i = 0; i < launches; ++i) {
+            if (operand_kind >= 2)
+                hipLaunchKernelGGL(mfma_fp8_rate_kernel, dim3(grid), dim3(256), 0, s, iters, operand_kind, (float*)scratch_device);
+            else
+                hipLaunchKernelGGL(mfma_rate_kernel, dim3(grid), dim3(256), 0, s, iters, operand_kind, (float*)scratch_device);
+        }
         if (hipGetLastError() != hipSuccess || hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess)
             return false;
         return hipEventElapsedTime(ms, e0, e1) == hipSuccess;
@@ -87,7 +129,7 @@ extern "C" int sp_probe_mfma_rate(int32_t operand_kind, int32_t milliseconds, vo
         timed = timed < 1 ? 1 : (timed > 4000 ? 4000 : timed);
         if (!run(warm, &ms) || !run(timed, &ms)) rc = SP_EHIP;
         else {
-            const double flops = (double)timed * grid * 4.0 * iters * 16.0 * (2.0 * 32 * 32 * 16);
+            const double flops = (double)timed * grid * 4.0 * iters * 16.0 * (2.0 * 32 * 32 * (operand_kind >= 2 ? 64 : 16));
             *tflops_host = (float)(flops / (ms * 1e-3) / 1e12);
         }
     }
