@@ -475,13 +475,13 @@ def main():
         fp8_ceiling = {"operands_0_or_1_tflops": sp.sp_probe_mfma_rate(2, 150),
                        "operands_random_tflops": sp.sp_probe_mfma_rate(3, 150)}
         fp8_rec = {"ms_per_step": sec8 * 1e3, "sequences_per_s": B4 / sec8,
-                   "what": "SP_DTYPE_FP8: q|k|v, FFN-up and FFN-down projections of the all-token layer on e4m3 operands "
+                   "what": "SP_DTYPE_FP8: the four projections of the all-token layer on e4m3 operands "
                            "(fp32 accumulate), everything else as in the bf16 mode; logits within 1e-1 of the oracle on "
                            "de-quantised weights instead of 3e-2",
                    "phases": {n: {"ms": acc8[n], "bound": "mfma", "tflops": gf[n] / acc8[n] / 1e9,
                                   "frac": gf[n] / acc8[n] / 1e9 / PEAK_FP8_TFLOPS, "peak": PEAK_FP8_TFLOPS}
-                              for n in ("qkv", "ffn_up", "ffn_down")},
-                   "other_phases_ms": {n: acc8[n] for n in sp.PHASES if n not in ("qkv", "ffn_up", "ffn_down")},
+                              for n in ("qkv", "oproj", "ffn_up", "ffn_down")},
+                   "other_phases_ms": {n: acc8[n] for n in sp.PHASES if n not in ("qkv", "oproj", "ffn_up", "ffn_down")},
                    "mfma_loop_ceiling_fp8": fp8_ceiling}
         phases["quantised_students_fp8_k8"] = fp8_rec
         st8.close()

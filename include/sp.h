@@ -57,13 +57,13 @@ typedef struct {
                          LayerNorm statistics, softmax, GELU, pooling and logits;
                          SP_DTYPE_FP8: quantised students (Section 2, Related Work: the method is orthogonal
                          to quantisation, every student can be quantised).  The bf16 path, except that in calls
-                         of >= 2048 token rows the query/key/value, FFN-up and FFN-down projections of every
-                         all-token layer run on fp8 (OCP e4m3) operands: weights quantised at load with one
+                         of >= 2048 token rows the four projections (query/key/value, attention output, FFN
+                         up, FFN down) of every all-token layer run on fp8 (OCP e4m3) operands: weights quantised at load with one
                          fp32 scale per output feature (max |w| -> 448), activations quantised by the kernel
                          that produces them as e4m3(16 * value) (one fixed power-of-two scale per tensor; the
-                         FFN activations exist only in fp8), fp32 accumulation, same epilogues.  The attention
-                         output projection, attention itself, the first-token last layer, the head and all
-                         smaller calls stay bf16 (the arena keeps both copies of the three matrices). */
+                         FFN activations exist only in fp8), fp32 accumulation, same epilogues.  Attention
+                         itself, the first-token last layer, the head and all smaller calls stay bf16 (the
+                         arena keeps both copies of the four matrices). */
     float ln_eps;     /* LayerNorm epsilon (BERT: 1e-12) */
     int32_t last_layer_all_tokens;
                       /* Only the first token of each sequence feeds the head (the pooled representation of
@@ -217,9 +217,9 @@ typedef struct {
     size_t first_q, first_att;
     int32_t first_rows;
     /* SP_DTYPE_FP8 only (0 otherwise), written by calls of >= 2048 token rows: e4m3 codes of 16 * value, one byte
-     * per element, [k_active][rows][width]: xq, x1q copies of x and x1 (width H); gq is GELU(FFN up-projection)
-     * (width F; such calls do not write `g`). */
-    size_t xq, x1q, gq;
+     * per element, [k_active][rows][width]: xq, x1q, attq copies of x, x1 and att (width H); gq is GELU(FFN
+     * up-projection) (width F; such calls do not write `g`). */
+    size_t xq, x1q, gq, attq;
 } sp_ws_layout;
 int sp_workspace_layout(const sp_config* cfg, int32_t total_tokens, int32_t batch, sp_ws_layout* out);
 

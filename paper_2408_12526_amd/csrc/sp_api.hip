@@ -66,6 +66,8 @@ ArenaLayout make_arena_layout(const sp_config& c)
         if (q8) {
             L.wqkv8 = take(3 * H * H) - base;
             L.sqkv = take(3 * H * 4) - base;
+            L.wo8 = take(H * H) - base;
+            L.so = take(H * 4) - base;
             L.w18 = take(F * H) - base;
             L.s1 = take(F * 4) - base;
             L.w28 = take(H * F) - base;
@@ -116,6 +118,7 @@ WsLayout make_ws_layout(const sp_config& c, int total_tokens, int batch)
     if (c.dtype == SP_DTYPE_FP8 && rows >= (size_t)kFp8MinRows) {
         W.xq = take(K * rows * H);
         W.x1q = take(K * rows * H);
+        W.attq = take(K * rows * H);
         W.gq = take(K * rows * F);
     }
     W.crows = (int)crows;
@@ -231,6 +234,7 @@ static void fill_student(const sp_config& c, const ArenaLayout& L, const float* 
             w.transpose(lb + L.wqkv + (size_t)part * H * H * wb, p, H, H); p += H * H;
             memcpy(lb + L.bqkv + (size_t)part * H * 4, p, H * 4); p += H;
         }
+        if (q8) quantize_transposed((uint8_t*)(lb + L.wo8), (float*)(lb + L.so), p, H, H);
         w.transpose(lb + L.wo, p, H, H); p += H * H;
         memcpy(lb + L.bo, p, H * 4); p += H;
         memcpy(lb + L.ln1g, p, H * 4); p += H;
@@ -297,9 +301,9 @@ static int run_students(const sp_model* M0, const WsLayout& W, const int32_t* id
     const bool fp8 = c.dtype == SP_DTYPE_FP8 && mrows % 256 == 0 && mrows >= kFp8MinRows && W.xq;
     const size_t qH = (size_t)rows * H, qF = (size_t)rows * F;       // bytes per student of the fp8 buffers
     char *xq = fp8 ? w + W.xq + m0 * qH : nullptr, *x1q = fp8 ? w + W.x1q + m0 * qH : nullptr;
-    char* gq = fp8 ? w + W.gq + m0 * qF : nullptr;
+    char *gq = fp8 ? w + W.gq + m0 * qF : nullptr, *attq = fp8 ? w + W.attq + m0 * qH : nullptr;
     SP_MARK(-1);
-    SP_TRY(launch_embed_ln(M, ids, cu, B, T, rows, mrows, k, x, att, s, xq, kActQuantScale));
+    SP_TRY(launch_embed_ln(M, ids, cu, B, T, rows, mrows, k, x, att, s, xq, kActQuantScale, attq));
     SP_MARK(SP_PHASE_EMBED);
     // Last layer on the first-token rows only (see sp_config.last_layer_all_tokens).  Not used by the partial
     // forwards of the tests unless they stop before the last layer.
@@ -369,7 +373,7 @@ static int run_students(const sp_model* M0, const WsLayout& W, const int32_t* id
             SP_TRY(launch_gemm(M, x, H, lo + L.wqkv, lo + L.bqkv, qkv, 3 * H, nullptr, 0, mrows, 3 * H, H, k, EPI_BIAS,
                                sH, s3H, 0, s));
         SP_MARK(SP_PHASE_QKV);
-        SP_TRY(launch_attention(M, qkv, vt, att, cu, B, T, max_seqlen, rows, k, s));
+        SP_TRY(launch_attention(M, qkv, vt, att, cu, B, T, max_seqlen, rows, k, s, attq, kActQuantScale));
         SP_MARK(SP_PHASE_ATTENTION);
         if (split_o > 1) {
             // few tokens: the reduction range is split over workgroups, and the slices are added together with the
@@ -379,8 +383,12 @@ static int run_students(const sp_model* M0, const WsLayout& W, const int32_t* id
             SP_TRY(launch_ln_reduce(M, part, split_o, slice, lo + L.bo, x, x1, rows, mrows, k, lo + L.ln1g, lo + L.ln1b, s));
             SP_MARK(SP_PHASE_LAYERNORM);
         } else {
-            SP_TRY(launch_gemm(M, att, H, lo + L.wo, lo + L.bo, u, H, x, H, mrows, H, H, k, EPI_BIAS_RESIDUAL, sH, sH, sH,
-                               s));
+            if (fp8)
+                SP_TRY(launch_gemm_fp8(M, attq, H, lo + L.wo8, lo + L.so, lo + L.bo, kActQuantScale, u, H, x, H, mrows, H, H,
+                                       k, EPI_BIAS_RESIDUAL, qH, sH, sH, s, nullptr, 0, 0, 0, 1.f));
+            else
+                SP_TRY(launch_gemm(M, att, H, lo + L.wo, lo + L.bo, u, H, x, H, mrows, H, H, k, EPI_BIAS_RESIDUAL, sH, sH,
+                                   sH, s));
             SP_MARK(SP_PHASE_OPROJ);
             SP_TRY(launch_layernorm(M, u, x1, rows, mrows, k, lo + L.ln1g, lo + L.ln1b, s, x1q, kActQuantScale));
             SP_MARK(SP_PHASE_LAYERNORM);
@@ -542,7 +550,7 @@ int sp_workspace_layout(const sp_config* cfg, int32_t total_tokens, int32_t batc
     out->x = W.x; out->qkv = W.qkv; out->vt = W.vt; out->att = W.att; out->x1 = W.x1; out->g = W.g; out->z = W.z;
     out->rows = W.rows; out->act_bytes = W.act_bytes;
     out->first_q = W.cq; out->first_att = W.catt; out->first_rows = W.crows;
-    out->xq = W.xq; out->x1q = W.x1q; out->gq = W.gq;
+    out->xq = W.xq; out->x1q = W.x1q; out->gq = W.gq; out->attq = W.attq;
     return SP_OK;
 }
 

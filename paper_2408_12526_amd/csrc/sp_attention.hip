@@ -16,6 +16,18 @@ constexpr int kKStride = kKeyTile + 1;   // 16-byte units per k-group of the key
 constexpr int kVStride = 68;    // bf16 elements per row of the transposed value tile (136 B)
 constexpr int kOutPitch = kD * 2 + 16;   // bytes per staged output row
 
+// eight bf16 values (one 16-byte chunk of an output row) -> eight e4m3 codes of value * qscale
+__device__ inline uint2 chunk_to_fp8(uint4 c, float qscale)
+{
+    const bf16x8 v = __builtin_bit_cast(bf16x8, c);
+    int lo = 0, hi = 0;
+    lo = __builtin_amdgcn_cvt_pk_fp8_f32((float)v[0] * qscale, (float)v[1] * qscale, lo, false);
+    lo = __builtin_amdgcn_cvt_pk_fp8_f32((float)v[2] * qscale, (float)v[3] * qscale, lo, true);
+    hi = __builtin_amdgcn_cvt_pk_fp8_f32((float)v[4] * qscale, (float)v[5] * qscale, hi, false);
+    hi = __builtin_amdgcn_cvt_pk_fp8_f32((float)v[6] * qscale, (float)v[7] * qscale, hi, true);
+    return uint2{(unsigned)lo, (unsigned)hi};
+}
+
 // -------------------------------------------------------------------------------------
 // bf16 kernel on the matrix cores.  One workgroup = (student, sequence, head, block of 128
 // queries); wave w owns queries q0 + 32w .. + 31.  Per 64-key tile:
@@ -30,7 +42,8 @@ constexpr int kOutPitch = kD * 2 + 16;   // bytes per staged output row
 __global__ __launch_bounds__(256) void attention_bf16_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ vt,
                                                              bf16* __restrict__ att,
                                                              const int32_t* __restrict__ cu, int B, int Tn, int rows,
-                                                             int H, int heads, int max_seqlen, int nqc, int min_len)
+                                                             int H, int heads, int max_seqlen, int nqc, int min_len,
+                                                             unsigned char* __restrict__ attq, float qscale)
 {
     __shared__ uint4 sK[8 * kKStride];             // [d-group of 8][key]
     __shared__ __attribute__((aligned(16))) bf16 sVt[kD * kVStride];   // [d][key]
@@ -176,11 +189,15 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(const bf16* __restr
         __builtin_amdgcn_wave_barrier();
         const int orow = lane >> 3, oc = lane & 7;
         const int qw = q0 + wave * 32;                      // the wave's first query
-        bf16* dst = att + ((size_t)m * rows + t0 + qw) * H + h * kD + oc * 8;
+        const size_t doff = ((size_t)m * rows + t0 + qw) * H + h * kD + oc * 8;
+        bf16* dst = att + doff;
 #pragma unroll
         for (int r0 = 0; r0 < 32; r0 += 8)
-            if (qw + r0 + orow < L)
-                *(uint4*)(dst + (size_t)(r0 + orow) * H) = *(const uint4*)(stg + (r0 + orow) * kOutPitch + oc * 16);
+            if (qw + r0 + orow < L) {
+                const uint4 c = *(const uint4*)(stg + (r0 + orow) * kOutPitch + oc * 16);
+                *(uint4*)(dst + (size_t)(r0 + orow) * H) = c;
+                if (attq) *(uint2*)(attq + doff + (size_t)(r0 + orow) * H) = chunk_to_fp8(c, qscale);   // fp8 copy
+            }
     }
 }
 
@@ -201,7 +218,8 @@ __global__ __launch_bounds__(256, 3) void attention_bf16_short_kernel(const bf16
                                                                       const bf16* __restrict__ vt, bf16* __restrict__ att,
                                                                       const int32_t* __restrict__ cu, int B, int Tn,
                                                                    int rows, int H, int heads, int max_seqlen,
-                                                                   int ngroups, int max_len)
+                                                                   int ngroups, int max_len,
+                                                                   unsigned char* __restrict__ attq, float qscale)
 {
     __shared__ uint4 sK_all[4][8 * kSKStride];
     __shared__ __attribute__((aligned(16))) bf16 sVt_all[4][kD * kSVStride];
@@ -341,11 +359,15 @@ __global__ __launch_bounds__(256, 3) void attention_bf16_short_kernel(const bf16
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             const int orow = lane >> 3, oc = lane & 7;
-            bf16* dst = att + ((size_t)m * rows + t0 + q0) * H + h * kD + oc * 8;
+            const size_t doff = ((size_t)m * rows + t0 + q0) * H + h * kD + oc * 8;
+            bf16* dst = att + doff;
 #pragma unroll
             for (int r0 = 0; r0 < 32; r0 += 8)
-                if (q0 + r0 + orow < L)
-                    *(uint4*)(dst + (size_t)(r0 + orow) * H) = *(const uint4*)(stg + (r0 + orow) * (kSVStride * 4) + oc * 16);
+                if (q0 + r0 + orow < L) {
+                    const uint4 c = *(const uint4*)(stg + (r0 + orow) * (kSVStride * 4) + oc * 16);
+                    *(uint4*)(dst + (size_t)(r0 + orow) * H) = c;
+                    if (attq) *(uint2*)(attq + doff + (size_t)(r0 + orow) * H) = chunk_to_fp8(c, qscale);   // fp8 copy
+                }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();                // the slice is rewritten by the next pass
         }
@@ -645,7 +667,7 @@ __global__ __launch_bounds__(64) void attention_f32_kernel(const float* __restri
 }  // namespace
 
 hipError_t launch_attention(const sp_model* M, const void* qkv, const void* vt, void* att, const int32_t* cu, int B,
-                            int T, int max_seqlen, int rows, int k, hipStream_t s)
+                            int T, int max_seqlen, int rows, int k, hipStream_t s, void* attq, float qscale)
 {
     const sp_config& c = M->cfg;
     if (c.hidden / c.heads != kD) return hipErrorInvalidValue;
@@ -658,14 +680,15 @@ hipError_t launch_attention(const sp_model* M, const void* qkv, const void* vt, 
         const int ngroups = (c.heads + 3) / 4;
         hipLaunchKernelGGL(attention_bf16_short_kernel, dim3((unsigned)((B * ngroups + 7) / 8 * 8), k), dim3(256), 0, s,
                            (const bf16*)qkv, (const bf16*)vt, (bf16*)att, cu, B, T, rows, c.hidden, c.heads, max_seqlen,
-                           ngroups, kShortLen);
+                           ngroups, kShortLen, (unsigned char*)attq, qscale);
         if (max_seqlen > kShortLen) {
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
             const int nqc = (max_seqlen + kQPerWg - 1) / kQPerWg;
             dim3 grid((unsigned)(B * c.heads * nqc), k);
             hipLaunchKernelGGL(attention_bf16_kernel, grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)vt,
-                               (bf16*)att, cu, B, T, rows, c.hidden, c.heads, max_seqlen, nqc, kShortLen);
+                               (bf16*)att, cu, B, T, rows, c.hidden, c.heads, max_seqlen, nqc, kShortLen,
+                               (unsigned char*)attq, qscale);
         }
     } else {
         const int nqc = (max_seqlen + 63) / 64;

@@ -109,7 +109,7 @@ __global__ __launch_bounds__(256) void embed_ln_kernel(const char* arena, size_t
                                                        const int32_t* __restrict__ cu, int B, int Tn, int rows,
                                                        int mrows, int H, int V, int P, float eps, T* __restrict__ x,
                                                        T* __restrict__ att, int rpw, unsigned char* __restrict__ xq,
-                                                       float qscale)
+                                                       float qscale, unsigned char* __restrict__ attq)
 {
     const int m = blockIdx.y, lane = threadIdx.x & 63;
     const int row0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * rpw;
@@ -146,7 +146,10 @@ __global__ __launch_bounds__(256) void embed_ln_kernel(const char* arena, size_t
             T* arow = att + ((size_t)m * rows + row) * H;
             for (int c = lane; c < nch; c += 64) { store8(out + c * 8, zero8); store8(arow + c * 8, zero8); }
             if (xq)
-                for (int c = lane; c < nch; c += 64) *(int2*)(xq + ((size_t)m * rows + row) * H + c * 8) = int2{0, 0};
+                for (int c = lane; c < nch; c += 64) {
+                    *(int2*)(xq + ((size_t)m * rows + row) * H + c * 8) = int2{0, 0};
+                    if (attq) *(int2*)(attq + ((size_t)m * rows + row) * H + c * 8) = int2{0, 0};
+                }
             continue;
         }
         const int id = __builtin_amdgcn_readlane(my_id, r), pos = __builtin_amdgcn_readlane(my_pos, r);
@@ -590,7 +593,7 @@ hipError_t launch_head_classify(const sp_model* M, const void* pooled, int B, in
 }
 
 hipError_t launch_embed_ln(const sp_model* M, const int32_t* ids, const int32_t* cu, int B, int T, int rows, int mrows,
-                           int k, void* x, void* att, hipStream_t s, void* xq, float qscale)
+                           int k, void* x, void* att, hipStream_t s, void* xq, float qscale, void* attq)
 {
     const sp_config& c = M->cfg;
     const ArenaLayout& L = M->L;
@@ -600,7 +603,7 @@ hipError_t launch_embed_ln(const sp_model* M, const int32_t* ids, const int32_t*
 #define SP_EMBED(T, MAXC)                                                                                          \
     hipLaunchKernelGGL((embed_ln_kernel<T, MAXC>), grid, dim3(256), 0, s, M->arena, L.student_stride, L.tok, L.pos, \
                        L.emb_g, L.emb_b, ids, cu, B, T_, rows, mrows, c.hidden, c.vocab, c.max_pos, c.ln_eps, (T*)x, \
-                       (T*)att, rpw, (unsigned char*)xq, qscale)
+                       (T*)att, rpw, (unsigned char*)xq, qscale, (unsigned char*)attq)
     const int T_ = T;
     if (maxc > kMaxChunks) return hipErrorInvalidValue;
     if (bf16_path(c)) {

@@ -12,7 +12,7 @@
 
 namespace sp {
 
-// SP_DTYPE_FP8 is the bf16 path with fp8 copies of three projection matrices: everything that asks "bf16 or fp32
+// SP_DTYPE_FP8 is the bf16 path with fp8 copies of the four projection matrices: everything that asks "bf16 or fp32
 // storage" treats the two alike.
 inline bool bf16_path(const sp_config& c) { return c.dtype != SP_DTYPE_FP32; }
 
@@ -83,9 +83,9 @@ struct ArenaLayout {
     // relative to the start of a layer
     size_t wqkv, bqkv, wo, bo, ln1g, ln1b, w1, b1, w2, b2, ln2g, ln2b;
     size_t wk_io;                  // the key projection once more, [in][out] as in the host blob (folded first-token queries)
-    // SP_DTYPE_FP8 only (0 otherwise), relative to the start of a layer: the fused q|k|v, FFN-up and FFN-down
-    // matrices once more as e4m3 codes, [out][in] bytes, and their per-output-feature scales (fp32)
-    size_t wqkv8, sqkv, w18, s1, w28, s2;
+    // SP_DTYPE_FP8 only (0 otherwise), relative to the start of a layer: the fused q|k|v, attention-output, FFN-up and
+    // FFN-down matrices once more as e4m3 codes, [out][in] bytes, and their per-output-feature scales (fp32)
+    size_t wqkv8, sqkv, wo8, so, w18, s1, w28, s2;
     size_t wp, wp_t, bp, wc, bc;   // wp: [in][out] (column-parallel head kernel); wp_t: [out][in] (GEMM operand)
     size_t student_stride;
 };
@@ -99,7 +99,7 @@ struct WsLayout {
     size_t cqt, cxb;                     // folded queries / weighted mean rows: [K][crows][heads][H]
     size_t part;                         // fp32 partial sums of split reductions: [K][kSplitMax][kSplitRows][H]
     size_t lpart;                        // per-group logit sums when two groups of students run side by side: [2][B][C]
-    size_t xq, x1q, gq;                  // SP_DTYPE_FP8 only: fp8 copies of x and x1 ([K][rows][H] bytes), fp8 g ([K][rows][F])
+    size_t xq, x1q, attq, gq;            // SP_DTYPE_FP8 only: fp8 copies of x, x1 and att ([K][rows][H] bytes), fp8 g ([K][rows][F])
     int rows, crows;
     int act_bytes;
 };
@@ -123,9 +123,11 @@ namespace sp {
 
 // X[m][row][:] = LN(tok[id[row]] + pos[row - cu[seq(row)]]) for row < T; zero rows up to `rows`.
 // Rows T..mrows of x and of att are zeroed.
-// xq (may be null): the rows once more as fp8 (e4m3) codes of value * qscale, [m][rows][H] bytes.
+// xq (may be null): the rows once more as fp8 (e4m3) codes of value * qscale, [m][rows][H] bytes; attq (may be
+// null): fp8 attention output buffer of the same shape, whose rows T..mrows are zeroed like those of att.
 hipError_t launch_embed_ln(const sp_model* M, const int32_t* ids, const int32_t* cu, int B, int T, int rows,
-                           int mrows, int k, void* x, void* att, hipStream_t s, void* xq = nullptr, float qscale = 1.f);
+                           int mrows, int k, void* x, void* att, hipStream_t s, void* xq = nullptr, float qscale = 1.f,
+                           void* attq = nullptr);
 
 // out[m][row][:] = LN(u[m][row][:]; g, b); g/b are byte offsets into the student slab.
 hipError_t launch_layernorm(const sp_model* M, const void* u, void* out, int rows, int mrows, int k, size_t g_off,
@@ -170,8 +172,10 @@ hipError_t launch_ln_reduce(const sp_model* M, const float* partials, int splits
 
 // att[m][t][h*64..] = softmax(q k^T / 8) v inside each sequence; qkv rows are [q | k | v] of width 3H.
 // bf16 path: the values are read from vt[m][H][rows] (transposed) instead of the third slice of qkv.
+// attq (may be null, bf16 path only): the output once more as e4m3 codes of value * qscale, [m][rows][H] bytes.
 hipError_t launch_attention(const sp_model* M, const void* qkv, const void* vt, void* att, const int32_t* cu, int B,
-                            int T, int max_seqlen, int rows, int k, hipStream_t s);
+                            int T, int max_seqlen, int rows, int k, hipStream_t s, void* attq = nullptr,
+                            float qscale = 1.f);
 
 // First-token rows of every sequence: xc[m][b][:] = x[m][cu[b]][:] (b < B), zero rows up to cmrows; the same
 // rows of attc are zeroed.

@@ -31,7 +31,7 @@ class sp_config(C.Structure):
 class sp_ws_layout(C.Structure):
     _fields_ = [(n, C.c_size_t) for n in ("x", "qkv", "vt", "att", "x1", "g", "z")] + [
         ("rows", C.c_int32), ("act_bytes", C.c_int32), ("first_q", C.c_size_t), ("first_att", C.c_size_t),
-        ("first_rows", C.c_int32), ("xq", C.c_size_t), ("x1q", C.c_size_t), ("gq", C.c_size_t)]
+        ("first_rows", C.c_int32), ("xq", C.c_size_t), ("x1q", C.c_size_t), ("gq", C.c_size_t), ("attq", C.c_size_t)]
 
 
 def _load() -> C.CDLL:
@@ -244,7 +244,7 @@ class Students:
             n = k_active * lay.first_rows * H
             t = ws[off:off + n * lay.act_bytes].view(dt).view(k_active, lay.first_rows, H)
             return t[:, :batch].double().cpu().numpy()
-        if name in ("xq", "x1q", "gq"):              # fp8 activations: e4m3 codes of 16 * value, [k][rows][width] bytes
+        if name in ("xq", "x1q", "gq", "attq"):              # fp8 activations: e4m3 codes of 16 * value, [k][rows][width] bytes
             width, off = (F if name == "gq" else H), getattr(lay, name)
             n = k_active * lay.rows * width
             t = ws[off:off + n].view(torch.float8_e4m3fn).view(k_active, lay.rows, width)

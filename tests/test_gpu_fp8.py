@@ -1,7 +1,7 @@
 """Quantised students (SP_DTYPE_FP8): the fp8 projections against the oracle.  Needs an MI355X.
 
 The oracle stays fp64 and consumes the de-quantised weights: every tensor rounded to bf16 as in the bf16 mode, except
-the query/key/value, FFN-up and FFN-down matrices of the layers that run on fp8 operands, which are quantised per
+the query/key/value, attention-output, FFN-up and FFN-down matrices of the layers that run on fp8 operands, which are quantised per
 output feature to e4m3 by the library conversion (torch.float8_e4m3fn) and multiplied back by their scales.  Activation
 quantisation is the HIP path's own rounding, like the bf16 rounding of activations in the bf16 mode.
 
@@ -21,7 +21,7 @@ from paper_2408_12526_amd import synth
 pytestmark = pytest.mark.gpu
 
 FP8_LOGITS_REL = 1e-1
-QUANT = ("Wq", "Wk", "Wv", "W1", "W2")
+QUANT = ("Wq", "Wk", "Wv", "Wo", "W1", "W2")
 
 
 def ocfg(s):
@@ -33,7 +33,7 @@ def rel_err(got, ref):
 
 
 def dequantised_weights(blob, shape, fp8_layers):
-    """bf16-rounded blob, with the three projection families of `fp8_layers` per-output-feature e4m3 instead."""
+    """bf16-rounded blob, with the four projection families of `fp8_layers` per-output-feature e4m3 instead."""
     out = torch.from_numpy(blob).to(torch.bfloat16).to(torch.float32).numpy()
     for m in range(shape.K):
         src, dst = synth.student_views(blob, shape, m), synth.student_views(out, shape, m)
@@ -91,7 +91,7 @@ def test_fp8_projections_stage_by_stage(sp, oracle64):
 
     for layer in range(shape.layers):
         ws = st.sp_forward_partial(d_ids, d_cu, mx, k, layer + 1)
-        got = {n: st.read_activation(ws, n, T, B, k) for n in ("qkv", "att", "x1", "x", "x1q", "gq", "xq")}
+        got = {n: st.read_activation(ws, n, T, B, k) for n in ("qkv", "att", "x1", "x", "x1q", "gq", "xq", "attq")}
         if layer == 0:
             ws0 = st.sp_forward_partial(d_ids, d_cu, mx, k, 0)
             x_in, xq_in = st.read_activation(ws0, "x", T, B, k), st.read_activation(ws0, "xq", T, B, k)
@@ -104,6 +104,11 @@ def test_fp8_projections_stage_by_stage(sp, oracle64):
             bqkv = np.concatenate([v[p + "bq"], v[p + "bk"], v[p + "bv"]])
             e = rel_err(got["qkv"][m], oracle64.linear(xq_in[m], Wqkv, bqkv))
             assert e < tol, f"layer {layer} student {m}: fp8 q|k|v projection, rel err {e:.3e}"
+            check_quantised(got["attq"][m], got["att"][m], f"layer {layer} student {m}: fp8 copy of the attention output")
+            want_x1 = ln_rows(x_in[m] + oracle64.linear(got["attq"][m], v[p + "Wo"], v[p + "bo"]), v[p + "ln1_g"],
+                              v[p + "ln1_b"])
+            e = rel_err(got["x1"][m], want_x1)
+            assert e < tol, f"layer {layer} student {m}: fp8 attention output projection + residual + LayerNorm, rel err {e:.3e}"
             check_quantised(got["x1q"][m], got["x1"][m], f"layer {layer} student {m}: fp8 copy of x1")
             want_g = torch.nn.functional.gelu(torch.from_numpy(oracle64.linear(got["x1q"][m], v[p + "W1"], v[p + "b1"]))).numpy()
             bound = 2.0 ** -4 * np.abs(want_g) + 2e-3 * np.abs(want_g).max()
