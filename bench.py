@@ -101,10 +101,18 @@ def last_first_work(shape, tokens, batch, k):
 def smi_sample():
     """Package power (W) and shader clock (MHz) as amd-smi reports them right now, or None (best effort: the tool may
     be missing or refuse an ordinary user)."""
+    import shutil
     import subprocess
+    # not under a profiler: its preloaded tool initialises the GPU in every child it is inherited by, and the tool
+    # below is a script whose interpreter is reached through further exec hops
+    if any(k.startswith(("ROCPROF", "ROCP_")) for k in os.environ) or "rocprof" in os.environ.get("LD_PRELOAD", ""):
+        return None
+    tool = shutil.which("amd-smi")
+    if not tool:
+        return None
     try:
-        out = subprocess.run(["amd-smi", "metric", "-g", "0", "--power", "--clock", "--json"], capture_output=True,
-                             text=True, timeout=20).stdout
+        out = subprocess.run([sys.executable, tool, "metric", "-g", "0", "--power", "--clock", "--json"],
+                             capture_output=True, text=True, timeout=20).stdout
         d = json.loads(out)
         d = d[0] if isinstance(d, list) else (d.get("gpu_data", [d])[0] if isinstance(d, dict) else d)
         power = d.get("power", {}).get("socket_power", {})
