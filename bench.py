@@ -140,6 +140,40 @@ def sampled_while(fn_busy, seconds):
     return box.get("s")
 
 
+def power_leg(sp, torch, forward_burst):
+    """Package power and shader clock (one amd-smi sample in the middle of each run) under: the matrix-instruction
+    loop on operands in {0, 1}, the same loop on random mantissas (bf16 and fp8), and the burst forward.  Shows which
+    part of the gap to the published matrix-core peak is the package power limit: the loop does nothing but matrix
+    instructions, and its rate follows the clock the limit allows for the data it multiplies."""
+    import threading
+    out = {}
+
+    def with_sample(name, fn, delay):
+        box = {}
+        th = threading.Thread(target=lambda: (time.sleep(delay), box.update(s=smi_sample())))
+        th.start()
+        val = fn()
+        th.join()
+        out[name] = {"result": val, "smi": box.get("s")}
+
+    out["idle"] = {"smi": smi_sample()}
+    for name, kind in (("mfma_loop_bf16_operands_0_or_1", 0), ("mfma_loop_bf16_operands_random", 1),
+                       ("mfma_loop_fp8_operands_0_or_1", 2), ("mfma_loop_fp8_operands_random", 3)):
+        with_sample(name, lambda kind=kind: {"tflops": sp.sp_probe_mfma_rate(kind, 1500)}, 0.8)
+
+    def burst():
+        t0 = time.perf_counter()
+        n = 0
+        while time.perf_counter() - t0 < 2.0:
+            for _ in range(20):
+                forward_burst()
+            torch.cuda.synchronize()
+            n += 20
+        return {"ms_per_step": (time.perf_counter() - t0) / n * 1e3}
+    with_sample("burst_forward_k8", burst, 1.0)
+    return out
+
+
 def first_only_runs(shape, tokens, max_len):
     """Whether sp_forward computes the last layer for the first-token rows only (sp_config.last_layer_all_tokens = 0)."""
     return shape.dtype == "bf16" and tokens >= 1024 and shape.heads % 4 == 0 and shape.heads <= 16 and max_len <= 512
@@ -361,7 +395,7 @@ def main():
                     help="timed calls per (workload, k_active) of the per-config table for calls of >= 4096 tokens "
                          "(after --config-warmup untimed ones); smaller calls are timed 5 x as often")
     ap.add_argument("--config-warmup", type=int, default=100)
-    ap.add_argument("--only", choices=["burst", "latency", "serve", "configs"], default=None,
+    ap.add_argument("--only", choices=["burst", "latency", "serve", "configs", "power"], default=None,
                     help="run one workload only (for profiling a single launch configuration)")
     ap.add_argument("--burst-k", default=None,
                     help="comma-separated k_active values for the burst workload (default: 8,4,2); profiles of one "
@@ -416,6 +450,11 @@ def main():
             st.sp_forward(ids, cu, mx, k, logits, ws)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps
+
+    if args.only == "power":
+        print(json.dumps({"power_and_clock": power_leg(sp, torch, lambda: st4.sp_forward(d_ids4, d_cu4, mx4, 8, logits4, ws4)),
+                          "workload": "c4_burst_b256, k_active 8" + (", single stream" if args.single_stream else "")}))
+        return
 
     burst = {}
     phases = {}
