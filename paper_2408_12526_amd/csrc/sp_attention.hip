@@ -214,12 +214,16 @@ constexpr int kSKStride = kSKey + 1;      // 16-byte units per d-group of the ke
 constexpr int kSVStride = 36;             // bf16 elements per row of the transposed value tile (72 B)
 static_assert(kD * kSVStride * 2 == 32 * (kSVStride * 4) && kSVStride * 4 >= kD * 2 + 16, "the value slice doubles as the 32 x 64 output staging tile");
 
-__global__ __launch_bounds__(256, 3) void attention_bf16_short_kernel(const bf16* __restrict__ qkv,
-                                                                      const bf16* __restrict__ vt, bf16* __restrict__ att,
-                                                                      const int32_t* __restrict__ cu, int B, int Tn,
-                                                                   int rows, int H, int heads, int max_seqlen,
-                                                                   int ngroups, int max_len,
-                                                                   unsigned char* __restrict__ attq, float qscale)
+// QB: blocks of 32 queries a wave carries through one pass over the keys.  Every pass re-reads the sequence's keys and
+// values, and between the passes of a dozen waves per compute unit they do not survive in the L2 (measured: the bytes
+// fetched from beyond the L2 are those of one read of the queries plus one read of keys and values PER PASS), so
+// QB = 2 halves the passes of sequences of more than 32 tokens; it costs the registers of a second set of queries and
+// output accumulators (two waves per SIMD instead of three).
+template <int QB>
+__global__ __launch_bounds__(256, QB == 1 ? 3 : 2) void attention_bf16_short_kernel(
+    const bf16* __restrict__ qkv, const bf16* __restrict__ vt, bf16* __restrict__ att, const int32_t* __restrict__ cu,
+    int B, int Tn, int rows, int H, int heads, int max_seqlen, int ngroups, int max_len,
+    unsigned char* __restrict__ attq, float qscale)
 {
     __shared__ uint4 sK_all[4][8 * kSKStride];
     __shared__ __attribute__((aligned(16))) bf16 sVt_all[4][kD * kSVStride];
@@ -254,21 +258,28 @@ __global__ __launch_bounds__(256, 3) void attention_bf16_short_kernel(const bf16
     const int lead = t0 & 7;
     const bf16* vbase = vt + ((size_t)m * H + h * kD) * rows + (t0 - lead);
 
-    for (int q0 = 0; q0 < L; q0 += 32) {
-        const int q = q0 + j;
-        bf16x8 qf[4];
+    for (int q0 = 0; q0 < L; q0 += 32 * QB) {
+        // query block qb covers queries q0 + 32 qb .. + 31; it is skipped as a whole (wave-uniform) if it lies beyond
+        // the sequence
+        bf16x8 qf[QB][4];
+        f32x16 o[QB][2];
+        float mrun[QB], lrun[QB];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            uint4 t = {0, 0, 0, 0};
-            if (q < L) t = *(const uint4*)(base + (size_t)q * ld + 16 * s + 8 * g);
-            qf[s] = __builtin_bit_cast(bf16x8, t);
+        for (int qb = 0; qb < QB; ++qb) {
+            const int q = q0 + 32 * qb + j;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                uint4 t = {0, 0, 0, 0};
+                if (q < L) t = *(const uint4*)(base + (size_t)q * ld + 16 * s + 8 * g);
+                qf[qb][s] = __builtin_bit_cast(bf16x8, t);
+            }
+#pragma unroll
+            for (int db = 0; db < 2; ++db)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) o[qb][db][e] = 0.f;
+            mrun[qb] = -INFINITY;
+            lrun[qb] = 0.f;
         }
-        f32x16 o[2];
-#pragma unroll
-        for (int db = 0; db < 2; ++db)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) o[db][e] = 0.f;
-        float mrun = -INFINITY, lrun = 0.f;
 
         uint4 kreg[4], vreg[4];
         auto fetch = [&](int kt0) {                  // kt0: first key of the tile relative to the sequence start
@@ -295,57 +306,64 @@ __global__ __launch_bounds__(256, 3) void attention_bf16_short_kernel(const bf16
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
 
-            f32x16 sc;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) sc[e] = 0.f;
+            for (int qb = 0; qb < QB; ++qb) {
+                if (qb > 0 && q0 + 32 * qb >= L) continue;
+                f32x16 sc;
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const uint4 t = sK[(2 * s + g) * kSKStride + j];
-                sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, t), qf[s], sc, 0, 0, 0);
-            }
-            float mx = mrun;
+                for (int e = 0; e < 16; ++e) sc[e] = 0.f;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int key = kt0 + 8 * (v >> 2) + 4 * g + (v & 3);
-                const float sv = key >= 0 && key < L ? sc[v] * sl2 : -INFINITY;
-                sc[v] = sv;
-                mx = fmaxf(mx, sv);
-            }
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float alpha = exp2f(mrun - mx);
-            mrun = mx;
-            float psum = 0.f;
-            bf16x8 pf[2];
+                for (int s = 0; s < 4; ++s) {
+                    const uint4 t = sK[(2 * s + g) * kSKStride + j];
+                    sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, t), qf[qb][s], sc, 0, 0, 0);
+                }
+                float mx = mrun[qb];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const float p = exp2f(sc[v] - mx);
-                psum += p;
-                pf[v >> 3][v & 7] = (bf16)p;
-            }
-            lrun = lrun * alpha + psum;
+                for (int v = 0; v < 16; ++v) {
+                    const int key = kt0 + 8 * (v >> 2) + 4 * g + (v & 3);
+                    const float sv = key >= 0 && key < L ? sc[v] * sl2 : -INFINITY;
+                    sc[v] = sv;
+                    mx = fmaxf(mx, sv);
+                }
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float alpha = exp2f(mrun[qb] - mx);
+                mrun[qb] = mx;
+                float psum = 0.f;
+                bf16x8 pf[2];
 #pragma unroll
-            for (int db = 0; db < 2; ++db)
+                for (int v = 0; v < 16; ++v) {
+                    const float p = exp2f(sc[v] - mx);
+                    psum += p;
+                    pf[v >> 3][v & 7] = (bf16)p;
+                }
+                lrun[qb] = lrun[qb] * alpha + psum;
 #pragma unroll
-                for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
+                for (int db = 0; db < 2; ++db)
 #pragma unroll
-            for (int s2 = 0; s2 < 2; ++s2) {
-                const int kbase = 16 * s2 + 4 * g;
+                    for (int e = 0; e < 16; ++e) o[qb][db][e] *= alpha;
 #pragma unroll
-                for (int db = 0; db < 2; ++db) {
-                    const bf16* vr = sVt + (db * 32 + j) * kSVStride + kbase;
-                    const bf16x4 lo = *(const bf16x4*)vr, hi = *(const bf16x4*)(vr + 8);
-                    const bf16x8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[s2], o[db], 0, 0, 0);
+                for (int s2 = 0; s2 < 2; ++s2) {
+                    const int kbase = 16 * s2 + 4 * g;
+#pragma unroll
+                    for (int db = 0; db < 2; ++db) {
+                        const bf16* vr = sVt + (db * 32 + j) * kSVStride + kbase;
+                        const bf16x4 lo = *(const bf16x4*)vr, hi = *(const bf16x4*)(vr + 8);
+                        const bf16x8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                        o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[s2], o[qb][db], 0, 0, 0);
+                    }
                 }
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();       // the slice is rewritten at the top of the next iteration
         }
-        const float inv = 1.0f / (lrun + __shfl_xor(lrun, 32));
-        // The 32 x 64 output block leaves through this wave's (now idle) value slice, so that a store instruction
+        // A 32 x 64 output block leaves through this wave's (now idle) value slice, so that a store instruction
         // writes eight whole 128-byte rows (eight-byte pieces of 32 rows per instruction are several times slower
         // on the way to memory).
-        {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            const int qs = q0 + 32 * qb;                    // first query of the block
+            if (qb > 0 && qs >= L) continue;
+            const float inv = 1.0f / (lrun[qb] + __shfl_xor(lrun[qb], 32));
             char* stg = (char*)sVt;                         // 32 rows of 144 bytes = the whole slice
 #pragma unroll
             for (int db = 0; db < 2; ++db)
@@ -353,23 +371,23 @@ __global__ __launch_bounds__(256, 3) void attention_bf16_short_kernel(const bf16
                 for (int v4 = 0; v4 < 4; ++v4) {
                     bf16x4 w;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) w[e] = (bf16)(o[db][4 * v4 + e] * inv);
+                    for (int e = 0; e < 4; ++e) w[e] = (bf16)(o[qb][db][4 * v4 + e] * inv);
                     *(bf16x4*)(stg + j * (kSVStride * 4) + (db * 32 + 8 * v4 + 4 * g) * 2) = w;
                 }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             const int orow = lane >> 3, oc = lane & 7;
-            const size_t doff = ((size_t)m * rows + t0 + q0) * H + h * kD + oc * 8;
+            const size_t doff = ((size_t)m * rows + t0 + qs) * H + h * kD + oc * 8;
             bf16* dst = att + doff;
 #pragma unroll
             for (int r0 = 0; r0 < 32; r0 += 8)
-                if (q0 + r0 + orow < L) {
+                if (qs + r0 + orow < L) {
                     const uint4 c = *(const uint4*)(stg + (r0 + orow) * (kSVStride * 4) + oc * 16);
                     *(uint4*)(dst + (size_t)(r0 + orow) * H) = c;
                     if (attq) *(uint2*)(attq + doff + (size_t)(r0 + orow) * H) = chunk_to_fp8(c, qscale);   // fp8 copy
                 }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-            __builtin_amdgcn_wave_barrier();                // the slice is rewritten by the next pass
+            __builtin_amdgcn_wave_barrier();                // the slice is rewritten by the next block / pass
         }
     }
 }
@@ -678,9 +696,16 @@ hipError_t launch_attention(const sp_model* M, const void* qkv, const void* vt, 
         // tile iterations in one wave, a long tail behind the ~5 of a typical one.)
         const int kShortLen = 128;
         const int ngroups = (c.heads + 3) / 4;
-        hipLaunchKernelGGL(attention_bf16_short_kernel, dim3((unsigned)((B * ngroups + 7) / 8 * 8), k), dim3(256), 0, s,
-                           (const bf16*)qkv, (const bf16*)vt, (bf16*)att, cu, B, T, rows, c.hidden, c.heads, max_seqlen,
-                           ngroups, kShortLen, (unsigned char*)attq, qscale);
+        // two query blocks per pass wherever a sequence can have more than one (burst workload: 0.330 -> 0.280 ms for
+        // the attention phase; four blocks, one wave per SIMD: 0.353 ms)
+        if (max_seqlen > 32)
+            hipLaunchKernelGGL(attention_bf16_short_kernel<2>, dim3((unsigned)((B * ngroups + 7) / 8 * 8), k), dim3(256), 0,
+                               s, (const bf16*)qkv, (const bf16*)vt, (bf16*)att, cu, B, T, rows, c.hidden, c.heads,
+                               max_seqlen, ngroups, kShortLen, (unsigned char*)attq, qscale);
+        else
+            hipLaunchKernelGGL(attention_bf16_short_kernel<1>, dim3((unsigned)((B * ngroups + 7) / 8 * 8), k), dim3(256), 0,
+                               s, (const bf16*)qkv, (const bf16*)vt, (bf16*)att, cu, B, T, rows, c.hidden, c.heads,
+                               max_seqlen, ngroups, kShortLen, (unsigned char*)attq, qscale);
         if (max_seqlen > kShortLen) {
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
