@@ -50,12 +50,14 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(const bf16* __restr
     __shared__ __attribute__((aligned(16))) char sOut[4][32 * kOutPitch];   // per wave: 32 output rows
 
     const int m = blockIdx.y;
-    // plain order: the few long sequences are spread over the XCDs by the round-robin placement of workgroups; a
-    // contiguous run of sequences per XCD leaves them unevenly loaded and was measured 1.5x slower
-    int idx = blockIdx.x;
-    const int qc = idx % nqc; idx /= nqc;
-    const int h = idx % heads;
-    const int b = idx / heads;
+    // (sequence, head) pairs go round the XCDs one by one (the few long sequences of a serving batch are spread evenly:
+    // a contiguous run of sequences per XCD left them unevenly loaded and was measured 1.5x slower), but the query
+    // blocks of one pair stay on one XCD (workgroup id mod 8), so that its keys and values are fetched into one L2
+    const int xcd = blockIdx.x & 7, y = blockIdx.x >> 3;
+    const int qc = y % nqc, pair = (y / nqc) * 8 + xcd;
+    if (pair >= B * heads) return;
+    const int h = pair % heads;
+    const int b = pair / heads;
     int t0 = cu[b], t1 = cu[b + 1];
     t0 = t0 < 0 ? 0 : (t0 > Tn - 1 ? Tn - 1 : t0);
     int L = t1 - t0;
@@ -710,7 +712,7 @@ hipError_t launch_attention(const sp_model* M, const void* qkv, const void* vt, 
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
             const int nqc = (max_seqlen + kQPerWg - 1) / kQPerWg;
-            dim3 grid((unsigned)(B * c.heads * nqc), k);
+            dim3 grid((unsigned)((B * c.heads + 7) / 8 * 8 * nqc), k);
             hipLaunchKernelGGL(attention_bf16_kernel, grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)vt,
                                (bf16*)att, cu, B, T, rows, c.hidden, c.heads, max_seqlen, nqc, kShortLen,
                                (unsigned char*)attq, qscale);
