@@ -330,6 +330,14 @@ static int run_students(const sp_model* M0, const WsLayout& W, const int32_t* id
             if (split_d == 1 && (F / 64) % sp == 0 && F / 64 / sp >= 2) split_d = sp;
         }
     }
+    // the same for the first-token rows of the last layer when they are few (a batch of up to 128 sequences)
+    int csplit_o = 1, csplit_d = 1;
+    if (first_only && cmrows <= kSplitRows) {
+        for (int sp = kSplitMax; sp > 1; --sp) {
+            if (csplit_o == 1 && (H / 64) % sp == 0 && H / 64 / sp >= 2) csplit_o = sp;
+            if (csplit_d == 1 && (F / 64) % sp == 0 && F / 64 / sp >= 2) csplit_d = sp;
+        }
+    }
     for (int l = 0; l < stop_layers; ++l) {
         const size_t lo = L.layer0 + (size_t)l * L.layer_stride;
         if (first_only && l == c.layers - 1) {
@@ -347,18 +355,34 @@ static int run_students(const sp_model* M0, const WsLayout& W, const int32_t* id
                                     lo + L.bqkv + (size_t)2 * H * 4, 64, true, catt, (size_t)crows * H, 64, H, cmrows, 64, H,
                                     k, s));
             SP_MARK(SP_PHASE_LAST_FIRST);
-            SP_TRY(launch_gemm(M, catt, H, lo + L.wo, lo + L.bo, cu2, H, cx, H, cmrows, H, H, k, EPI_BIAS_RESIDUAL, cH, cH,
-                               cH, s));
-            SP_MARK(SP_PHASE_LAST_FIRST);
-            SP_TRY(launch_layernorm(M, cu2, cx1, crows, cmrows, k, lo + L.ln1g, lo + L.ln1b, s));
+            if (csplit_o > 1) {
+                // few rows: a 64-row tile walking the whole reduction range is a long serial chain; split it over
+                // workgroups and add the slices together with bias, residual and LayerNorm
+                SP_TRY(launch_gemm_splitk(M, catt, H, lo + L.wo, part, cmrows, H, H, k, csplit_o, cH, slice, s));
+                SP_MARK(SP_PHASE_LAST_FIRST);
+                SP_TRY(launch_ln_reduce(M, part, csplit_o, slice, lo + L.bo, cx, cx1, crows, cmrows, k, lo + L.ln1g,
+                                        lo + L.ln1b, s));
+            } else {
+                SP_TRY(launch_gemm(M, catt, H, lo + L.wo, lo + L.bo, cu2, H, cx, H, cmrows, H, H, k, EPI_BIAS_RESIDUAL, cH,
+                                   cH, cH, s));
+                SP_MARK(SP_PHASE_LAST_FIRST);
+                SP_TRY(launch_layernorm(M, cu2, cx1, crows, cmrows, k, lo + L.ln1g, lo + L.ln1b, s));
+            }
             SP_MARK(SP_PHASE_LAST_FIRST);
             SP_TRY(launch_gemm(M, cx1, H, lo + L.w1, lo + L.b1, cg, F, nullptr, 0, cmrows, F, H, k, EPI_BIAS_GELU, cH, cF, 0,
                                s));
             SP_MARK(SP_PHASE_LAST_FIRST);
-            SP_TRY(launch_gemm(M, cg, F, lo + L.w2, lo + L.b2, cu2, H, cx1, H, cmrows, H, F, k, EPI_BIAS_RESIDUAL, cF, cH,
-                               cH, s));
-            SP_MARK(SP_PHASE_LAST_FIRST);
-            SP_TRY(launch_layernorm(M, cu2, cx, crows, cmrows, k, lo + L.ln2g, lo + L.ln2b, s));
+            if (csplit_d > 1) {
+                SP_TRY(launch_gemm_splitk(M, cg, F, lo + L.w2, part, cmrows, H, F, k, csplit_d, cF, slice, s));
+                SP_MARK(SP_PHASE_LAST_FIRST);
+                SP_TRY(launch_ln_reduce(M, part, csplit_d, slice, lo + L.b2, cx1, cx, crows, cmrows, k, lo + L.ln2g,
+                                        lo + L.ln2b, s));
+            } else {
+                SP_TRY(launch_gemm(M, cg, F, lo + L.w2, lo + L.b2, cu2, H, cx1, H, cmrows, H, F, k, EPI_BIAS_RESIDUAL, cF,
+                                   cH, cH, s));
+                SP_MARK(SP_PHASE_LAST_FIRST);
+                SP_TRY(launch_layernorm(M, cu2, cx, crows, cmrows, k, lo + L.ln2g, lo + L.ln2b, s));
+            }
             SP_MARK(SP_PHASE_LAST_FIRST);
             compact_final = true;
             continue;
