@@ -1,5 +1,7 @@
 // Bandwidth-bound kernels of the student forward: embedding gather + LayerNorm,
 // stand-alone LayerNorm, and the pooled head with the cross-student sum.
+#include <type_traits>
+
 #include "sp_internal.h"
 
 namespace sp {
@@ -54,7 +56,8 @@ __device__ inline void store8_fp8(unsigned char* p, const float (&v)[8], float q
 }
 
 // qout (may be null): the same row once more as fp8 codes of value * qscale, for the fp8 projections
-template <typename T, int MAXC>
+// (Q8 is a template parameter: the plain bf16 / fp32 instantiations carry no trace of the second output)
+template <typename T, int MAXC, bool Q8 = false>
 __device__ inline void ln_row_store(float (&v)[MAXC][8], int nch, int lane, int H, const float (&gg)[MAXC][8],
                                     const float (&bb)[MAXC][8], float eps, T* out, unsigned char* qout = nullptr,
                                     float qscale = 1.f)
@@ -81,7 +84,7 @@ __device__ inline void ln_row_store(float (&v)[MAXC][8], int nch, int lane, int 
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[e] = gg[i][e] * ((v[i][e] - mean) * inv) + bb[i][e];
             store8(out + c * 8, o);
-            if (qout) store8_fp8(qout + c * 8, o, qscale);
+            if (Q8) store8_fp8(qout + c * 8, o, qscale);
         }
     }
 }
@@ -102,7 +105,7 @@ __device__ inline void load_gamma_beta(const float* g, const float* b, int nch, 
 inline int rows_per_wave(int mrows, int k) { return (long)mrows * k >= 32768 ? 8 : 1; }
 
 // One wave per rpw consecutive packed token rows, grid.y = student.
-template <typename T, int MAXC>
+template <typename T, int MAXC, bool Q8>
 __global__ __launch_bounds__(256) void embed_ln_kernel(const char* arena, size_t student_stride, size_t tok_off,
                                                        size_t pos_off, size_t g_off, size_t b_off,
                                                        const int32_t* __restrict__ ids,
@@ -145,7 +148,7 @@ __global__ __launch_bounds__(256) void embed_ln_kernel(const char* arena, size_t
             const float zero8[8] = {0, 0, 0, 0, 0, 0, 0, 0};
             T* arow = att + ((size_t)m * rows + row) * H;
             for (int c = lane; c < nch; c += 64) { store8(out + c * 8, zero8); store8(arow + c * 8, zero8); }
-            if (xq)
+            if (Q8)
                 for (int c = lane; c < nch; c += 64) {
                     *(int2*)(xq + ((size_t)m * rows + row) * H + c * 8) = int2{0, 0};
                     if (attq) *(int2*)(attq + ((size_t)m * rows + row) * H + c * 8) = int2{0, 0};
@@ -167,11 +170,11 @@ __global__ __launch_bounds__(256) void embed_ln_kernel(const char* arena, size_t
                 for (int e = 0; e < 8; ++e) v[i][e] = a[e] + p8[e];
             }
         }
-        ln_row_store<T, MAXC>(v, nch, lane, H, gg, bb, eps, out, xq ? xq + ((size_t)m * rows + row) * H : nullptr, qscale);
+        ln_row_store<T, MAXC, Q8>(v, nch, lane, H, gg, bb, eps, out, Q8 ? xq + ((size_t)m * rows + row) * H : nullptr, qscale);
     }
 }
 
-template <typename T, int MAXC>
+template <typename T, int MAXC, bool Q8>
 __global__ __launch_bounds__(256) void layernorm_kernel(const char* arena, size_t student_stride, size_t g_off,
                                                         size_t b_off, const T* __restrict__ u, T* __restrict__ out,
                                                         int rows, int mrows, int H, float eps, int rpw,
@@ -195,8 +198,8 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const char* arena, size_
             const int c = lane + 64 * i;
             if (c < nch) load8(in + c * 8, v[i]);
         }
-        ln_row_store<T, MAXC>(v, nch, lane, H, gg, bb, eps, out + ((size_t)m * rows + row) * H,
-                              outq ? outq + ((size_t)m * rows + row) * H : nullptr, qscale);
+        ln_row_store<T, MAXC, Q8>(v, nch, lane, H, gg, bb, eps, out + ((size_t)m * rows + row) * H,
+                                  Q8 ? outq + ((size_t)m * rows + row) * H : nullptr, qscale);
     }
 }
 
@@ -600,10 +603,15 @@ hipError_t launch_embed_ln(const sp_model* M, const int32_t* ids, const int32_t*
     const int rpw = rows_per_wave(mrows, k);
     dim3 grid((mrows + 4 * rpw - 1) / (4 * rpw), k);
     const int maxc = (c.hidden / 8 + 63) / 64;              // 8-element chunks per lane
-#define SP_EMBED(T, MAXC)                                                                                          \
-    hipLaunchKernelGGL((embed_ln_kernel<T, MAXC>), grid, dim3(256), 0, s, M->arena, L.student_stride, L.tok, L.pos, \
+#define SP_EMBED(T, MAXC) do {                                                                                     \
+    if (xq && std::is_same<T, bf16>::value)                                                                        \
+        hipLaunchKernelGGL((embed_ln_kernel<bf16, MAXC, true>), grid, dim3(256), 0, s, M->arena, L.student_stride, L.tok, \
+                           L.pos, L.emb_g, L.emb_b, ids, cu, B, T_, rows, mrows, c.hidden, c.vocab, c.max_pos, c.ln_eps,  \
+                           (bf16*)x, (bf16*)att, rpw, (unsigned char*)xq, qscale, (unsigned char*)attq);               \
+    else                                                                                                           \
+    hipLaunchKernelGGL((embed_ln_kernel<T, MAXC, false>), grid, dim3(256), 0, s, M->arena, L.student_stride, L.tok, L.pos, \
                        L.emb_g, L.emb_b, ids, cu, B, T_, rows, mrows, c.hidden, c.vocab, c.max_pos, c.ln_eps, (T*)x, \
-                       (T*)att, rpw, (unsigned char*)xq, qscale, (unsigned char*)attq)
+                       (T*)att, rpw, (unsigned char*)xq, qscale, (unsigned char*)attq); } while (0)
     const int T_ = T;
     if (maxc > kMaxChunks) return hipErrorInvalidValue;
     if (bf16_path(c)) {
@@ -623,9 +631,14 @@ hipError_t launch_layernorm(const sp_model* M, const void* u, void* out, int row
     dim3 grid((mrows + 4 * rpw - 1) / (4 * rpw), k);
     const int maxc = (c.hidden / 8 + 63) / 64;              // 8-element chunks per lane
     if (maxc > kMaxChunks) return hipErrorInvalidValue;
-#define SP_LN(T, MAXC)                                                                                              \
-    hipLaunchKernelGGL((layernorm_kernel<T, MAXC>), grid, dim3(256), 0, s, M->arena, M->L.student_stride, g_off,    \
-                       b_off, (const T*)u, (T*)out, rows, mrows, c.hidden, c.ln_eps, rpw, (unsigned char*)outq, qscale)
+#define SP_LN(T, MAXC) do {                                                                                         \
+    if (outq && std::is_same<T, bf16>::value)                                                                       \
+        hipLaunchKernelGGL((layernorm_kernel<bf16, MAXC, true>), grid, dim3(256), 0, s, M->arena, M->L.student_stride, \
+                           g_off, b_off, (const bf16*)u, (bf16*)out, rows, mrows, c.hidden, c.ln_eps, rpw,         \
+                           (unsigned char*)outq, qscale);                                                          \
+    else                                                                                                            \
+    hipLaunchKernelGGL((layernorm_kernel<T, MAXC, false>), grid, dim3(256), 0, s, M->arena, M->L.student_stride, g_off,    \
+                       b_off, (const T*)u, (T*)out, rows, mrows, c.hidden, c.ln_eps, rpw, (unsigned char*)outq, qscale); } while (0)
     if (bf16_path(c)) {
         if (maxc <= 1) SP_LN(bf16, 1); else if (maxc == 2) SP_LN(bf16, 2); else SP_LN(bf16, 4);
     } else {
