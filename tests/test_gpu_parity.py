@@ -633,3 +633,55 @@ def test_two_threads_issue_large_calls_on_one_model(sp):
         t.join()
     assert not errors, errors
     assert results == {0: 0, 1: 0}, results
+
+
+@pytest.mark.parametrize("total", [70, 1500, 2600])
+def test_widest_head_and_odd_student_count(sp, oracle64, total):
+    """The limits of the head: 16 classes (the most the kernels take), five students with k_active 1, 3 and 5 (odd
+    counts split unevenly over the two student groups of a large call), at a small, a medium and a large call size."""
+    shape = synth.StudentShape(K=5, layers=2, hidden=256, heads=4, ffn=512, vocab=400, max_pos=256, classes=16,
+                               dtype="bf16")
+    rng = np.random.default_rng(3000 + total)
+    lengths = []
+    left = total
+    while left > 0:
+        n = int(min(left, rng.integers(1, 200)))
+        lengths.append(n)
+        left -= n
+    lengths = np.array(lengths, dtype=np.int32)
+    ids = synth.make_ids(rng, total, shape.vocab)
+    blob = synth.make_weights(rng, shape, std=0.03, ln_random=True, qk_std=float(np.sqrt(1.5 / shape.hidden)))
+    st = sp.Students(sp.config_from_shape(shape), blob)
+    d_ids, d_cu, cu = gpu_inputs(lengths, ids, sp)
+    _, terms = oracle64.forward(ocfg(shape), oracle_weights(blob, shape), ids, cu, shape.K, want_terms=True)
+    for k in (1, 3, 5):
+        got = st.sp_forward(d_ids, d_cu, int(lengths.max()), k).cpu().numpy().astype(np.float64)
+        assert got.shape == (len(lengths), 16)
+        check_logits(got, terms[:k].sum(0), shape, f"{total} tokens, 16 classes, k_active={k}")
+    st.close()
+
+
+def test_degenerate_calls_are_refused(sp):
+    """Empty inputs and inconsistent sizes never reach a kernel: an empty batch, fewer tokens than sequences, a
+    max_seqlen of 0 or one that cannot hold the tokens."""
+    w = synth.WORKLOADS[1]
+    batch, blob = synth.make_workload(w)
+    st = sp.Students(sp.config_from_shape(w.shape), blob)
+    lib = sp.raw_lib()
+    ids = torch.zeros(8, dtype=torch.int32, device="cuda")
+    cu = torch.tensor([0, 3, 8], dtype=torch.int32, device="cuda")
+    ws = st.workspace(8, 2)
+    out = torch.zeros(2, w.shape.classes, dtype=torch.float32, device="cuda")
+
+    def call(batch_n, total, max_seqlen, k=1):
+        return lib.sp_forward(st.handle, ids.data_ptr(), cu.data_ptr(), batch_n, total, max_seqlen, k, ws.data_ptr(),
+                              ws.numel(), out.data_ptr(), None)
+    assert call(2, 8, 5) == 0
+    assert call(0, 0, 5) == -2            # empty batch
+    assert call(0, 8, 5) == -2
+    assert call(2, 1, 5) == -2            # fewer tokens than sequences: some sequence would be empty
+    assert call(2, 8, 0) == -2
+    assert call(2, 8, 3) == -2            # two sequences of at most three tokens cannot hold eight
+    assert call(2, 8, w.shape.max_pos + 1) == -2
+    torch.cuda.synchronize()
+    st.close()
