@@ -3,6 +3,9 @@
 // accumulate) with both operands staged through LDS; the fp32 kernel is a plain FMA tile
 // kernel used by the fp32 path.
 #include <atomic>
+#ifndef SP_NS64
+#define SP_NS64 3
+#endif
 #include <type_traits>
 
 #include "sp_internal.h"
@@ -44,7 +47,11 @@ __device__ inline float gelu_erf(float u) { return 0.5f * u * (1.0f + erff(u * 0
 // -------------------------------------------------------------------------------------
 template <int BM, int BN>
 struct GemmTile {
-    static constexpr int BK = 64, NS = 2, STEPS = 4, LSPREAD = 2;
+    static constexpr int BK = 64, STEPS = 4, LSPREAD = 2;
+    // ring depth: three stages for the 64 x 64 tile (measured, 64 rows x 8 students: FFN down, depth 3072, 26.4 -> 17.5 us;
+    // FFN up 11.2 -> 10.2 us; four stages no better; one student: no change, a lone workgroup per compute unit is
+    // bound by that unit's load path at about 28 B per cycle either way), two for the 128 x 128 tile
+    static constexpr int NS = BM == 64 ? SP_NS64 : 2;
     static constexpr int WTM = BM / 2, WTN = BN / 2;        // wave tile
     // The 256 x 256 tile keeps a ring of five operand tiles (256 rows x 64 reduction elements, 32 KB each: the whole
     // LDS) instead of two stages of an activation and a weight tile; the smaller tiles use the two-stage ring.
@@ -53,7 +60,7 @@ struct GemmTile {
     // epilogue staging: wave w keeps rows [h * WTM / 2, (h + 1) * WTM / 2) of its sub-tile, WTN * 2 bytes each, in
     // one half of the staging area (= one stage of the two-stage ring, two slots of the five-slot ring)
     static constexpr size_t half_bytes = (size_t)(BM + BN) * 8 * 16;
-    static_assert(NS == 2 && (size_t)4 * (WTM / 2) * WTN * 2 <= half_bytes, "staging halves must fit the ring stages");
+    static_assert(NS >= 2 && (size_t)4 * (WTM / 2) * WTN * 2 <= half_bytes, "staging halves must fit the ring stages");
     static constexpr size_t smem_bytes = ring_bytes;
 };
 
@@ -133,13 +140,15 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
     const int rr = lane / CPR, cc = lane % CPR;
     const size_t row0 = (size_t)m0 + wm * WTM;
     const int col0 = n0 + wn * WTN;
-    const int ha = (Kd / BK) & 1;                           // the ring stage that is idle during the last k-tile
+    // staging half 0 sits in a ring stage that is idle during the last k-tile (the one after it in ring order), half 1
+    // in the next one (for a two-stage ring: the last k-tile's own stage, free once the loop is over)
+    const int ha = (Kd / BK) % NS, hb1 = (Kd / BK + 1) % NS;
     // five-slot ring: the last k-tile sits in slots sl, sl + 1 (mod 5).  Staging half 0 is a pair of adjacent slots
     // among the other three (idle during the last k-tile), half 1 a pair among the rest (free once the loop is over).
     const int sl = (2 * (Kd / BK - 1)) % 5;
     const int hs0 = sl == 0 ? 2 : (sl == 1 ? 3 : (sl == 4 ? 1 : 0)), hs1 = sl <= 1 ? 0 : (sl == 4 ? 3 : 2);
     auto half_ptr = [&](int h) {
-        const size_t hb = G::RING5 ? (size_t)(h ? hs1 : hs0) * (256 * 8 * 16) : (size_t)(h ^ ha) * G::half_bytes;
+        const size_t hb = G::RING5 ? (size_t)(h ? hs1 : hs0) * (256 * 8 * 16) : (size_t)(h ? hb1 : ha) * G::half_bytes;
         return (char*)smem + hb + (size_t)wave * HR * ROWB;
     };
     auto swz = [](int r, int chunk) { return chunk ^ ((r >> KSH) & (CPR - 1)); };
