@@ -180,3 +180,23 @@ def test_fp8_burst_workload_part(sp, oracle64):
         print(f"fp8 burst k_active={k}: rel err {e:.3e}", flush=True)
         assert e <= FP8_LOGITS_REL
     st.close()
+
+
+def test_fp8_large_width(sp, oracle64):
+    """Quantised students at the large width (hidden 1024, 16 heads, FFN 4096: reduction depths 1024 and 4096, four and
+    sixteen 256-wide feature tiles), sequences of up to 300 tokens, every sequence against the oracle."""
+    shape = synth.StudentShape(K=2, layers=2, hidden=1024, heads=16, ffn=4096, vocab=500, max_pos=320, classes=2,
+                               dtype="fp8")
+    rng = np.random.default_rng(64)
+    lengths = rng.integers(30, 301, size=14).astype(np.int32)
+    assert 2048 <= lengths.sum()
+    ids = synth.make_ids(rng, int(lengths.sum()), shape.vocab)
+    blob = synth.make_weights(rng, shape, std=0.02, ln_random=True, qk_std=float(np.sqrt(1.5 / shape.hidden)))
+    cu = sp.sp_pack(lengths)
+    st = sp.Students(sp.config_from_shape(shape), blob)
+    got = st.sp_forward(torch.from_numpy(ids).cuda(), torch.from_numpy(cu).cuda(), int(lengths.max()), shape.K)
+    want = oracle64.forward(ocfg(shape), dequantised_weights(blob, shape, range(shape.layers - 1)), ids, cu, shape.K)
+    e = rel_err(got.cpu().numpy().astype(np.float64), want)
+    print(f"fp8 hidden 1024: rel err {e:.3e}", flush=True)
+    assert e <= FP8_LOGITS_REL
+    st.close()
