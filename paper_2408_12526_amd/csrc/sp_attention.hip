@@ -15,6 +15,8 @@ constexpr int kKeyTile = 64;    // keys staged in LDS per step
 constexpr int kKStride = kKeyTile + 1;   // 16-byte units per k-group of the key tile
 constexpr int kVStride = 68;    // bf16 elements per row of the transposed value tile (136 B)
 constexpr int kOutPitch = kD * 2 + 16;   // bytes per staged output row
+constexpr int kLongKBytes = 8 * kKStride * 16, kLongVBytes = kD * kVStride * 2;
+constexpr int kLongLdsBytes = kLongKBytes + kLongVBytes + 4 * 32 * kOutPitch;
 
 // eight bf16 values (one 16-byte chunk of an output row) -> eight e4m3 codes of value * qscale
 __device__ inline uint2 chunk_to_fp8(uint4 c, float qscale)
@@ -39,21 +41,21 @@ __device__ inline uint2 chunk_to_fp8(uint4 c, float qscale)
 //                     probabilities, which already sit in the B-operand register layout
 //                     once the reduction slots of V^T are enumerated in the same key order)
 // -------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void attention_bf16_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ vt,
-                                                             bf16* __restrict__ att,
-                                                             const int32_t* __restrict__ cu, int B, int Tn, int rows,
-                                                             int H, int heads, int max_seqlen, int nqc, int min_len,
-                                                             unsigned char* __restrict__ attq, float qscale)
+__device__ __forceinline__ void attention_long_body(char* lds, int bid, const bf16* __restrict__ qkv,
+                                                    const bf16* __restrict__ vt, bf16* __restrict__ att,
+                                                    const int32_t* __restrict__ cu, int B, int Tn, int rows, int H,
+                                                    int heads, int max_seqlen, int nqc, int min_len,
+                                                    unsigned char* __restrict__ attq, float qscale)
 {
-    __shared__ uint4 sK[8 * kKStride];             // [d-group of 8][key]
-    __shared__ __attribute__((aligned(16))) bf16 sVt[kD * kVStride];   // [d][key]
-    __shared__ __attribute__((aligned(16))) char sOut[4][32 * kOutPitch];   // per wave: 32 output rows
+    uint4* sK = (uint4*)lds;                                          // [d-group of 8][key], 8 * kKStride units
+    bf16* sVt = (bf16*)(lds + kLongKBytes);                           // [d][key], kD rows of kVStride
+    char* sOut0 = lds + kLongKBytes + kLongVBytes;                    // per wave: 32 output rows of kOutPitch bytes
 
     const int m = blockIdx.y;
     // (sequence, head) pairs go round the XCDs one by one (the few long sequences of a serving batch are spread evenly:
     // a contiguous run of sequences per XCD left them unevenly loaded and was measured 1.5x slower), but the query
     // blocks of one pair stay on one XCD (workgroup id mod 8), so that its keys and values are fetched into one L2
-    const int xcd = blockIdx.x & 7, y = blockIdx.x >> 3;
+    const int xcd = bid & 7, y = bid >> 3;
     const int qc = y % nqc, pair = (y / nqc) * 8 + xcd;
     if (pair >= B * heads) return;
     const int h = pair % heads;
@@ -96,20 +98,30 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(const bf16* __restr
     const int lead = t0 & 7;
     const bf16* vbase = vt + ((size_t)m * H + h * kD) * rows + (t0 - lead);
     const int lrow = tid >> 3, lc = tid & 7;
-    for (int kt0 = -lead; kt0 < L; kt0 += kKeyTile) {
-        // stage the key tile (rows = keys) and the value tile (rows = head dimensions); what lies beyond the
-        // sequence is zero-filled
+    // the key tile (rows = keys) and the value tile (rows = head dimensions) travel through registers: the next
+    // tile is requested before the current one is multiplied; what lies beyond the sequence is zero-filled
+    uint4 kreg[2], vreg[2];
+    auto fetch = [&](int kt0) {
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
             const int r = lrow + 32 * p;                      // key of the tile, or head dimension
-            uint4 kk = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
-            if (kt0 + r >= 0 && kt0 + r < L) kk = *(const uint4*)(base + (ptrdiff_t)(kt0 + r) * (ptrdiff_t)ld + H + lc * 8);
-            if (kt0 + lc * 8 < L) vv = *(const uint4*)(vbase + (size_t)r * rows + (kt0 + lead) + lc * 8);
-            sK[lc * kKStride + r] = kk;
-            uint2* vd = (uint2*)(sVt + r * kVStride + lc * 8);
-            vd[0] = uint2{vv.x, vv.y};
-            vd[1] = uint2{vv.z, vv.w};
+            kreg[p] = uint4{0, 0, 0, 0};
+            vreg[p] = uint4{0, 0, 0, 0};
+            if (kt0 + r >= 0 && kt0 + r < L) kreg[p] = *(const uint4*)(base + (ptrdiff_t)(kt0 + r) * (ptrdiff_t)ld + H + lc * 8);
+            if (kt0 + lc * 8 < L) vreg[p] = *(const uint4*)(vbase + (size_t)r * rows + (kt0 + lead) + lc * 8);
         }
+    };
+    fetch(-lead);
+    for (int kt0 = -lead; kt0 < L; kt0 += kKeyTile) {
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const int r = lrow + 32 * p;
+            sK[lc * kKStride + r] = kreg[p];
+            uint2* vd = (uint2*)(sVt + r * kVStride + lc * 8);
+            vd[0] = uint2{vreg[p].x, vreg[p].y};
+            vd[1] = uint2{vreg[p].z, vreg[p].w};
+        }
+        if (kt0 + kKeyTile < L) fetch(kt0 + kKeyTile);
         __syncthreads();
 
         if (wave_active) {
@@ -177,7 +189,7 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(const bf16* __restr
         const float lsum = lrun + __shfl_xor(lrun, 32);
         const float inv = 1.0f / lsum;
         // the wave's 32 x 64 output block leaves through a private LDS tile as whole 128-byte rows
-        char* stg = sOut[wave];
+        char* stg = sOut0 + wave * (32 * kOutPitch);
 #pragma unroll
         for (int db = 0; db < 2; ++db)
 #pragma unroll
@@ -221,21 +233,22 @@ static_assert(kD * kSVStride * 2 == 32 * (kSVStride * 4) && kSVStride * 4 >= kD 
 // fetched from beyond the L2 are those of one read of the queries plus one read of keys and values PER PASS), so
 // QB = 2 halves the passes of sequences of more than 32 tokens; it costs the registers of a second set of queries and
 // output accumulators (two waves per SIMD instead of three).
-template <int QB>
-__global__ __launch_bounds__(256, QB == 1 ? 3 : 2) void attention_bf16_short_kernel(
-    const bf16* __restrict__ qkv, const bf16* __restrict__ vt, bf16* __restrict__ att, const int32_t* __restrict__ cu,
-    int B, int Tn, int rows, int H, int heads, int max_seqlen, int ngroups, int max_len,
-    unsigned char* __restrict__ attq, float qscale)
-{
-    __shared__ uint4 sK_all[4][8 * kSKStride];
-    __shared__ __attribute__((aligned(16))) bf16 sVt_all[4][kD * kSVStride];
+constexpr int kShortKBytes = 8 * kSKStride * 16, kShortVBytes = kD * kSVStride * 2;   // per wave
+constexpr int kShortLdsBytes = 4 * (kShortKBytes + kShortVBytes);
 
+template <int QB>
+__device__ __forceinline__ void attention_short_body(char* lds, int bid, const bf16* __restrict__ qkv,
+                                                     const bf16* __restrict__ vt, bf16* __restrict__ att,
+                                                     const int32_t* __restrict__ cu, int B, int Tn, int rows, int H,
+                                                     int heads, int max_seqlen, int ngroups, int max_len,
+                                                     unsigned char* __restrict__ attq, float qscale)
+{
     const int m = blockIdx.y;
     // XCD-aware order (workgroup id mod 8 selects the XCD): each XCD takes a contiguous run of sequences, so that
     // the lines of the token-contiguous value rows which neighbouring sequences share are fetched into one L2
     const int total = B * ngroups, chunk = (total + 7) >> 3;
-    const int lin = (int)(blockIdx.x & 7) * chunk + (int)(blockIdx.x >> 3);
-    if ((int)(blockIdx.x >> 3) >= chunk || lin >= total) return;
+    const int lin = (bid & 7) * chunk + (bid >> 3);
+    if ((bid >> 3) >= chunk || lin >= total) return;
     const int b = lin / ngroups, hg = lin % ngroups;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int h = hg * 4 + wave;
@@ -246,8 +259,8 @@ __global__ __launch_bounds__(256, QB == 1 ? 3 : 2) void attention_bf16_short_ker
     L = L > max_seqlen ? max_seqlen : L;
     L = L > Tn - t0 ? Tn - t0 : L;
     if (L > max_len || h >= heads) return;         // long sequences belong to the cooperative kernel
-    uint4* sK = sK_all[wave];
-    bf16* sVt = sVt_all[wave];
+    uint4* sK = (uint4*)(lds + wave * kShortKBytes);
+    bf16* sVt = (bf16*)(lds + 4 * kShortKBytes + wave * kShortVBytes);
 
     const int j = lane & 31, g = lane >> 5;
     const size_t ld = (size_t)3 * H;
@@ -392,6 +405,38 @@ __global__ __launch_bounds__(256, QB == 1 ? 3 : 2) void attention_bf16_short_ker
             __builtin_amdgcn_wave_barrier();                // the slice is rewritten by the next block / pass
         }
     }
+}
+
+template <int QB>
+__global__ __launch_bounds__(256, QB == 1 ? 3 : 2) void attention_bf16_short_kernel(
+    const bf16* __restrict__ qkv, const bf16* __restrict__ vt, bf16* __restrict__ att, const int32_t* __restrict__ cu,
+    int B, int Tn, int rows, int H, int heads, int max_seqlen, int ngroups, int max_len,
+    unsigned char* __restrict__ attq, float qscale)
+{
+    __shared__ __attribute__((aligned(16))) char lds[kShortLdsBytes];
+    attention_short_body<QB>(lds, (int)blockIdx.x, qkv, vt, att, cu, B, Tn, rows, H, heads, max_seqlen, ngroups, max_len,
+                             attq, qscale);
+}
+
+// Batches with sequences on both sides of the split: one launch.  The first nlong workgroup ids (a multiple of 8, so
+// the id-to-XCD relation of both bodies is kept) are the cooperative kernel's (sequence, head, query block) items,
+// most of which leave at once; the rest are the per-wave kernel's.  The few long items start first and run beside
+// the many short ones instead of in a launch of their own that cannot fill the chip.
+__global__ __launch_bounds__(256, 2) void attention_bf16_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ vt,
+                                                                bf16* __restrict__ att, const int32_t* __restrict__ cu,
+                                                                int B, int Tn, int rows, int H, int heads,
+                                                                int max_seqlen, int nqc, int ngroups, int split_len,
+                                                                int nlong, unsigned char* __restrict__ attq,
+                                                                float qscale)
+{
+    constexpr int kBytes = kLongLdsBytes > kShortLdsBytes ? kLongLdsBytes : kShortLdsBytes;
+    __shared__ __attribute__((aligned(16))) char lds[kBytes];
+    const int bid = (int)blockIdx.x;
+    if (bid < nlong)
+        attention_long_body(lds, bid, qkv, vt, att, cu, B, Tn, rows, H, heads, max_seqlen, nqc, split_len, attq, qscale);
+    else
+        attention_short_body<2>(lds, bid - nlong, qkv, vt, att, cu, B, Tn, rows, H, heads, max_seqlen, ngroups,
+                                split_len, attq, qscale);
 }
 
 // -------------------------------------------------------------------------------------
@@ -698,24 +743,23 @@ hipError_t launch_attention(const sp_model* M, const void* qkv, const void* vt, 
         // tile iterations in one wave, a long tail behind the ~5 of a typical one.)
         const int kShortLen = 128;
         const int ngroups = (c.heads + 3) / 4;
-        // two query blocks per pass wherever a sequence can have more than one (burst workload: 0.330 -> 0.280 ms for
-        // the attention phase; four blocks, one wave per SIMD: 0.353 ms)
-        if (max_seqlen > 32)
-            hipLaunchKernelGGL(attention_bf16_short_kernel<2>, dim3((unsigned)((B * ngroups + 7) / 8 * 8), k), dim3(256), 0,
-                               s, (const bf16*)qkv, (const bf16*)vt, (bf16*)att, cu, B, T, rows, c.hidden, c.heads,
-                               max_seqlen, ngroups, kShortLen, (unsigned char*)attq, qscale);
-        else
-            hipLaunchKernelGGL(attention_bf16_short_kernel<1>, dim3((unsigned)((B * ngroups + 7) / 8 * 8), k), dim3(256), 0,
-                               s, (const bf16*)qkv, (const bf16*)vt, (bf16*)att, cu, B, T, rows, c.hidden, c.heads,
-                               max_seqlen, ngroups, kShortLen, (unsigned char*)attq, qscale);
+        const unsigned nshort = (unsigned)((B * ngroups + 7) / 8 * 8);
         if (max_seqlen > kShortLen) {
-            hipError_t e = hipGetLastError();
-            if (e != hipSuccess) return e;
             const int nqc = (max_seqlen + kQPerWg - 1) / kQPerWg;
-            dim3 grid((unsigned)((B * c.heads + 7) / 8 * 8 * nqc), k);
-            hipLaunchKernelGGL(attention_bf16_kernel, grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)vt,
-                               (bf16*)att, cu, B, T, rows, c.hidden, c.heads, max_seqlen, nqc, kShortLen,
-                               (unsigned char*)attq, qscale);
+            const unsigned nlong = (unsigned)((B * c.heads + 7) / 8 * 8 * nqc);
+            hipLaunchKernelGGL(attention_bf16_kernel, dim3(nlong + nshort, k), dim3(256), 0, s, (const bf16*)qkv,
+                               (const bf16*)vt, (bf16*)att, cu, B, T, rows, c.hidden, c.heads, max_seqlen, nqc, ngroups,
+                               kShortLen, (int)nlong, (unsigned char*)attq, qscale);
+        } else if (max_seqlen > 32) {
+            // two query blocks per pass wherever a sequence can have more than one (burst workload: 0.330 -> 0.280 ms
+            // for the attention phase; four blocks, one wave per SIMD: 0.353 ms)
+            hipLaunchKernelGGL(attention_bf16_short_kernel<2>, dim3(nshort, k), dim3(256), 0, s, (const bf16*)qkv,
+                               (const bf16*)vt, (bf16*)att, cu, B, T, rows, c.hidden, c.heads, max_seqlen, ngroups,
+                               kShortLen, (unsigned char*)attq, qscale);
+        } else {
+            hipLaunchKernelGGL(attention_bf16_short_kernel<1>, dim3(nshort, k), dim3(256), 0, s, (const bf16*)qkv,
+                               (const bf16*)vt, (bf16*)att, cu, B, T, rows, c.hidden, c.heads, max_seqlen, ngroups,
+                               kShortLen, (unsigned char*)attq, qscale);
         }
     } else {
         const int nqc = (max_seqlen + 63) / 64;

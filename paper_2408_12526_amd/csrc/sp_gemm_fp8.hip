@@ -11,11 +11,16 @@
 // chunks of a row (chunks 4 s + 2 g and 4 s + 2 g + 1 in k-step s for lane half g; both operands use the same map,
 // so the order inside the reduction is immaterial).
 //
-// Two stages of 64 KB.  One iteration (k-tile kt, first k-step's fragments already in registers):
-//   read the second k-step's fragments; 16 matrix instructions of the first k-step;
-//   wait for this wave's share of k-tile kt + 1, barrier (stage of kt is free, kt + 1 is visible);
-//   read the first k-step's fragments of kt + 1; 16 matrix instructions of the second k-step, with the 16
-//   wave-loads of k-tile kt + 2 (into the freed stage) issued one per instruction.
+// Five slots of one operand tile each (256 rows x 128 B = 32 KB; the whole LDS), as in the bf16 kernel of this tile
+// size: k-tile t keeps its activations in slot 2 t mod 5 and its weights in slot (2 t + 1) mod 5.  A k-tile is two
+// k-steps of sixteen matrix instructions; each instruction pair carries one wave-load and one fragment read (the
+// fragments of the next k-step go into the second register set), so that the load path sees one request per 128
+// matrix-core cycles all the time and a load has more than a thousand cycles to land:
+//   k-step 0 of k-tile j: activations of k-tile j + 2 -> slot of the weights of k-tile j - 1 (free since the barrier
+//                         of k-tile j - 1); fragments of k-step 1;
+//   barrier (every wave holds its last fragments of k-tile j; k-tile j + 1 has landed and is visible to all);
+//   k-step 1:             weights of k-tile j + 2 -> slot of the activations of k-tile j; fragments of k-step 0 of
+//                         k-tile j + 1.
 #include <atomic>
 #include <type_traits>
 
@@ -26,10 +31,12 @@ namespace sp {
 namespace {
 
 typedef int v8i __attribute__((ext_vector_type(8)));
+typedef int v4i __attribute__((ext_vector_type(4)));
 
 constexpr int F8_BM = 256, F8_BN = 256, F8_KB = 128;        // tile; bytes (= elements) of a row per k-tile
-constexpr int F8_STAGE = (F8_BM + F8_BN) * 8;               // 16-byte units per stage
-constexpr size_t F8_SMEM = (size_t)2 * F8_STAGE * 16;       // 128 KB
+constexpr int F8_SLOT = 256 * 8;                            // 16-byte units per slot (one operand tile)
+constexpr size_t F8_SMEM = (size_t)5 * F8_SLOT * 16;        // 160 KB
+static_assert(F8_BM == 256 && F8_BN == 256, "a slot holds one 256-row operand tile");
 
 template <int EPI>
 __global__ __launch_bounds__(256, 1) void gemm_fp8_kernel(const unsigned char* __restrict__ A, int lda, size_t a_ss,
@@ -40,7 +47,7 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_kernel(const unsigned char* _
                                                           int mtiles, int ntiles, int total, bf16* __restrict__ out2,
                                                           int n_split, int ld2, size_t o2_ss, int mb, float q_out)
 {
-    constexpr int BM = F8_BM, KB = F8_KB, STAGE = F8_STAGE;
+    constexpr int BM = F8_BM, KB = F8_KB, SLOT = F8_SLOT;
     constexpr int TM = 4, TN = 4, WT = 128;
     extern __shared__ uint4 smem[];
 
@@ -65,107 +72,173 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_kernel(const unsigned char* _
     // address has to be kept in vector registers across the main loop)
     const unsigned a_lane = (unsigned)((wave * 8 + lrow) * lda + lchunk * 16);
     const unsigned w_lane = (unsigned)((wave * 8 + lrow) * Kd + lchunk * 16);
-    auto issue_a = [&](int i, int kb, int stage) {           // i-th of the 8 wave-loads of an activation tile
+    auto issue_a = [&](int i, int kb, int slot) {            // i-th of the 8 wave-loads of an activation tile
         __builtin_amdgcn_global_load_lds((gbl_void*)(Ag + ((size_t)i * 32 * lda + kb) + a_lane),
-                                         (lds_void*)(smem + stage * STAGE + (wave + i * 4) * 64), 16, 0, 0);
+                                         (lds_void*)(smem + slot * SLOT + (wave + i * 4) * 64), 16, 0, 0);
     };
-    auto issue_w = [&](int i, int kb, int stage) {           // ... of a weight tile
+    auto issue_w = [&](int i, int kb, int slot) {            // ... of a weight tile
         __builtin_amdgcn_global_load_lds((gbl_void*)(Wg + ((size_t)i * 32 * Kd + kb) + w_lane),
-                                         (lds_void*)(smem + stage * STAGE + BM * 8 + (wave + i * 4) * 64), 16, 0, 0);
+                                         (lds_void*)(smem + slot * SLOT + (wave + i * 4) * 64), 16, 0, 0);
     };
 
     const int j31 = lane & 31, g = lane >> 5;
     const int nk = Kd / KB;
     const float* scl = (const float*)(sb + s_off) + n0 + wn * WT + 4 * g;
     f32x16 acc[TN][TM];
+    // The accumulators start from bias / (sw / qa), so that the epilogue's multiplication by sw / qa restores the
+    // bias.  Bias and scales of the wave's 128 features come in by one direct-to-LDS load as well, the oldest in
+    // flight (lanes 0-31: bias, lanes 32-63: scales), into the part of slot 4 that only this wave's own first load
+    // of the activation tile of k-tile 2 overwrites later.  (Fetched into registers instead, their use would make
+    // the compiler wait for every direct-to-LDS load issued after them.)
+    float* seed_lds = (float*)(smem + 4 * SLOT + wave * 64);
+    {
+        const float* src = (lane < 32 ? (const float*)(sb + b_off) : (const float*)(sb + s_off)) + n0 + wn * WT + 4 * (lane & 31);
+        __builtin_amdgcn_global_load_lds((gbl_void*)src, (lds_void*)seed_lds, 16, 0, 0);
+    }
+    // start: both tiles of k-tiles 0 and 1
 #pragma unroll
     for (int i = 0; i < 8; ++i) issue_a(i, 0, 0);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) issue_w(i, 0, 0);
+    for (int i = 0; i < 8; ++i) issue_w(i, 0, 1);
+    if (nk > 1) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) issue_a(i, KB, 2);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) issue_w(i, KB, 3);
+    }
+
+    // Fragment addresses.  Rows of the wave's blocks are 32 apart and the wave tiles start at multiples of 128, so
+    // one swizzle key ((row >> 1) & 7 = (lane % 32 >> 1) & 7) serves every fragment of both operands; per operand
+    // and chunk (two k-steps x two chunks) one lane offset, the block (32 rows = 4096 bytes) an immediate.
+    const int key = (j31 >> 1) & 7;
+    int wch[2][2], xch[2][2];                               // [k-step][chunk]: 16-byte unit inside a slot, block 0
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int c = (4 * st + 2 * g + h) ^ key;
+            wch[st][h] = (wn * WT + j31) * 8 + c;
+            xch[st][h] = (wm * WT + j31) * 8 + c;
+        }
+    auto frag = [&](int slot, const int (&ch)[2][2], int blk, int st) {
+        // (read as vector types, not as the four members of a uint4: the compiler keeps type-based alias information
+        // on such loads, and without it it makes every LDS read wait for all direct-to-LDS loads in flight)
+        const v4i* base = (const v4i*)(smem + slot * SLOT + blk * (32 * 8));
+        const v4i lo = base[ch[st][0]], hi = base[ch[st][1]];
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    };
+
+    // residual rows of this wave's 128 x 128 sub-tile -> its staging slice, [128 tokens][256 bytes] with chunk
+    // (feature / 8) ^ (token & 15); 32 wave-loads of four rows each
+    const size_t row0 = (size_t)m0 + wm * WT;
+    const int col0 = n0 + wn * WT;
+    char* slice = (char*)smem + (size_t)wave * (WT * WT * 2);
+    // (wave-load q covers tokens 4 q + lane / 16; the swizzle repeats every 16 tokens, so four lane offsets serve
+    // all of them and the rest of the address is uniform)
+    unsigned roff[4];
+#pragma unroll
+    for (int qq = 0; qq < 4; ++qq) {
+        const int t = qq * 4 + (lane >> 4), cc = lane & 15;
+        roff[qq] = EPI == EPI_BIAS_RESIDUAL ? (unsigned)(t * ldr + ((cc ^ t) << 3)) * 2u : 0u;
+    }
+    const char* rbase = (const char*)(res + (size_t)m * r_ss + row0 * ldr + col0);
+    auto issue_residual = [&](int q) {
+        __builtin_amdgcn_global_load_lds((gbl_void*)(rbase + (size_t)(q >> 2) * 16 * ldr * 2 + roff[q & 3]),
+                                         (lds_void*)(slice + q * 1024), 16, 0, 0);
+    };
+
+    v8i fw[2][TN], fx[2][TM];
+    f32x4 f4[TN][4];                                        // sw / qa of the lane's features
+    if (nk > 1) wait_vmcnt<16>(); else wait_vmcnt<0>();   // bias, scales and k-tile 0
+    barrier_lds();
     {
-        // the accumulators start from bias / (sw / qa), so that the epilogue's multiplication restores the bias
-        const float* bias = (const float*)(sb + b_off) + n0 + wn * WT + 4 * g;
+        // (all reads first, one wait: with direct-to-LDS loads in flight the compiler waits for the whole LDS queue
+        // at every first use of a read's result)
+        f32x4 b4[TN][4], s4[TN][4];
 #pragma unroll
         for (int i = 0; i < TN; ++i)
 #pragma unroll
             for (int v4 = 0; v4 < 4; ++v4) {
-                const f32x4 b4 = *(const f32x4*)(bias + i * 32 + 8 * v4), s4 = *(const f32x4*)(scl + i * 32 + 8 * v4);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float seed = b4[e] / (s4[e] * inv_qa);
-#pragma unroll
-                    for (int j = 0; j < TM; ++j) acc[i][j][4 * v4 + e] = seed;
-                }
+                b4[i][v4] = *(const f32x4*)(seed_lds + i * 32 + 8 * v4 + 4 * g);
+                s4[i][v4] = *(const f32x4*)(seed_lds + 128 + i * 32 + 8 * v4 + 4 * g);
             }
-    }
-
-    int woff[TN], xoff[TM], wkey[TN], xkey[TM];
-#pragma unroll
-    for (int i = 0; i < TN; ++i) { const int r = wn * WT + i * 32 + j31; woff[i] = BM * 8 + r * 8; wkey[i] = (r >> 1) & 7; }
-#pragma unroll
-    for (int j = 0; j < TM; ++j) { const int r = wm * WT + j * 32 + j31; xoff[j] = r * 8; xkey[j] = (r >> 1) & 7; }
-    auto frag = [&](const uint4* st, int off, int key, int s) {
-        const int c0 = 4 * s + 2 * g;
-        const uint4 lo = st[off + (c0 ^ key)], hi = st[off + ((c0 + 1) ^ key)];
-        return v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
-    };
-    auto read_frags = [&](const uint4* st, int s, v8i (&fw)[TN], v8i (&fx)[TM]) {
-#pragma unroll
-        for (int i = 0; i < TN; ++i) fw[i] = frag(st, woff[i], wkey[i], s);
-#pragma unroll
-        for (int j = 0; j < TM; ++j) fx[j] = frag(st, xoff[j], xkey[j], s);
-    };
-    // sixteen matrix instructions; with LOADS, the sixteen wave-loads of k-tile lkt (into `lstage`) go one in front
-    // of each
-    auto multiply = [&](const v8i (&fw)[TN], const v8i (&fx)[TM], auto loads_c, int lkt, int lstage) {
-        constexpr bool LOADS = decltype(loads_c)::value;
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < TN; ++i)
 #pragma unroll
-            for (int j = 0; j < TM; ++j) {
-                const int idx = i * TM + j;
-                if (LOADS) {
-                    if (idx < 8) issue_a(idx, lkt * KB, lstage); else issue_w(idx - 8, lkt * KB, lstage);
+            for (int v4 = 0; v4 < 4; ++v4)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float seed = b4[i][v4][e] * __builtin_amdgcn_rcpf(s4[i][v4][e] * inv_qa);
+#pragma unroll
+                    for (int j = 0; j < TM; ++j) acc[i][j][4 * v4 + e] = seed;
                 }
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fw[i], fx[j], acc[i][j], 0, 0, 0, 0x7f7f7f7f,
-                                                                            0, 0x7f7f7f7f);
+    }
+    __builtin_amdgcn_s_waitcnt(0xc07f);                     // lgkmcnt(0): the seeds are read before slot 4 is refilled
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < TN; ++i) fw[0][i] = frag(1, wch, i, 0);
+#pragma unroll
+    for (int j = 0; j < TM; ++j) fx[0][j] = frag(0, xch, j, 0);
+
+    int sa = 0;                                             // activation slot of k-tile j
+    // One k-tile; the flags are compile-time, so no variant has a branch in its body.
+    //   L0 / L1: the loads of k-step 0 / 1 exist (k-tile j + 2 exists);  NEXT: k-tile j + 1 exists;  RES: k-step 1 carries the residual loads (last k-tile: the whole
+    //            ring is free after its barrier).
+    auto ktile = [&](int j, auto l0_c, auto l1_c, auto next_c, auto res_c) {
+        constexpr bool L0 = decltype(l0_c)::value, L1 = decltype(l1_c)::value, NEXT = decltype(next_c)::value;
+        constexpr bool RES = decltype(res_c)::value;
+        auto rot = [](int s0, int d) { const int t = s0 + d; return t >= 5 ? t - 5 : t; };
+        const int s1 = rot(sa, 1), s2 = rot(sa, 2), s3 = rot(sa, 3), s4 = rot(sa, 4);
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            if (s == 1) {
+                // k-tile j + 1 has landed; the only younger loads are the eight of k-step 0
+                if (L1) wait_vmcnt<8>(); else if (NEXT) wait_vmcnt<0>();
+                barrier_lds();
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            const int xslot = s == 0 ? sa : s2, wslot = s == 0 ? s1 : s3, fstep = s == 0 ? 1 : 0;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {                   // one load, one fragment, two matrix instructions
+                if (s == 0 && L0) issue_a(q, (j + 2) * KB, s4);
+                if (s == 1 && L1) issue_w(q, (j + 2) * KB, sa);
+                if (s == 1 && RES) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) issue_residual(4 * q + r);
+                }
+                if (s == 0 || NEXT) {
+                    if (q < TN) fw[(s + 1) & 1][q] = frag(wslot, wch, q, fstep);
+                    else fx[(s + 1) & 1][q - TN] = frag(xslot, xch, q - TN, fstep);
+                }
+#pragma unroll
+                for (int idx = 2 * q; idx < 2 * q + 2; ++idx) {
+                    const int i = idx / TM, jj = idx % TM;
+                    acc[i][jj] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fw[s & 1][i], fx[s & 1][jj], acc[i][jj], 0,
+                                                                                 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
-    };
-
-    v8i fw0[TN], fx0[TM], fw1[TN], fx1[TM];
-    f32x4 f4[TN][4];                                        // sw / qa of the lane's features
-    wait_vmcnt<0>();
-    barrier_lds();
-    if (nk > 1) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) issue_a(i, KB, 1);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) issue_w(i, KB, 1);
-    }
-    read_frags(smem, 0, fw0, fx0);
-    // NEXT: k-tile kt + 1 exists; LOADS: k-tile kt + 2 exists (the steady state has both and no branch)
-    auto ktile = [&](int kt, auto next_c, auto loads_c) {
-        constexpr bool NEXT = decltype(next_c)::value;
-        const int st = kt & 1;
-        __builtin_amdgcn_s_waitcnt(0xc07f);                 // lgkmcnt(0): the first k-step's fragments are here
-        __builtin_amdgcn_sched_barrier(0);
-        read_frags(smem + st * STAGE, 1, fw1, fx1);
-        __builtin_amdgcn_sched_barrier(0);
-        multiply(fw0, fx0, std::false_type{}, 0, 0);
-        if (NEXT) wait_vmcnt<0>();                          // this wave's share of k-tile kt + 1 (requested a k-tile ago)
-        __builtin_amdgcn_s_waitcnt(0xc07f);                 // lgkmcnt(0): the second k-step's fragments are here
-        __builtin_amdgcn_s_barrier();
-        __builtin_amdgcn_sched_barrier(0);
-        if (NEXT) read_frags(smem + (st ^ 1) * STAGE, 0, fw0, fx0);
-        __builtin_amdgcn_sched_barrier(0);
-        multiply(fw1, fx1, loads_c, kt + 2, st);
+        }
+        sa = s2;
     };
     {
-        int kt = 0;
-        for (; kt + 2 < nk; ++kt) ktile(kt, std::true_type{}, std::true_type{});
-        if (kt + 1 < nk) { ktile(kt, std::true_type{}, std::false_type{}); ++kt; }
-        ktile(kt, std::false_type{}, std::false_type{});
+        constexpr std::true_type Y{};
+        constexpr std::false_type N{};
+        constexpr std::integral_constant<bool, EPI == EPI_BIAS_RESIDUAL> R{};
+        if (nk >= 3) {
+            // (the first k-tile stays outside the loop: its matrix instructions take the seeds from vector registers
+            // and leave their results in accumulation registers, which is where the loop then keeps them)
+            ktile(0, Y, Y, Y, N);
+            for (int jt = 1; jt < nk - 2; ++jt) ktile(jt, Y, Y, Y, N);
+            ktile(nk - 2, N, N, Y, N);
+            ktile(nk - 1, N, N, N, R);
+        } else if (nk == 2) {
+            ktile(0, N, N, Y, N);
+            ktile(1, N, N, N, R);
+        } else {
+            ktile(0, N, N, N, R);
+        }
     }
     // the epilogue's per-feature factors sw / qa (fetched here and not earlier: the main loop has no registers to
     // spare for them)
@@ -177,9 +250,6 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_kernel(const unsigned char* _
     // ---- epilogue.  Accumulator element v of lane l in block (i, j): token = l % 32,
     // feature = 8 * (v / 4) + 4 * (l / 32) + v % 4 inside the 32x32 block.  After the barrier of the last
     // iteration nobody reads the ring: each wave stages its 128 x 128 sub-tile in its own slice of it.
-    const size_t row0 = (size_t)m0 + wm * WT;
-    const int col0 = n0 + wn * WT;
-
     if (EPI == EPI_BIAS_GELU) {
         // fp8 output, e4m3(gelu(.) * q_out): staged [128 tokens][128 bytes], chunk (feature / 16) ^ (token & 7)
         char* slice = (char*)smem + (size_t)wave * (WT * WT);
@@ -208,7 +278,6 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_kernel(const unsigned char* _
         return;
     }
 
-    char* slice = (char*)smem + (size_t)wave * (WT * WT * 2);
     bf16* out = (bf16*)outv;
     const bool transposed = EPI == EPI_QKV && n0 >= n_split;
     const int rr = lane >> 4, cc = lane & 15;
@@ -234,16 +303,7 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_kernel(const unsigned char* _
     }
 
     // staged [128 tokens][128 features]: 256-byte rows, chunk (feature / 8) ^ (token & 15)
-    if (EPI == EPI_BIAS_RESIDUAL) {
-        const bf16* rb = res + (size_t)m * r_ss + row0 * ldr + col0;
-#pragma unroll 8
-        for (int q = 0; q < 32; ++q) {
-            const int t = q * 4 + rr;
-            __builtin_amdgcn_global_load_lds((gbl_void*)(rb + (size_t)t * ldr + ((cc ^ (t & 15)) << 3)),
-                                             (lds_void*)(slice + q * 1024), 16, 0, 0);
-        }
-        wait_vmcnt<0>();
-    }
+    if (EPI == EPI_BIAS_RESIDUAL) wait_vmcnt<0>();          // the residual rows, requested during the last k-step
 #pragma unroll
     for (int jj = 0; jj < TM; ++jj)
 #pragma unroll
