@@ -61,7 +61,8 @@ struct GemmTile {
     // one half of the staging area (= one stage of the two-stage ring, two slots of the five-slot ring)
     static constexpr size_t half_bytes = (size_t)(BM + BN) * 8 * 16;
     static_assert(NS >= 2 && (size_t)4 * (WTM / 2) * WTN * 2 <= half_bytes, "staging halves must fit the ring stages");
-    static constexpr size_t smem_bytes = ring_bytes;
+    // (the smaller tiles keep the waves' bias values behind the ring, one kilobyte per wave)
+    static constexpr size_t smem_bytes = ring_bytes + (RING5 ? 0 : 4 * 1024);
 };
 
 template <int BM, int BN, int EPI>
@@ -118,17 +119,26 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
                                              16, 0, 0);
     };
 
-    // The lane's bias values, as the oldest loads in flight: the accumulators start from them.
+    // The accumulators start from the lane's bias values.  They come in through LDS, by one direct-to-LDS wave-load
+    // per wave issued before the operand tiles (lane l fetches features 4 (l mod WTN / 4) .. + 3 of the wave's WTN, so
+    // the first WTN floats of the wave's kilobyte are its bias): fetched into registers instead, their first use would
+    // make the compiler wait for every direct-to-LDS load issued after them, i.e. for the whole ring instead of the
+    // first k-tile.
     const int j31 = lane & 31, g = lane >> 5;
     f32x4 b4[TN][4];
-    {
-        const float* bias = (const float*)(arena + (size_t)m * student_stride + b_off) + n0 + wn * G::WTN + 4 * g;
+    auto request_bias = [&](float* seed_lds) {
+        if (EPI == EPI_PARTIAL) return;
+        const float* bias_w = (const float*)(arena + (size_t)m * student_stride + b_off) + n0 + wn * G::WTN;
+        __builtin_amdgcn_global_load_lds((gbl_void*)(bias_w + 4 * (lane % (G::WTN / 4))), (lds_void*)seed_lds, 16, 0, 0);
+    };
+    auto read_bias = [&](const float* seed_lds) {
 #pragma unroll
         for (int i = 0; i < TN; ++i)
 #pragma unroll
             for (int v4 = 0; v4 < 4; ++v4)
-                b4[i][v4] = EPI == EPI_PARTIAL ? f32x4{0.f, 0.f, 0.f, 0.f} : *(const f32x4*)(bias + i * 32 + 8 * v4);
-    }
+                b4[i][v4] = EPI == EPI_PARTIAL ? f32x4{0.f, 0.f, 0.f, 0.f} : *(const f32x4*)(seed_lds + 4 * g + i * 32 + 8 * v4);
+        __builtin_amdgcn_sched_barrier(0);
+    };
 
     // Epilogue staging geometry (used early by the residual prefetch).
     constexpr int WTM = G::WTM, WTN = G::WTN;
@@ -193,8 +203,12 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
             __builtin_amdgcn_global_load_lds((gbl_void*)(w_src + (size_t)i * 32 * ldw + k0),
                                              (lds_void*)(smem + slot * SLOT + (wave + i * 4) * 64), 16, 0, 0);
         };
-        // k-tile t: activations in slot 2 t mod 5, weights in slot (2 t + 1) mod 5.  Start: both tiles of k-tiles 0
-        // and 1 and the activation tile of k-tile 2 (Kd is a multiple of 128, so there are at least two k-tiles).
+        // k-tile t: activations in slot 2 t mod 5, weights in slot (2 t + 1) mod 5.  Start: the wave's 128 bias values
+        // (one wave-load, both lane halves fetch the same 512 bytes, into the part of slot 4 that only this wave's own
+        // first load of the activation tile of k-tile 2 overwrites later), then both tiles of k-tiles 0 and 1 (Kd is a
+        // multiple of 128, so there are at least two k-tiles).
+        float* seed_lds = (float*)(smem + 4 * SLOT + wave * 64);
+        request_bias(seed_lds);
 #pragma unroll
         for (int i = 0; i < 8; ++i) issue_a(i, 0, 0);
 #pragma unroll
@@ -203,18 +217,17 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
         for (int i = 0; i < 8; ++i) issue_a(i, BK, 2);
 #pragma unroll
         for (int i = 0; i < 8; ++i) issue_w(i, BK, 3);
-        if (nk > 2) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) issue_a(i, 2 * BK, 4);
-        }
+        wait_vmcnt<16>();                                   // bias and k-tile 0
+        barrier_lds();
+        read_bias(seed_lds);
 #pragma unroll
         for (int i = 0; i < TN; ++i)
 #pragma unroll
             for (int j = 0; j < TM; ++j)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[i][j][e] = b4[i][e >> 2][e & 3];
-        if (nk > 2) wait_vmcnt<24>(); else wait_vmcnt<16>();
-        barrier_lds();
+        __builtin_amdgcn_s_waitcnt(0xc07f);                 // lgkmcnt(0): the bias is read before slot 4 is refilled
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < TN; ++i) fw[0][i] = __builtin_bit_cast(bf16x8, smem[SLOT + woff[i] + (g ^ wkey[i])]);
 #pragma unroll
@@ -238,8 +251,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
                     barrier_lds();
                 }
                 __builtin_amdgcn_sched_barrier(0);
-                const bool do_loads =
-                    STEADY || (s == 3 ? j + 2 < nk : (s == 0 ? j >= 1 && j + 1 < nk : j >= 1 && j + 2 < nk));
+                const bool do_loads = STEADY || (s == 0 ? j >= 1 && j + 1 < nk : j + 2 < nk);
                 const bool do_frags = s + 1 < STEPS || STEADY || j + 1 < nk;
                 const int xslot = s + 1 < STEPS ? sa : s2, wslot = s + 1 < STEPS ? s1 : s3;
                 const int kg = 2 * (s + 1 < STEPS ? s + 1 : 0) + g;
@@ -282,19 +294,22 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
             ktile(jt, std::false_type{});
         }
     } else {
+        float* seed_lds = (float*)((char*)smem + G::ring_bytes) + wave * 256;   // one kilobyte per wave behind the ring
+        request_bias(seed_lds);
 #pragma unroll
         for (int t = 0; t < NS; ++t)
             if (t < nk)
 #pragma unroll
                 for (int i = 0; i < LPW; ++i) issue1(i, t * BK, t);
+        if (nk >= NS) wait_vmcnt<(NS - 1) * LPW>(); else wait_vmcnt<0>();   // bias and k-tile 0
+        barrier_lds();
+        read_bias(seed_lds);
 #pragma unroll
         for (int i = 0; i < TN; ++i)
 #pragma unroll
             for (int j = 0; j < TM; ++j)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[i][j][e] = b4[i][e >> 2][e & 3];
-        if (nk >= NS) wait_vmcnt<(NS - 1) * LPW>(); else wait_vmcnt<0>();
-        barrier_lds();
 #pragma unroll
         for (int i = 0; i < TN; ++i) fw[0][i] = __builtin_bit_cast(bf16x8, smem[woff[i] + (g ^ wkey[i])]);
 #pragma unroll
