@@ -62,8 +62,9 @@ typedef struct {
                          fp32 scale per output feature (max |w| -> 448), activations quantised by the kernel
                          that produces them as e4m3(16 * value) (one fixed power-of-two scale per tensor; the
                          FFN activations exist only in fp8), fp32 accumulation, same epilogues.  Attention
-                         itself, the first-token last layer, the head and all smaller calls stay bf16 (the
-                         arena keeps both copies of the four matrices). */
+                         itself, the first-token last layer, the head, all smaller calls, and students whose
+                         hidden or FFN width is not a multiple of 256 stay bf16 (the arena keeps both copies
+                         of the four matrices). */
     float ln_eps;     /* LayerNorm epsilon (BERT: 1e-12) */
     int32_t last_layer_all_tokens;
                       /* Only the first token of each sequence feeds the head (the pooled representation of

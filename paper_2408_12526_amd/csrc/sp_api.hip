@@ -298,7 +298,9 @@ static int run_students(const sp_model* M0, const WsLayout& W, const int32_t* id
 #define SP_TRY(expr) do { if ((expr) != hipSuccess) return SP_EHIP; } while (0)
 #define SP_MARK(ph) do { if (pt) pt->mark(ph, s); } while (0)
     // quantised students: the three large projections of the all-token layers on fp8 operands (large calls only)
-    const bool fp8 = c.dtype == SP_DTYPE_FP8 && mrows % 256 == 0 && mrows >= kFp8MinRows && W.xq;
+    // (the fp8 kernel has one tile size, 256 x 256: widths that are not multiples of it stay on the bf16 path)
+    const bool fp8 = c.dtype == SP_DTYPE_FP8 && mrows % 256 == 0 && mrows >= kFp8MinRows && W.xq && H % 256 == 0 &&
+                     F % 256 == 0;
     const size_t qH = (size_t)rows * H, qF = (size_t)rows * F;       // bytes per student of the fp8 buffers
     char *xq = fp8 ? w + W.xq + m0 * qH : nullptr, *x1q = fp8 ? w + W.x1q + m0 * qH : nullptr;
     char *gq = fp8 ? w + W.gq + m0 * qF : nullptr, *attq = fp8 ? w + W.attq + m0 * qH : nullptr;

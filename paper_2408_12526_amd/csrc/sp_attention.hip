@@ -10,13 +10,34 @@ namespace sp {
 namespace {
 
 constexpr int kD = 64;          // head width
-constexpr int kQPerWg = 128;    // queries per workgroup: 4 waves x 32
+constexpr int kQPerWg = 256;    // queries per workgroup of the long-sequence body: 4 waves x 2 blocks of 32
 constexpr int kKeyTile = 64;    // keys staged in LDS per step
 constexpr int kKStride = kKeyTile + 1;   // 16-byte units per k-group of the key tile
 constexpr int kVStride = 68;    // bf16 elements per row of the transposed value tile (136 B)
 constexpr int kOutPitch = kD * 2 + 16;   // bytes per staged output row
 constexpr int kLongKBytes = 8 * kKStride * 16, kLongVBytes = kD * kVStride * 2;
-constexpr int kLongLdsBytes = kLongKBytes + kLongVBytes + 4 * 32 * kOutPitch;
+constexpr int kLongTileBytes = kLongKBytes + kLongVBytes;   // one buffer of the key/value tile
+constexpr int kLongLdsBytes = 2 * kLongTileBytes;
+static_assert(kLongTileBytes % 16 == 0 && 4 * 32 * kOutPitch <= kLongLdsBytes, "the output tiles reuse the key/value buffers");
+
+// 2^x by the hardware instruction alone.  (exp2f() wraps it in a range test, a scaling and an ldexp so that results
+// below 2^-126 come out as denormals: four more instructions per value, which a softmax numerator does not need;
+// arguments here are <= 0, and what underflows is flushed to zero.)
+__device__ inline float exp2_raw(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// The value of lane l ^ 32, for both halves of the wave at once: v_permlane32_swap exchanges lanes 32-63 of its first
+// operand with lanes 0-31 of its second, so with x in both, `lo` ends up as x[l % 32] and `hi` as x[32 + l % 32] in every
+// lane.  (One instruction instead of the LDS round trip of a general lane permutation.  The instruction needs two idle
+// issue slots after a vector write of its operands, which the compiler cannot know about inside an asm statement:
+// hence the s_nop in front; the one behind keeps the same distance to the first reader.)
+__device__ inline void halves(float x, float& lo, float& hi)
+{
+    lo = x;
+    hi = x;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(lo), "+v"(hi));
+}
+__device__ inline float max_across_halves(float x) { float lo, hi; halves(x, lo, hi); return fmaxf(lo, hi); }
+__device__ inline float sum_across_halves(float x) { float lo, hi; halves(x, lo, hi); return lo + hi; }
 
 // eight bf16 values (one 16-byte chunk of an output row) -> eight e4m3 codes of value * qscale
 __device__ inline uint2 chunk_to_fp8(uint4 c, float qscale)
@@ -31,15 +52,20 @@ __device__ inline uint2 chunk_to_fp8(uint4 c, float qscale)
 }
 
 // -------------------------------------------------------------------------------------
-// bf16 kernel on the matrix cores.  One workgroup = (student, sequence, head, block of 128
-// queries); wave w owns queries q0 + 32w .. + 31.  Per 64-key tile:
-//   S^T = K Q^T      (A operand: key rows from LDS, B operand: the wave's queries, kept in
+// bf16 body on the matrix cores for long sequences.  One workgroup = (student, sequence, head, block of 256
+// queries); wave w owns queries q0 + 64 w .. + 63 as two blocks of 32, which share every key and value fragment
+// it reads from LDS.  Per 64-key tile and query block:
+//   S^T = K Q^T      (A operand: key rows from LDS, B operand: the block's queries, kept in
 //                     registers for the whole kernel)
 //   online softmax   per query = per lane column; a query's keys sit in 16 accumulator
-//                    registers of two lanes (l and l + 32)
+//                    registers of two lanes (l and l + 32); the 1/sqrt(d) log2(e) factor rides in the
+//                    fused multiply-add in front of the exponential
 //   O^T += V^T P^T   (A operand: transposed value tile from LDS; B operand: the
 //                     probabilities, which already sit in the B-operand register layout
 //                     once the reduction slots of V^T are enumerated in the same key order)
+// The key/value tiles are double-buffered in LDS and travel through registers: tile t + 2 is requested from
+// memory and tile t + 1 written to the idle buffer while tile t is multiplied; one barrier per tile, which
+// waits for LDS traffic only (the loads stay in flight across it).
 // -------------------------------------------------------------------------------------
 __device__ __forceinline__ void attention_long_body(char* lds, int bid, const bf16* __restrict__ qkv,
                                                     const bf16* __restrict__ vt, bf16* __restrict__ att,
@@ -47,10 +73,6 @@ __device__ __forceinline__ void attention_long_body(char* lds, int bid, const bf
                                                     int heads, int max_seqlen, int nqc, int min_len,
                                                     unsigned char* __restrict__ attq, float qscale)
 {
-    uint4* sK = (uint4*)lds;                                          // [d-group of 8][key], 8 * kKStride units
-    bf16* sVt = (bf16*)(lds + kLongKBytes);                           // [d][key], kD rows of kVStride
-    char* sOut0 = lds + kLongKBytes + kLongVBytes;                    // per wave: 32 output rows of kOutPitch bytes
-
     const int m = blockIdx.y;
     // (sequence, head) pairs go round the XCDs one by one (the few long sequences of a serving batch are spread evenly:
     // a contiguous run of sequences per XCD left them unevenly loaded and was measured 1.5x slower), but the query
@@ -69,28 +91,33 @@ __device__ __forceinline__ void attention_long_body(char* lds, int bid, const bf
     const int q0 = qc * kQPerWg;
     if (q0 >= L || L <= min_len) return;            // whole workgroup leaves together
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int j = lane & 31, g = lane >> 5;
     const size_t ld = (size_t)3 * H;
     const bf16* base = qkv + ((size_t)m * rows + t0) * ld + h * kD;
-    const int q = q0 + wave * 32 + j;               // this lane's query
-    const bool wave_active = q0 + wave * 32 < L;
+    const int qw = q0 + wave * 64;                  // the wave's first query
+    const int g4 = 4 * g;
 
     // queries: B operand of S^T = K Q^T, four k-steps of 16 over d
-    bf16x8 qf[4];
+    bf16x8 qf[2][4];
+    f32x16 o[2][2];
+    float mrun[2], lrun[2];                         // running maximum (raw scores) and sum of a query's half of the keys
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        uint4 t = {0, 0, 0, 0};
-        if (q < L) t = *(const uint4*)(base + (size_t)q * ld + 16 * s + 8 * g);
-        qf[s] = __builtin_bit_cast(bf16x8, t);
+    for (int qb = 0; qb < 2; ++qb) {
+        const int q = qw + 32 * qb + j;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            uint4 t = {0, 0, 0, 0};
+            if (q < L) t = *(const uint4*)(base + (size_t)q * ld + 16 * s + 8 * g);
+            qf[qb][s] = __builtin_bit_cast(bf16x8, t);
+        }
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) o[qb][db][e] = 0.f;
+        mrun[qb] = -INFINITY;
+        lrun[qb] = 0.f;
     }
-
-    f32x16 o[2];
-#pragma unroll
-    for (int db = 0; db < 2; ++db)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) o[db][e] = 0.f;
-    float mrun = -INFINITY, lrun = 0.f;
     const float sl2 = 0.125f * 1.44269504088896341f;   // 1/sqrt(64) * log2(e)
 
     // Key tiles start at a token index that is a multiple of 8, so that the transposed values (token-contiguous
@@ -98,21 +125,20 @@ __device__ __forceinline__ void attention_long_body(char* lds, int bid, const bf
     const int lead = t0 & 7;
     const bf16* vbase = vt + ((size_t)m * H + h * kD) * rows + (t0 - lead);
     const int lrow = tid >> 3, lc = tid & 7;
-    // the key tile (rows = keys) and the value tile (rows = head dimensions) travel through registers: the next
-    // tile is requested before the current one is multiplied; what lies beyond the sequence is zero-filled
     uint4 kreg[2], vreg[2];
-    auto fetch = [&](int kt0) {
+    auto fetch = [&](int kt0) {                     // what lies beyond the sequence is zero-filled
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
-            const int r = lrow + 32 * p;                      // key of the tile, or head dimension
+            const int r = lrow + 32 * p;            // key of the tile, or head dimension
             kreg[p] = uint4{0, 0, 0, 0};
             vreg[p] = uint4{0, 0, 0, 0};
             if (kt0 + r >= 0 && kt0 + r < L) kreg[p] = *(const uint4*)(base + (ptrdiff_t)(kt0 + r) * (ptrdiff_t)ld + H + lc * 8);
             if (kt0 + lc * 8 < L) vreg[p] = *(const uint4*)(vbase + (size_t)r * rows + (kt0 + lead) + lc * 8);
         }
     };
-    fetch(-lead);
-    for (int kt0 = -lead; kt0 < L; kt0 += kKeyTile) {
+    auto stage = [&](int buf) {                     // registers -> LDS buffer: keys [d-group of 8][key], values [d][key]
+        uint4* sK = (uint4*)(lds + buf * kLongTileBytes);
+        bf16* sVt = (bf16*)(lds + buf * kLongTileBytes + kLongKBytes);
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
             const int r = lrow + 32 * p;
@@ -121,51 +147,79 @@ __device__ __forceinline__ void attention_long_body(char* lds, int bid, const bf
             vd[0] = uint2{vreg[p].x, vreg[p].y};
             vd[1] = uint2{vreg[p].z, vreg[p].w};
         }
-        if (kt0 + kKeyTile < L) fetch(kt0 + kKeyTile);
-        __syncthreads();
-
-        if (wave_active) {
-            // scores of this wave's 32 queries against the 64 keys: two 32x32 blocks
-            f32x16 sc[2];
+    };
+    const bool act1 = qw + 32 < L;                  // the wave's second query block exists (wave-uniform)
+    const bool act0 = qw < L;
+    fetch(-lead);
+    stage(0);
+    if (-lead + kKeyTile < L) fetch(-lead + kKeyTile);
+    barrier_lds();
+    int buf = 0;
+    for (int kt0 = -lead; kt0 < L; kt0 += kKeyTile, buf ^= 1) {
+        const uint4* sK = (const uint4*)(lds + buf * kLongTileBytes);
+        const bf16* sVt = (const bf16*)(lds + buf * kLongTileBytes + kLongKBytes);
+        if (act0) {
+            // scores of the wave's query blocks against the 64 keys: two 32x32 blocks each
+            f32x16 sc[2][2];
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
+            for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) sc[kb][e] = 0.f;
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) sc[qb][kb][e] = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int s = 0; s < 4; ++s) {
-                    const uint4 t = sK[(2 * s + g) * kKStride + kb * 32 + j];
-                    sc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, t), qf[s], sc[kb], 0, 0, 0);
+                    const bf16x8 kf = __builtin_bit_cast(bf16x8, sK[(2 * s + g) * kKStride + kb * 32 + j]);
+                    sc[0][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0][s], sc[0][kb], 0, 0, 0);
+                    if (act1) sc[1][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[1][s], sc[1][kb], 0, 0, 0);
                 }
+            // accumulator register v of this lane is key 8*(v/4) + 4*g + v%4 of its block; only the first and the
+            // last tile of a sequence have keys to mask
+            const bool edge = kt0 < 0 || kt0 + kKeyTile > L;
+            bf16x8 pf[2][2][2];
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
+                if (qb == 1 && !act1) continue;
+                float mx = mrun[qb];
+                if (edge) {
+                    // key kt0 + c + 4 g with c = 32 kb + 8 (v / 4) + v % 4 is valid if 0 <= key < L: the upper bound is
+                    // one comparison of the lane's 4 g with a uniform value; only the first four registers of block 0
+                    // can lie in front of the sequence (kt0 >= -7)
+#pragma unroll
+                    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            const int c = kb * 32 + 8 * (v >> 2) + (v & 3);
+                            bool ok = g4 < L - kt0 - c;
+                            if (kb == 0 && v < 4) ok = ok && g4 >= -kt0 - c;
+                            if (!ok) sc[qb][kb][v] = -INFINITY;
+                        }
+                }
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sc[qb][kb][v]);
+                mx = max_across_halves(mx);                 // the other half of the query's keys
+                const float alpha = exp2_raw((mrun[qb] - mx) * sl2);   // first tile: exp2(-inf) = 0
+                mrun[qb] = mx;
+                const float nm = -mx * sl2;
+                float psum = 0.f;
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const float p = exp2_raw(fmaf(sc[qb][kb][v], sl2, nm));
+                        psum += p;
+                        pf[qb][kb][v >> 3][v & 7] = (bf16)p;
+                    }
+                lrun[qb] = lrun[qb] * alpha + psum;
+#pragma unroll
+                for (int db = 0; db < 2; ++db)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) o[qb][db][e] *= alpha;
             }
-            // accumulator register v of this lane is key 8*(v/4) + 4*g + v%4 of its block
-            float mx = mrun;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int key = kt0 + kb * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-                    const float sv = key >= 0 && key < L ? sc[kb][v] * sl2 : -INFINITY;
-                    sc[kb][v] = sv;
-                    mx = fmaxf(mx, sv);
-                }
-            mx = fmaxf(mx, __shfl_xor(mx, 32));          // the other half of the query's keys
-            const float alpha = exp2f(mrun - mx);        // first tile: exp2(-inf) = 0
-            mrun = mx;
-            float psum = 0.f;
-            bf16x8 pf[2][2];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const float p = exp2f(sc[kb][v] - mx);
-                    psum += p;
-                    pf[kb][v >> 3][v & 7] = (bf16)p;
-                }
-            lrun = lrun * alpha + psum;
-#pragma unroll
-            for (int db = 0; db < 2; ++db)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
             // O^T += V^T P^T.  Reduction slot e of k-step s2 in block kb is key
             // 32*kb + 16*s2 + 8*(e/4) + 4*g + e%4, the key held by register 8*s2 + e above.
 #pragma unroll
@@ -178,40 +232,49 @@ __device__ __forceinline__ void attention_long_body(char* lds, int bid, const bf
                         const bf16* vr = sVt + (db * 32 + j) * kVStride + kbase;
                         const bf16x4 lo = *(const bf16x4*)vr, hi = *(const bf16x4*)(vr + 8);
                         const bf16x8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kb][s2], o[db], 0, 0, 0);
+                        o[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[0][kb][s2], o[0][db], 0, 0, 0);
+                        if (act1) o[1][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[1][kb][s2], o[1][db], 0, 0, 0);
                     }
                 }
         }
-        __syncthreads();
+        if (kt0 + kKeyTile < L) {
+            stage(buf ^ 1);                         // (idle since the barrier of the previous tile)
+            if (kt0 + 2 * kKeyTile < L) fetch(kt0 + 2 * kKeyTile);
+        }
+        barrier_lds();
     }
 
-    if (wave_active) {
-        const float lsum = lrun + __shfl_xor(lrun, 32);
-        const float inv = 1.0f / lsum;
-        // the wave's 32 x 64 output block leaves through a private LDS tile as whole 128-byte rows
-        char* stg = sOut0 + wave * (32 * kOutPitch);
+    // Each 32 x 64 output block leaves through a wave-private LDS tile (the key/value buffers are idle now) as whole
+    // 128-byte rows.
+    char* stg = lds + wave * (32 * kOutPitch);
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        const int qs = qw + 32 * qb;                // first query of the block
+        if (qs >= L) continue;
+        const float inv = 1.0f / sum_across_halves(lrun[qb]);
 #pragma unroll
         for (int db = 0; db < 2; ++db)
 #pragma unroll
             for (int v4 = 0; v4 < 4; ++v4) {
                 bf16x4 w;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) w[e] = (bf16)(o[db][4 * v4 + e] * inv);
+                for (int e = 0; e < 4; ++e) w[e] = (bf16)(o[qb][db][4 * v4 + e] * inv);
                 *(bf16x4*)(stg + j * kOutPitch + (db * 32 + 8 * v4 + 4 * g) * 2) = w;
             }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         const int orow = lane >> 3, oc = lane & 7;
-        const int qw = q0 + wave * 32;                      // the wave's first query
-        const size_t doff = ((size_t)m * rows + t0 + qw) * H + h * kD + oc * 8;
+        const size_t doff = ((size_t)m * rows + t0 + qs) * H + h * kD + oc * 8;
         bf16* dst = att + doff;
 #pragma unroll
         for (int r0 = 0; r0 < 32; r0 += 8)
-            if (qw + r0 + orow < L) {
+            if (qs + r0 + orow < L) {
                 const uint4 c = *(const uint4*)(stg + (r0 + orow) * kOutPitch + oc * 16);
                 *(uint4*)(dst + (size_t)(r0 + orow) * H) = c;
                 if (attq) *(uint2*)(attq + doff + (size_t)(r0 + orow) * H) = chunk_to_fp8(c, qscale);   // fp8 copy
             }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();            // the tile is rewritten by the next block
     }
 }
 
@@ -263,6 +326,7 @@ __device__ __forceinline__ void attention_short_body(char* lds, int bid, const b
     bf16* sVt = (bf16*)(lds + 4 * kShortKBytes + wave * kShortVBytes);
 
     const int j = lane & 31, g = lane >> 5;
+    const int g4 = 4 * g;
     const size_t ld = (size_t)3 * H;
     const bf16* base = qkv + ((size_t)m * rows + t0) * ld + h * kD;
     const float sl2 = 0.125f * 1.44269504088896341f;
@@ -335,19 +399,23 @@ __device__ __forceinline__ void attention_short_body(char* lds, int bid, const b
                 float mx = mrun[qb];
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int key = kt0 + 8 * (v >> 2) + 4 * g + (v & 3);
-                    const float sv = key >= 0 && key < L ? sc[v] * sl2 : -INFINITY;
+                    // key kt0 + c + 4 g, c = 8 (v / 4) + v % 4, is valid if 0 <= key < L: one comparison of the lane's
+                    // 4 g with a uniform value; only the first four registers can lie in front of the sequence
+                    const int c = 8 * (v >> 2) + (v & 3);
+                    bool ok = g4 < L - kt0 - c;
+                    if (v < 4) ok = ok && g4 >= -kt0 - c;
+                    const float sv = ok ? sc[v] * sl2 : -INFINITY;
                     sc[v] = sv;
                     mx = fmaxf(mx, sv);
                 }
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const float alpha = exp2f(mrun[qb] - mx);
+                mx = max_across_halves(mx);
+                const float alpha = exp2_raw(mrun[qb] - mx);
                 mrun[qb] = mx;
                 float psum = 0.f;
                 bf16x8 pf[2];
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const float p = exp2f(sc[v] - mx);
+                    const float p = exp2_raw(sc[v] - mx);
                     psum += p;
                     pf[v >> 3][v & 7] = (bf16)p;
                 }
@@ -378,7 +446,7 @@ __device__ __forceinline__ void attention_short_body(char* lds, int bid, const b
         for (int qb = 0; qb < QB; ++qb) {
             const int qs = q0 + 32 * qb;                    // first query of the block
             if (qb > 0 && qs >= L) continue;
-            const float inv = 1.0f / (lrun[qb] + __shfl_xor(lrun[qb], 32));
+            const float inv = 1.0f / sum_across_halves(lrun[qb]);
             char* stg = (char*)sVt;                         // 32 rows of 144 bytes = the whole slice
 #pragma unroll
             for (int db = 0; db < 2; ++db)
@@ -616,7 +684,7 @@ __global__ __launch_bounds__(512, 4) void attention_first_fold_kernel(const bf16
         for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
         float sum = 0.f;
         for (int t = lane; t < L; t += 64) {
-            const float e = exp2f(row[t] - mx);
+            const float e = exp2_raw(row[t] - mx);
             row[t] = e;
             sum += e;
         }

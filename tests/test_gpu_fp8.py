@@ -160,6 +160,18 @@ def test_fp8_mode_keeps_small_calls_on_the_bf16_path(sp, oracle64):
     st.close()
 
 
+def test_fp8_mode_keeps_other_widths_on_the_bf16_path(sp, oracle64):
+    """The fp8 kernel's one tile is 256 x 256: quantised students whose widths are not multiples of 256 (hidden 384
+    here) run large calls in bf16 as well and must meet the bf16 bound against the bf16 oracle weights."""
+    shape = synth.StudentShape(K=2, layers=2, hidden=384, heads=6, ffn=640, vocab=300, max_pos=320, classes=3, dtype="fp8")
+    lengths, ids, blob, cu = make_case(sp, 64, 40, shape)
+    st = sp.Students(sp.config_from_shape(shape), blob)
+    got = st.sp_forward(torch.from_numpy(ids).cuda(), torch.from_numpy(cu).cuda(), int(lengths.max()), shape.K)
+    want = oracle64.forward(ocfg(shape), dequantised_weights(blob, shape, ()), ids, cu, shape.K)
+    assert rel_err(got.cpu().numpy().astype(np.float64), want) <= 3e-2
+    st.close()
+
+
 def test_fp8_burst_workload_part(sp, oracle64):
     """The burst workload with quantised students (hidden 768, 58 token tiles, reduction depths 768 and 3072): one
     third of the sequences against the oracle at k_active 8 and 2."""

@@ -63,7 +63,8 @@ SINGLE_TILE_LENGTHS = (7, 1, 30, 19)                # 57 tokens: the single-tile
 
 @pytest.mark.parametrize("dtype,lens", [("fp32", STAGE_LENGTHS), ("bf16", STAGE_LENGTHS),
                                         ("bf16", SINGLE_TILE_LENGTHS), ("bf16", (64,)),
-                                        ("bf16", (300, 5, 140, 64, 257))])   # > 256 tokens: the key/value-sharing kernel
+                                        ("bf16", (300, 5, 140, 64, 257)),   # > 256 tokens: the key/value-sharing kernel
+                                        ("bf16", (320, 193, 129, 161))])    # its partly filled waves and query blocks
 def test_every_stage_against_oracle_pieces(sp, oracle64, dtype, lens):
     """Each kernel in isolation: its output against the oracle's piece applied to the kernel's own input
     (as the HIP path left it in the workspace), so that one kernel's rounding is not charged to the next."""
