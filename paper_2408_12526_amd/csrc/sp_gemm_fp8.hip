@@ -183,8 +183,8 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_kernel(const unsigned char* _
 
     int sa = 0;                                             // activation slot of k-tile j
     // One k-tile; the flags are compile-time, so no variant has a branch in its body.
-    //   L0 / L1: the loads of k-step 0 / 1 exist (k-tile j + 2 exists);  NEXT: k-tile j + 1 exists;  RES: k-step 1 carries the residual loads (last k-tile: the whole
-    //            ring is free after its barrier).
+    //   L0 / L1: the loads of k-step 0 / 1 exist (k-tile j + 2 exists);  NEXT: k-tile j + 1 exists;
+    //   RES: k-step 1 carries the residual loads (last k-tile: the whole ring is free after its barrier).
     auto ktile = [&](int j, auto l0_c, auto l1_c, auto next_c, auto res_c) {
         constexpr bool L0 = decltype(l0_c)::value, L1 = decltype(l1_c)::value, NEXT = decltype(next_c)::value;
         constexpr bool RES = decltype(res_c)::value;
@@ -252,7 +252,7 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_kernel(const unsigned char* _
     // iteration nobody reads the ring: each wave stages its 128 x 128 sub-tile in its own slice of it.
     if (EPI == EPI_BIAS_GELU) {
         // fp8 output, e4m3(gelu(.) * q_out): staged [128 tokens][128 bytes], chunk (feature / 16) ^ (token & 7)
-        char* slice = (char*)smem + (size_t)wave * (WT * WT);
+        char* slice8 = (char*)smem + (size_t)wave * (WT * WT);
 #pragma unroll
         for (int jj = 0; jj < TM; ++jj)
 #pragma unroll
@@ -266,14 +266,14 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_kernel(const unsigned char* _
                     int w = 0;
                     w = __builtin_amdgcn_cvt_pk_fp8_f32(r[0], r[1], w, false);
                     w = __builtin_amdgcn_cvt_pk_fp8_f32(r[2], r[3], w, true);
-                    *(int*)(slice + t * 128 + (((f >> 4) ^ (t & 7)) << 4) + (f & 15)) = w;
+                    *(int*)(slice8 + t * 128 + (((f >> 4) ^ (t & 7)) << 4) + (f & 15)) = w;
                 }
         unsigned char* dst = (unsigned char*)outv + (size_t)m * o_ss + row0 * ldo + col0;
         const int rr = lane >> 3, cc = lane & 7;
 #pragma unroll 4
         for (int q = 0; q < 16; ++q) {
             const int t = q * 8 + rr;
-            *(uint4*)(dst + (size_t)t * ldo + ((cc ^ (t & 7)) << 4)) = *(const uint4*)(slice + t * 128 + (cc << 4));
+            *(uint4*)(dst + (size_t)t * ldo + ((cc ^ (t & 7)) << 4)) = *(const uint4*)(slice8 + t * 128 + (cc << 4));
         }
         return;
     }

@@ -30,20 +30,26 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 //   erfc(4.3) = 1.2e-9, so |x| is clamped at 4.3 sqrt 2 (in the erfc term only: beyond it the term stays below 4e-9
 //   instead of growing with |x|).
 // Evaluated in fp32 the result is within 3.2e-7 of the exact function for every x (0.03 bf16 ulp at most where
-// |gelu| > 1e-3).  One quarter-rate instruction (exp2) and eleven full-rate ones: the epilogue of the FFN
+// |gelu| > 1e-3).  One quarter-rate instruction (exp2) and nine full-rate ones: the epilogue of the FFN
 // up-projection is bound by these vector instructions while the matrix cores wait (libm's erff costs several times
-// more; the rational-exponential formula 7.1.26 of Abramowitz & Stegun needs a reciprocal as well).
+// more; the rational-exponential formula 7.1.26 of Abramowitz & Stegun needs a reciprocal as well).  To get there:
+//   * the polynomial is in a = |x| directly (coefficient i carries 2^(-(i + 1) / 2)), so z is never formed, and the
+//     halving of erfc rides in the exponent: |x| erfc / 2 = a 2^(a Q'(a) - 1), the -1 being the addend of the
+//     multiply-add that forms the exponent;
+//   * clamps are median-of-three instructions (one each for the clamp of x and for max(x, 0), the latter with the
+//     largest finite float as its upper bound: fminf / fmaxf, and a median with an infinite bound, which the
+//     compiler rewrites as one of them, cost a second instruction that quiets signalling NaNs first); |.| is an
+//     operand modifier.
 __device__ inline float gelu_erf_fast(float x)
 {
-    const float ax = __builtin_fminf(__builtin_fabsf(x), 6.0811f);
-    const float z = ax * 0.70710678118654752f;
-    float q = __builtin_fmaf(2.393906887e-04f, z, -4.185345790e-03f);
-    q = __builtin_fmaf(q, z, 3.190982192e-02f);
-    q = __builtin_fmaf(q, z, -1.505803052e-01f);
-    q = __builtin_fmaf(q, z, -9.178313831e-01f);
-    q = __builtin_fmaf(q, z, -1.627967815e+00f);
-    const float e = __builtin_amdgcn_exp2f(q * z);
-    return __builtin_fmaf(-0.5f * ax, e, __builtin_fmaxf(x, 0.0f));
+    const float a = __builtin_fabsf(__builtin_amdgcn_fmed3f(x, -6.0811f, 6.0811f));
+    float q = __builtin_fmaf(2.992383634e-05f, a, -7.398715825e-04f);
+    q = __builtin_fmaf(q, a, 7.977455854e-03f);
+    q = __builtin_fmaf(q, a, -5.323817581e-02f);
+    q = __builtin_fmaf(q, a, -4.589156806e-01f);
+    q = __builtin_fmaf(q, a, -1.151147127e+00f);
+    const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(q, a, -1.0f));
+    return __builtin_fmaf(-a, e, __builtin_amdgcn_fmed3f(x, 0.0f, 3.402823466e+38f));
 }
 
 typedef __attribute__((address_space(3))) void lds_void;
