@@ -127,21 +127,28 @@ def smi_sample():
 
 
 def sampled_while(fn_busy, seconds):
-    """Run fn_busy() repeatedly on this thread for about `seconds` while a helper thread takes one amd-smi sample in
-    the middle of it."""
+    """Run fn_busy() repeatedly on this thread for about `seconds` while a helper thread takes two amd-smi readings in
+    the middle of it; the one with the higher power is returned (the tool's figures lag the load)."""
     import threading
-    box = {}
-    th = threading.Thread(target=lambda: (time.sleep(seconds * 0.3), box.update(s=smi_sample())))
+    box = []
+
+    def sampler():
+        time.sleep(seconds * 0.3)
+        for _ in range(2):
+            r = smi_sample()
+            if r and r.get("socket_power_w") is not None:
+                box.append(r)
+    th = threading.Thread(target=sampler)
     th.start()
     t0 = time.perf_counter()
     while time.perf_counter() - t0 < seconds or th.is_alive():
         fn_busy()
     th.join()
-    return box.get("s")
+    return max(box, key=lambda r: r["socket_power_w"]) if box else None
 
 
 def power_leg(sp, torch, forward_burst):
-    """Package power and shader clock (one amd-smi sample in the middle of each run) under: the matrix-instruction
+    """Package power and shader clock (amd-smi readings in the middle of each run) under: the matrix-instruction
     loop on operands in {0, 1}, the same loop on random mantissas (bf16 and fp8), and the burst forward.  Shows which
     part of the gap to the published matrix-core peak is the package power limit: the loop does nothing but matrix
     instructions, and its rate follows the clock the limit allows for the data it multiplies."""
@@ -149,22 +156,31 @@ def power_leg(sp, torch, forward_burst):
     out = {}
 
     def with_sample(name, fn, delay):
-        box = {}
-        th = threading.Thread(target=lambda: (time.sleep(delay), box.update(s=smi_sample())))
+        # two readings, the one with the higher power kept: the tool's figures lag the load by a few hundred ms, and
+        # the first launch of a kernel can start late
+        box = []
+
+        def sampler():
+            time.sleep(delay)
+            for _ in range(2):
+                r = smi_sample()
+                if r and r.get("socket_power_w") is not None:
+                    box.append(r)
+        th = threading.Thread(target=sampler)
         th.start()
         val = fn()
         th.join()
-        out[name] = {"result": val, "smi": box.get("s")}
+        out[name] = {"result": val, "smi": max(box, key=lambda r: r["socket_power_w"]) if box else None}
 
     out["idle"] = {"smi": smi_sample()}
     for name, kind in (("mfma_loop_bf16_operands_0_or_1", 0), ("mfma_loop_bf16_operands_random", 1),
                        ("mfma_loop_fp8_operands_0_or_1", 2), ("mfma_loop_fp8_operands_random", 3)):
-        with_sample(name, lambda kind=kind: {"tflops": sp.sp_probe_mfma_rate(kind, 1500)}, 0.8)
+        with_sample(name, lambda kind=kind: {"tflops": sp.sp_probe_mfma_rate(kind, 2000)}, 0.7)
 
     def burst():
         t0 = time.perf_counter()
         n = 0
-        while time.perf_counter() - t0 < 2.0:
+        while time.perf_counter() - t0 < 2.5:
             for _ in range(20):
                 forward_burst()
             torch.cuda.synchronize()
