@@ -404,18 +404,21 @@ __device__ __forceinline__ void attention_short_body(char* lds, int bid, const b
                     const int c = 8 * (v >> 2) + (v & 3);
                     bool ok = g4 < L - kt0 - c;
                     if (v < 4) ok = ok && g4 >= -kt0 - c;
-                    const float sv = ok ? sc[v] * sl2 : -INFINITY;
+                    const float sv = ok ? sc[v] : -INFINITY;
                     sc[v] = sv;
                     mx = fmaxf(mx, sv);
                 }
                 mx = max_across_halves(mx);
-                const float alpha = exp2_raw(mrun[qb] - mx);
+                // (running maximum on the raw scores; the 1/sqrt(d) log2(e) factor rides in the multiply-add in front of
+                // the exponential)
+                const float alpha = exp2_raw((mrun[qb] - mx) * sl2);
                 mrun[qb] = mx;
+                const float nm = -mx * sl2;
                 float psum = 0.f;
                 bf16x8 pf[2];
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const float p = exp2_raw(sc[v] - mx);
+                    const float p = exp2_raw(fmaf(sc[v], sl2, nm));
                     psum += p;
                     pf[v >> 3][v & 7] = (bf16)p;
                 }
