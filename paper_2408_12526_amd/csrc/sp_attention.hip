@@ -25,19 +25,9 @@ static_assert(kLongTileBytes % 16 == 0 && 4 * 32 * kOutPitch <= kLongLdsBytes, "
 // arguments here are <= 0, and what underflows is flushed to zero.)
 __device__ inline float exp2_raw(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// The value of lane l ^ 32, for both halves of the wave at once: v_permlane32_swap exchanges lanes 32-63 of its first
-// operand with lanes 0-31 of its second, so with x in both, `lo` ends up as x[l % 32] and `hi` as x[32 + l % 32] in every
-// lane.  (One instruction instead of the LDS round trip of a general lane permutation.  The instruction needs two idle
-// issue slots after a vector write of its operands, which the compiler cannot know about inside an asm statement:
-// hence the s_nop in front; the one behind keeps the same distance to the first reader.)
-__device__ inline void halves(float x, float& lo, float& hi)
-{
-    lo = x;
-    hi = x;
-    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(lo), "+v"(hi));
-}
-__device__ inline float max_across_halves(float x) { float lo, hi; halves(x, lo, hi); return fmaxf(lo, hi); }
-__device__ inline float sum_across_halves(float x) { float lo, hi; halves(x, lo, hi); return lo + hi; }
+// A query's keys sit in lanes l and l ^ 32: maximum and sum over the two (every lane active).
+__device__ inline float max_across_halves(float x) { float lo = x, hi = x; swap_halves(lo, hi); return fmaxf(lo, hi); }
+__device__ inline float sum_across_halves(float x) { float lo = x, hi = x; swap_halves(lo, hi); return lo + hi; }
 
 // eight bf16 values (one 16-byte chunk of an output row) -> eight e4m3 codes of value * qscale
 __device__ inline uint2 chunk_to_fp8(uint4 c, float qscale)
@@ -683,16 +673,14 @@ __global__ __launch_bounds__(512, 4) void attention_first_fold_kernel(const bf16
         float* row = sc + hh * LP;
         float mx = -INFINITY;
         for (int t = lane; t < L; t += 64) mx = fmaxf(mx, row[t]);
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+        mx = wave_max(mx);
         float sum = 0.f;
         for (int t = lane; t < L; t += 64) {
             const float e = exp2_raw(row[t] - mx);
             row[t] = e;
             sum += e;
         }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+        sum = wave_sum(sum);
         const float inv = 1.0f / sum;
         for (int t = lane; t < L16; t += 64) pT[hh * PP + t] = (bf16)(t < L ? row[t] * inv : 0.f);
     }

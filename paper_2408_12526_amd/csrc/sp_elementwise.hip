@@ -10,13 +10,6 @@ namespace {
 
 constexpr int kMaxChunks = 4;  // 8-element chunks per lane: hidden <= 64 * 8 * kMaxChunks
 
-__device__ inline float wave_sum(float v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
-}
-
 __device__ inline void load8(const float* p, float (&v)[8])
 {
     const f32x4 a = *(const f32x4*)p, b = *(const f32x4*)(p + 4);
@@ -342,10 +335,17 @@ struct PoolerWeights {
             if (s < nseq) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
+                    // sum over the eight lanes that share lane % 8: other half of the row, other row of the pair,
+                    // other half of the wave
                     float a = acc[s][e];
-                    a += __shfl_xor(a, 8);
-                    a += __shfl_xor(a, 16);
-                    a += __shfl_xor(a, 32);
+                    a += dpp_moved<0x128>(a);               // row_ror:8
+                    float lo = a, hi = a;
+                    swap_rows(lo, hi);
+                    a = lo + hi;
+                    lo = a;
+                    hi = a;
+                    swap_halves(lo, hi);
+                    a = lo + hi;
                     if (rl == 0) red[(wv * kSeqPerWg + s) * 64 + c8 + e] = a;
                 }
             }

@@ -52,6 +52,59 @@ __device__ inline float gelu_erf_fast(float x)
     return __builtin_fmaf(-a, e, __builtin_amdgcn_fmed3f(x, 0.0f, 3.402823466e+38f));
 }
 
+// ---- reductions over the 64 lanes of a wave, result in every lane -------------------------------------------------
+// Inside a row of 16 lanes the second operand of each step comes through the data-parallel-primitive path of the
+// instruction itself (neighbour in the pair, other pair of the quad, mirror image in the half row, mirror image in the
+// row: after each step every lane of the growing group holds the group's result); rows 0|1 and 2|3, then the two halves
+// of the wave, are exchanged by the row / half swap instructions (both operands hold the value; afterwards one has the
+// even rows' (lower half's) data in every row (half), the other the odd rows' (upper half's)).  Eight instructions
+// where six general lane permutations through LDS (`__shfl_xor`) take about forty, and no LDS round trips on the
+// critical path.  Every lane of the wave must be active.  (The swaps are inline assembly with the two idle issue slots
+// the hardware wants after a vector write of their operands: this toolchain's builtins return their first result
+// twice.)
+template <int CTRL>
+__device__ inline float dpp_moved(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+__device__ inline void swap_rows(float& a, float& b)       // odd rows of a <-> even rows of b
+{
+    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+__device__ inline void swap_halves(float& a, float& b)     // lanes 32-63 of a <-> lanes 0-31 of b
+{
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+constexpr int kDppPair = 0xB1, kDppQuad = 0x4E, kDppHalfRowMirror = 0x141, kDppRowMirror = 0x140;
+__device__ inline float wave_sum(float v)
+{
+    v += dpp_moved<kDppPair>(v);           // quad_perm [1, 0, 3, 2]
+    v += dpp_moved<kDppQuad>(v);           // quad_perm [2, 3, 0, 1]
+    v += dpp_moved<kDppHalfRowMirror>(v);
+    v += dpp_moved<kDppRowMirror>(v);
+    float a = v, b = v;
+    swap_rows(a, b);
+    v = a + b;
+    a = v;
+    b = v;
+    swap_halves(a, b);
+    return a + b;
+}
+__device__ inline float wave_max(float v)
+{
+    v = __builtin_fmaxf(v, dpp_moved<kDppPair>(v));
+    v = __builtin_fmaxf(v, dpp_moved<kDppQuad>(v));
+    v = __builtin_fmaxf(v, dpp_moved<kDppHalfRowMirror>(v));
+    v = __builtin_fmaxf(v, dpp_moved<kDppRowMirror>(v));
+    float a = v, b = v;
+    swap_rows(a, b);
+    v = __builtin_fmaxf(a, b);
+    a = v;
+    b = v;
+    swap_halves(a, b);
+    return __builtin_fmaxf(a, b);
+}
+
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) const void gbl_void;
 
