@@ -61,14 +61,16 @@ __device__ inline void ln_row_store(float (&v)[MAXC][8], int nch, int lane, int 
         if (lane + 64 * i < nch)
 #pragma unroll
             for (int e = 0; e < 8; ++e) s += v[i][e];
-    const float mean = wave_sum(s) / (float)H;
+    // (1 / H once and the hardware reciprocal square root: a correctly rounded division is ten dependent instructions)
+    const float inv_h = __builtin_amdgcn_rcpf((float)H);
+    const float mean = wave_sum(s) * inv_h;
     float q = 0.f;
 #pragma unroll
     for (int i = 0; i < MAXC; ++i)
         if (lane + 64 * i < nch)
 #pragma unroll
             for (int e = 0; e < 8; ++e) { const float d = v[i][e] - mean; q += d * d; }
-    const float inv = 1.0f / sqrtf(wave_sum(q) / (float)H + eps);
+    const float inv = __builtin_amdgcn_rsqf(wave_sum(q) * inv_h + eps);
 #pragma unroll
     for (int i = 0; i < MAXC; ++i) {
         const int c = lane + 64 * i;
@@ -510,7 +512,8 @@ __global__ __launch_bounds__(256) void head_small_kernel(const char* arena, size
         sum = wave_sum(sum);
         if (lane == 0) wsum[0][wv] = sum;
         __syncthreads();
-        const float mean = (wsum[0][0] + wsum[0][1] + wsum[0][2] + wsum[0][3]) / (float)H;
+        const float inv_h = __builtin_amdgcn_rcpf((float)H);
+        const float mean = (wsum[0][0] + wsum[0][1] + wsum[0][2] + wsum[0][3]) * inv_h;
         float q = 0.f;
 #pragma unroll
         for (int j = 0; j < MAXJ; ++j)
@@ -518,7 +521,7 @@ __global__ __launch_bounds__(256) void head_small_kernel(const char* arena, size
         q = wave_sum(q);
         if (lane == 0) wsum[1][wv] = q;
         __syncthreads();
-        const float inv = 1.0f / sqrtf((wsum[1][0] + wsum[1][1] + wsum[1][2] + wsum[1][3]) / (float)H + eps);
+        const float inv = __builtin_amdgcn_rsqf((wsum[1][0] + wsum[1][1] + wsum[1][2] + wsum[1][3]) * inv_h + eps);
 #pragma unroll
         for (int j = 0; j < MAXJ; ++j) {
             const int i = tid + 256 * j;
