@@ -205,8 +205,8 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
         };
         // k-tile t: activations in slot 2 t mod 5, weights in slot (2 t + 1) mod 5.  Start: the wave's 128 bias values
         // (one wave-load, both lane halves fetch the same 512 bytes, into the part of slot 4 that only this wave's own
-        // first load of the activation tile of k-tile 2 overwrites later), then both tiles of k-tiles 0 and 1 (Kd is a
-        // multiple of 128, so there are at least two k-tiles).
+        // first load of the activation tile of k-tile 2 overwrites later), then both tiles of k-tiles 0 and 1 (the reduction depth is
+        // at least 256: four k-tiles or more).
         float* seed_lds = (float*)(smem + 4 * SLOT + wave * 64);
         request_bias(seed_lds);
 #pragma unroll
@@ -239,20 +239,24 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
         //   steps 1, 2: activation tile of k-tile j + 2            -> slot sa + 4 (weights of k-tile j - 1)
         //   step 3, after the barrier: first half of the weight tile of k-tile j + 2 -> slot sa (idle from here on)
         // The barrier of step 3 needs k-tile j + 1 complete; the only younger loads are the eight of the activation
-        // tile of k-tile j + 2.  STEADY: 1 <= j <= nk - 3, every load exists, no branches in the body.
-        auto ktile = [&](int j, auto steady_c) {
-            constexpr bool STEADY = decltype(steady_c)::value;
+        // tile of k-tile j + 2.
+        // The variants (first k-tile, steady state, last two) are compile-time instances: none has a branch in its body,
+        // and the scheduling fences fix the interleaving of loads, LDS reads and MFMAs in all of them.
+        //   L0: the loads of step 0 exist (j >= 1 and k-tile j + 1 exists);  L2: those of steps 1 to 3 (k-tile j + 2 exists);
+        //   NEXT: k-tile j + 1 exists.
+        auto ktile = [&](int j, auto l0_c, auto l2_c, auto next_c) {
+            constexpr bool L0 = decltype(l0_c)::value, L2 = decltype(l2_c)::value, NEXT = decltype(next_c)::value;
             auto rot = [](int s0, int d) { const int t = s0 + d; return t >= 5 ? t - 5 : t; };
             const int s1 = rot(sa, 1), s2 = rot(sa, 2), s3 = rot(sa, 3), s4 = rot(sa, 4);
 #pragma unroll
             for (int s = 0; s < STEPS; ++s) {
                 if (s == STEPS - 1) {
-                    if (STEADY || j + 2 < nk) wait_vmcnt<8>(); else if (j + 1 < nk) wait_vmcnt<0>();
+                    if (L2) wait_vmcnt<8>(); else if (NEXT) wait_vmcnt<0>();
                     barrier_lds();
                 }
                 __builtin_amdgcn_sched_barrier(0);
-                const bool do_loads = STEADY || (s == 0 ? j >= 1 && j + 1 < nk : j + 2 < nk);
-                const bool do_frags = s + 1 < STEPS || STEADY || j + 1 < nk;
+                const bool do_loads = s == 0 ? L0 : L2;
+                const bool do_frags = s + 1 < STEPS || NEXT;
                 const int xslot = s + 1 < STEPS ? sa : s2, wslot = s + 1 < STEPS ? s1 : s3;
                 const int kg = 2 * (s + 1 < STEPS ? s + 1 : 0) + g;
                 constexpr int NF = TM + TN, NM = TM * TN;
@@ -284,14 +288,17 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
             }
             sa = s2;
         };
-        int jt = 0;
-        ktile(jt++, std::false_type{});
-        for (; jt < nk - 2; ++jt) ktile(jt, std::true_type{});
-        for (; jt < nk; ++jt) {
+        {
+            constexpr std::true_type Y{};
+            constexpr std::false_type N{};
+            // (the launcher gives this tile only reduction depths of at least 256: four k-tiles or more)
+            ktile(0, N, Y, Y);
+            for (int jt = 1; jt < nk - 2; ++jt) ktile(jt, Y, Y, Y);
+            ktile(nk - 2, Y, N, Y);
             // from here on only the two slots of the last k-tile are read: the first half of the residual rows goes
             // into two of the others
-            if (EPI == EPI_BIAS_RESIDUAL && jt == nk - 1) issue_residual(0);
-            ktile(jt, std::false_type{});
+            if (EPI == EPI_BIAS_RESIDUAL) issue_residual(0);
+            ktile(nk - 1, N, N, N);
         }
     } else {
         float* seed_lds = (float*)((char*)smem + G::ring_bytes) + wave * 256;   // one kilobyte per wave behind the ring
@@ -578,7 +585,7 @@ hipError_t launch_bf16(const sp_model* M, const void* A, int lda, size_t w_off, 
     // a feature tile must lie entirely on one side of n_split
     // (a grid of fewer large tiles than compute units leaves part of the chip idle: smaller tiles then; measured on the
     // batch-32 workload, one student: 0.285 -> 0.236 ms per call)
-    if (mrows % 256 == 0 && mrows >= 2048 && N % 256 == 0 && n_split % 256 == 0 &&
+    if (mrows % 256 == 0 && mrows >= 2048 && N % 256 == 0 && n_split % 256 == 0 && Kd >= 256 &&
         (long)k * (mrows / 256) * (N / 256) >= kLargeTileMinWorkgroups) {
         return launch_bf16_tile<256, 256, EPI>(SP_ARGS);
     }
