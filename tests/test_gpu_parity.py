@@ -276,7 +276,8 @@ LARGE_OTHER = {
                                        classes=2, dtype="bf16"),
     "512D_ffn1280": synth.StudentShape(K=2, layers=2, hidden=512, heads=8, ffn=1280, vocab=1000, max_pos=128,
                                        classes=3, dtype="bf16"),
-    # the shortest reduction the large tile can meet: two k-tiles (FFN up-projection of a 128-wide student)
+    # reduction depth 128 (two k-tiles): such projections go to the 128 x 128 tile even in large calls; the shortest
+    # reduction the large tile meets is depth 256 (four k-tiles: the 256-wide student above)
     "128D_ffn256": synth.StudentShape(K=3, layers=2, hidden=128, heads=2, ffn=256, vocab=1000, max_pos=128,
                                       classes=2, dtype="bf16"),
 }
