@@ -167,6 +167,37 @@ def test_first_token_last_layer_matches_all_tokens(sp, oracle64):
     assert rel_err(got[False], got[True]) < 1e-2
 
 
+def test_sequences_longer_than_512_tokens(sp, oracle64):
+    """Sequences beyond 512 tokens: three and four 256-query workgroups per (sequence, head) in the key/value-sharing
+    attention body, a dozen key tiles per query block; the folded first-token attention does not take them (its
+    score buffer is sized for 512), so the last layer runs on every token although the call is large enough.  Whole
+    forward against the oracle, every sequence, each k_active; and the attention stage by itself."""
+    shape = synth.StudentShape(K=2, layers=2, hidden=256, heads=4, ffn=512, vocab=200, max_pos=1024, classes=3,
+                               dtype="bf16")
+    rng = np.random.default_rng(29)
+    lengths = np.array([700, 513, 40, 1, 1000, 257], dtype=np.int32)
+    ids = synth.make_ids(rng, int(lengths.sum()), shape.vocab)
+    blob = synth.make_weights(rng, shape, std=0.05, ln_random=True, qk_std=0.12)
+    st = sp.Students(sp.config_from_shape(shape), blob)
+    d_ids, d_cu, cu = gpu_inputs(lengths, ids, sp)
+    ow = oracle_weights(blob, shape)
+    for k in (1, 2):
+        got = st.sp_forward(d_ids, d_cu, int(lengths.max()), k).cpu().numpy().astype(np.float64)
+        want = oracle64.forward(ocfg(shape), ow, ids, cu, k)
+        check_logits(got, want, shape, f"long sequences k_active={k}")
+    T, B = int(cu[-1]), len(lengths)
+    ws = st.sp_forward_partial(d_ids, d_cu, int(lengths.max()), shape.K, 1)
+    qkv, att = st.read_activation(ws, "qkv", T, B, shape.K), st.read_activation(ws, "att", T, B, shape.K)
+    for m in range(shape.K):
+        for b in range(B):
+            rows = slice(int(cu[b]), int(cu[b + 1]))
+            a = qkv[m][rows]
+            H = shape.hidden
+            e = rel_err(att[m][rows], oracle64.attention(a[:, :H], a[:, H:2 * H], a[:, 2 * H:], shape.heads))
+            assert e < 1.2e-2, f"student {m}, sequence of {lengths[b]} tokens: attention rel err {e:.3e}"
+    st.close()
+
+
 def test_folded_first_token_attention_against_the_definition(sp, oracle64):
     """The first-token last layer never forms keys and values (the query is folded through the key projection, the
     value projection is applied to the weighted mean of the token rows).  Its attention output is checked against the
