@@ -3,9 +3,6 @@
 // accumulate) with both operands staged through LDS; the fp32 kernel is a plain FMA tile
 // kernel used by the fp32 path.
 #include <atomic>
-#ifndef SP_NS64
-#define SP_NS64 3
-#endif
 #include <type_traits>
 
 #include "sp_internal.h"
@@ -29,9 +26,9 @@ __device__ inline float gelu_erf(float u) { return 0.5f * u * (1.0f + erff(u * 0
 //   * LDS tile = [row][8 slots of 16 B]; slot s of row r holds k-chunk s ^ ((r >> 1) & 7).  The 16 lanes that
 //     a ds_read_b128 serves per cycle then hit 16 distinct 16-byte bank groups (no bank conflicts), and the
 //     global side still reads whole 128-byte rows.
-//   * two-stage ring over the reduction dimension.  The loads that refill a stage are spread over the MFMAs of
-//     two k-steps (a burst of loads stalls the issuing wave behind the address unit's queue), and the
-//     fragments of k-step s + 1 are read while step s multiplies.  One barrier per 64-wide k-tile, placed where
+//   * ring of two stages (128 x 128 tile) or three (64 x 64) over the reduction dimension.  The loads that refill
+//     a stage are spread over the MFMAs of two k-steps (a burst of loads stalls the issuing wave behind the
+//     address unit's queue), and the fragments of k-step s + 1 are read while step s multiplies.  One barrier per 64-wide k-tile, placed where
 //     every wave already holds its last fragments of the tile in registers.
 //   * 256 x 256 tile: a wave stalls on its direct-to-LDS loads once more than about four of them per k-step are
 //     issued (the address unit's queue), and two stages force sixteen loads per k-tile into the two k-steps that
@@ -42,8 +39,9 @@ __device__ inline float gelu_erf(float u) { return 0.5f * u * (1.0f + erff(u * 0
 //     whole 16-byte-per-lane row segments.  Staged rows are unpadded and their 16-byte chunks XOR-swizzled by row,
 //     which lets the residual rows arrive by the same direct-to-LDS loads: half of them are requested before the
 //     last k-tile (into the ring stage that is already idle), the rest while the first half is being processed.
-//   * the accumulators start from the bias values, which are the first loads of the kernel (sixteen dependent
-//     global loads in the epilogue cost several microseconds per tile, and so the adds disappear as well).
+//   * the accumulators start from the bias values (sixteen dependent global loads in the epilogue cost several
+//     microseconds per tile, and so the adds disappear as well); they come in through LDS by the first
+//     direct-to-LDS load of the kernel (see request_bias).
 // -------------------------------------------------------------------------------------
 template <int BM, int BN>
 struct GemmTile {
@@ -51,7 +49,7 @@ struct GemmTile {
     // ring depth: three stages for the 64 x 64 tile (measured, 64 rows x 8 students: FFN down, depth 3072, 26.4 -> 17.5 us;
     // FFN up 11.2 -> 10.2 us; four stages no better; one student: no change, a lone workgroup per compute unit is
     // bound by that unit's load path at about 28 B per cycle either way), two for the 128 x 128 tile
-    static constexpr int NS = BM == 64 ? SP_NS64 : 2;
+    static constexpr int NS = BM == 64 ? 3 : 2;
     static constexpr int WTM = BM / 2, WTN = BN / 2;        // wave tile
     // The 256 x 256 tile keeps a ring of five operand tiles (256 rows x 64 reduction elements, 32 KB each: the whole
     // LDS) instead of two stages of an activation and a weight tile; the smaller tiles use the two-stage ring.
