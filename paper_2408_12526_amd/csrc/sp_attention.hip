@@ -579,38 +579,77 @@ __global__ __launch_bounds__(256) void head_gemm_kernel(const bf16* __restrict__
         *(uint4*)(o + (size_t)(r0 + rr) * ldo) = *(const uint4*)(stg + (r0 + rr) * PITCH + cc * 16);
 }
 
-// One workgroup (eight waves) per (student, sequence).
-//   scores: heads x tokens tiles on the matrix cores; the waves split the feature (reduction) range, each keeps its
-//           slice of the folded queries in registers, and the eight partial tiles are added in a fixed order;
-//   softmax per head;
-//   weighted mean rows: features x heads tiles on the matrix cores, each wave owns HEADS / 4 blocks of 32 features.
-// The token rows x are the only large global reads (twice, the second time from cache).
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// Maximum / sum over the four lanes l % 16 + {0, 16, 32, 48} (every lane active).
+__device__ inline float max_across_rows(float v)
+{
+    float a = v, b = v;
+    swap_rows(a, b);
+    v = fmaxf(a, b);
+    a = v;
+    b = v;
+    swap_halves(a, b);
+    return fmaxf(a, b);
+}
+__device__ inline float sum_across_rows(float v)
+{
+    float a = v, b = v;
+    swap_rows(a, b);
+    v = a + b;
+    a = v;
+    b = v;
+    swap_halves(a, b);
+    return a + b;
+}
+
+// One workgroup (eight waves) per (student, sequence); the sequence's token rows x are read from global memory once, in
+// tiles of 32 tokens, and every wave touches only its own eighth of the features (FW = H / 8 of them):
+//   scores: heads x tokens on the matrix cores (16 x 16 x 32 shape: two blocks of 16 tokens, FW / 32 steps of 32
+//           features); the token rows arrive in registers in operand layout (lane: token l % 16, eight features); the
+//           waves' partial tiles are added in a fixed order through LDS;
+//   weighted rows: features x heads, reduction over the tile's 32 tokens in one instruction.  That operand wants eight
+//           tokens of one feature per lane, so the wave writes its registers to its own LDS slab (16-byte chunks
+//           XOR-swizzled by the token) and reads them back as 4-byte pieces (two neighbouring features) of eight
+//           tokens, unzipped into two operands: row r of operand c is feature 2 r + c of a block of 32.  The softmax
+//           is the running one (maximum and sum per head, accumulators rescaled when the maximum moves); every wave
+//           keeps the statistics of all heads: lane l holds head l % 16 and tokens 8 (l / 16) ... + 8 of the tile.
+// The next tile's rows are requested as soon as the current ones are in LDS.  Two workgroup barriers per tile; about
+// 66 KB of LDS at hidden width 768 and at most 128 registers, so two workgroups share a compute unit and one's
+// start-up and barrier waits are covered by the other.
 //   qt   [m][b][head][H]   folded queries (row stride HEADS * H)
 //   xbar [m][b][head][H]   output; rows b in [B, gridDim.x) are zeroed (they feed padded projections)
 constexpr int kFoldMaxLen = 512;
 constexpr int kFoldWaves = 8;
-constexpr size_t kFoldPartBytes = (size_t)kFoldWaves * 16 * 32 * 4;
-constexpr size_t kFoldMaxSmem =                               // 16 heads, longest sequence
-    kFoldPartBytes + (size_t)16 * (kFoldMaxLen + 4) * 4 + (size_t)16 * (kFoldMaxLen + 8) * 2;
+template <int HEADS>
+struct FoldLds {
+    static constexpr int H = HEADS * kD, FW = H / kFoldWaves;   // features per wave
+    static constexpr int SCP = 36;                          // pitch of a head's 32 scores (floats)
+    static constexpr size_t slab_bytes = (size_t)32 * FW * 2;   // per wave: 32 tokens x FW features
+    static constexpr size_t bytes = kFoldWaves * (slab_bytes + 16 * 32 * 4) + (size_t)16 * SCP * 4;
+    static_assert(FW % 32 == 0 && HEADS <= 16 && bytes <= 160 * 1024, "whole reduction steps per wave, heads in one block");
+};
 
 template <int HEADS>
-__global__ __launch_bounds__(512, 4) void attention_first_fold_kernel(const bf16* __restrict__ x,
+__global__ __launch_bounds__(512, HEADS == 16 ? 2 : 4) void attention_first_fold_kernel(const bf16* __restrict__ x,
                                                                       const bf16* __restrict__ qt,
                                                                       bf16* __restrict__ xbar,
                                                                       const int32_t* __restrict__ cu, int B, int Tn,
-                                                                      int rows, int crows, int max_seqlen, int LP, int PP)
+                                                                      int rows, int crows, int max_seqlen)
 {
-    constexpr int H = HEADS * kD;
-    constexpr int KS = H / (kFoldWaves * 16);               // 16-feature reduction steps per wave (scores)
+    using F = FoldLds<HEADS>;
+    constexpr int H = F::H, FW = F::FW, SCP = F::SCP, NW = kFoldWaves;
+    constexpr int KS = FW / 32;                             // 32-feature steps (scores) = 32-feature blocks (output)
+    constexpr int PITCH = FW * 2;                           // slab row, bytes
     extern __shared__ uint4 fold_smem[];
-    float* part = (float*)fold_smem;                        // [waves][16][32] partial score tiles
-    float* sc = part + kFoldWaves * 16 * 32;                // [HEADS][LP] scores
-    bf16* pT = (bf16*)(sc + HEADS * LP);                    // [HEADS][PP] probabilities, zero beyond the sequence
+    float* part = (float*)((char*)fold_smem + NW * F::slab_bytes);   // [waves][16][32] partial score tiles
+    float* sc = part + NW * 16 * 32;                        // [16][SCP] scores of the current tile, log2 units
     const int m = blockIdx.y, b = blockIdx.x;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    char* slab = (char*)fold_smem + wave * F::slab_bytes;   // this wave's features of the tile: [token][FW / 8 chunks]
     bf16* xb = xbar + ((size_t)m * crows + b) * HEADS * H;
     if (b >= B) {
-        for (int c = tid; c < HEADS * H / 8; c += 64 * kFoldWaves) ((uint4*)xb)[c] = make_uint4(0, 0, 0, 0);
+        for (int c = tid; c < HEADS * H / 8; c += 64 * NW) ((uint4*)xb)[c] = make_uint4(0, 0, 0, 0);
         return;
     }
     int t0 = cu[b], t1 = cu[b + 1];
@@ -619,125 +658,123 @@ __global__ __launch_bounds__(512, 4) void attention_first_fold_kernel(const bf16
     L = L < 1 ? 1 : L;
     L = L > max_seqlen ? max_seqlen : L;
     L = L > Tn - t0 ? Tn - t0 : L;
-    const bf16* xs = x + ((size_t)m * rows + t0) * H;       // the sequence's token rows
-    const int j31 = lane & 31, g = lane >> 5;
+    const int l16 = lane & 15, kg = lane >> 4;
+    const bf16* xw = x + ((size_t)m * rows + t0) * H + wave * FW + 8 * kg;   // this lane's features of the first token
+    const int nt = (L + 31) >> 5;
 
-    // scores[head][token] = (q~[head] . x[token]) / 8, in log2 units
+    // folded-query operands: row = head, the wave's features in steps of 32 (lane: eight of them)
     bf16x8 fq[KS];
     {
-        const bf16* qr = qt + (((size_t)m * crows + b) * HEADS + (j31 < HEADS ? j31 : 0)) * H + wave * (H / kFoldWaves) + 8 * g;
+        const bf16* qr = qt + (((size_t)m * crows + b) * HEADS + (l16 < HEADS ? l16 : 0)) * H + wave * FW + 8 * kg;
 #pragma unroll
         for (int st = 0; st < KS; ++st) {
-            fq[st] = *(const bf16x8*)(qr + 16 * st);
-            if (j31 >= HEADS) {
+            fq[st] = *(const bf16x8*)(qr + 32 * st);
+            if (l16 >= HEADS) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) fq[st][e] = (bf16)0.f;
             }
         }
     }
-    const float scale = 0.125f * 1.44269504088896341f;
-    // (the rows of the next tile are requested before the current tile is multiplied and reduced)
-    bf16x8 fx[KS];
+    // token rows of a tile in operand layout: block nb holds tokens 16 nb + l16.  Rows beyond the sequence repeat its
+    // last row (they get probability zero).
+    bf16x8 xr[2][KS];
     auto load_tile = [&](int tile) {
-        const int tok = tile * 32 + j31;
-        const bf16* xr = xs + (size_t)(tok < L ? tok : L - 1) * H + wave * (H / kFoldWaves) + 8 * g;
 #pragma unroll
-        for (int st = 0; st < KS; ++st) fx[st] = *(const bf16x8*)(xr + 16 * st);
+        for (int nb = 0; nb < 2; ++nb) {
+            int tok = tile * 32 + 16 * nb + l16;
+            tok = tok < L ? tok : L - 1;
+#pragma unroll
+            for (int st = 0; st < KS; ++st) xr[nb][st] = *(const bf16x8*)(xw + (size_t)tok * H + 32 * st);
+        }
     };
     load_tile(0);
-    for (int tile = 0; tile * 32 < L; ++tile) {
-        f32x16 acc;
+
+    const float scale = 0.125f * 1.44269504088896341f;
+    f32x4 acc[2 * KS];                                      // [block of 32 features][c]: feature 2 row + c, column = head
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+    for (int a = 0; a < 2 * KS; ++a) acc[a] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float mrun = -INFINITY, lrun = 0.f;
+    for (int tile = 0; tile < nt; ++tile) {
+        // partial scores[head][token] over this wave's features
+        f32x4 sa[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
         for (int st = 0; st < KS; ++st)
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[st], fx[st], acc, 0, 0, 0);   // rows: heads, columns: tokens
-        if ((tile + 1) * 32 < L) load_tile(tile + 1);
 #pragma unroll
-        for (int v = 0; v < 8; ++v)                         // rows 0..15 of the tile
-            part[(wave * 16 + 8 * (v / 4) + 4 * g + v % 4) * 32 + j31] = acc[v];
-        __syncthreads();
+            for (int nb = 0; nb < 2; ++nb)
+                sa[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fq[st], xr[nb][st], sa[nb], 0, 0, 0);   // rows: heads, columns: tokens
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) part[(wave * 16 + 4 * kg + v) * 32 + 16 * nb + l16] = sa[nb][v];
+        // the rows into the wave's slab: chunk ch of token r sits in slot ch ^ ((r / 2) % 4).  (The wave's previous
+        // reads of the slab are behind it: LDS accesses of one wave execute in order.)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int st = 0; st < KS; ++st)
+                *(bf16x8*)(slab + (16 * nb + l16) * PITCH + (((4 * st + kg) ^ ((l16 >> 1) & 3)) << 4)) = xr[nb][st];
+        __builtin_amdgcn_sched_barrier(0);                  // (the next rows take over the registers of these)
+        if (tile + 1 < nt) load_tile(tile + 1);
+        barrier_lds();
         {
             const int hh = tid >> 5, t = tid & 31;          // 16 x 32 sums, one per thread, waves in a fixed order
             float sum = 0.f;
 #pragma unroll
-            for (int w = 0; w < kFoldWaves; ++w) sum += part[(w * 16 + hh) * 32 + t];
-            if (hh < HEADS && tile * 32 + t < L) sc[hh * LP + tile * 32 + t] = sum * scale;
+            for (int w = 0; w < NW; ++w) sum += part[(w * 16 + hh) * 32 + t];
+            sc[hh * SCP + t] = tile * 32 + t < L ? sum * scale : -INFINITY;
         }
-        __syncthreads();
-    }
+        barrier_lds();
 
-    // softmax over the sequence, one wave per head at a time; probabilities as bf16, zero up to a multiple of 16 tokens
-    const int L16 = (L + 15) & ~15;
-    for (int hh = wave; hh < HEADS; hh += kFoldWaves) {
-        float* row = sc + hh * LP;
+        // xbar^T[feature][head] += sum_t x[t][feature] p[head][t]
+        const float* sr = sc + (l16 < HEADS ? l16 : 0) * SCP + 8 * kg;
+        const f32x4 s0 = *(const f32x4*)sr, s1 = *(const f32x4*)(sr + 4);
+        float p[8];
         float mx = -INFINITY;
-        for (int t = lane; t < L; t += 64) mx = fmaxf(mx, row[t]);
-        mx = wave_max(mx);
-        float sum = 0.f;
-        for (int t = lane; t < L; t += 64) {
-            const float e = exp2_raw(row[t] - mx);
-            row[t] = e;
-            sum += e;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            p[e] = s0[e];
+            p[4 + e] = s1[e];
+            mx = fmaxf(mx, fmaxf(s0[e], s1[e]));
         }
-        sum = wave_sum(sum);
-        const float inv = 1.0f / sum;
-        for (int t = lane; t < L16; t += 64) pT[hh * PP + t] = (bf16)(t < L ? row[t] * inv : 0.f);
+        mx = fmaxf(mrun, max_across_rows(mx));              // finite: the tile has at least one token of the sequence
+        const float alpha = exp2_raw(mrun - mx);            // first tile: exp2(-inf) = 0
+        mrun = mx;
+        float ls = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            p[e] = exp2_raw(p[e] - mx);
+            ls += p[e];
+        }
+        lrun = fmaf(lrun, alpha, ls);
+#pragma unroll
+        for (int a = 0; a < 2 * KS; ++a) acc[a] *= alpha;
+        bf16x8 fp;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) fp[e] = (bf16)(l16 < HEADS ? p[e] : 0.f);
+#pragma unroll
+        for (int gq = 0; gq < KS; ++gq) {
+            bf16x2 xv[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e)                     // token 8 kg + e of the tile: (token / 2) % 4 = e / 2
+                xv[e] = *(const bf16x2*)(slab + (8 * kg + e) * PITCH + (((4 * gq + (l16 >> 2)) ^ (e >> 1)) << 4) + (l16 & 3) * 4);
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                bf16x8 fx;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) fx[e] = xv[e][c];
+                acc[2 * gq + c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fx, fp, acc[2 * gq + c], 0, 0, 0);   // rows: features, columns: heads
+            }
+        }
     }
-    __syncthreads();
-
-    // xbar^T[feature][head] = sum_t x[t][feature] p[head][t].  The instruction wants, per lane, eight tokens of one
-    // feature; token rows are feature-contiguous, so a lane loads four neighbouring features (8 bytes) of each of
-    // its eight tokens and unzips them into four operands: row r of operand c is feature 4 r + c of a block of 128
-    // features.  (Two-byte gathers would be one load instruction per token and feature row, and the address unit
-    // spends the same sixteen cycles on a wave's load whatever its width.)  Wave w < H / 128 owns block w.
-    if (wave < H / 128) {
-        f32x16 acc[4];
+    const float inv = 1.0f / sum_across_rows(lrun);
+    // lane: head l16; element v of acc[2 gq + c] is feature 32 gq + 2 (4 kg + v) + c of the wave's FW
+    if (l16 < HEADS) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
+        for (int gq = 0; gq < KS; ++gq) {
+            bf16x8 r;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[c][e] = 0.f;
-        const bf16* pr = pT + (j31 < HEADS ? j31 : 0) * PP + 8 * g;
-        const bf16* xc = xs + wave * 128 + 4 * j31;         // this lane's four feature columns
-        // (the rows of the next sixteen tokens are requested before the current ones are multiplied; rows beyond the
-        // sequence are clamped to its last row and carry p = 0)
-        bf16x4 xv[8];
-        auto load_rows = [&](int k0) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                int tk = k0 + 8 * g + e;
-                tk = tk < L ? tk : L - 1;
-                xv[e] = *(const bf16x4*)(xc + (size_t)tk * H);
-            }
-        };
-        load_rows(0);
-        for (int k0 = 0; k0 < L16; k0 += 16) {
-            bf16x8 fp = *(const bf16x8*)(pr + k0);
-            if (j31 >= HEADS) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) fp[e] = (bf16)0.f;
-            }
-            bf16x8 fxc[4];
-#pragma unroll
-            for (int c = 0; c < 4; ++c)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) fxc[c][e] = xv[e][c];
-            if (k0 + 16 < L16) load_rows(k0 + 16);
-#pragma unroll
-            for (int c = 0; c < 4; ++c)
-                acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fxc[c], fp, acc[c], 0, 0, 0);   // rows: features, columns: heads
-        }
-        // lane: head j31; accumulator element 4 v4 + e of operand c is feature 4 (8 v4 + 4 g + e) + c of the block
-        if (j31 < HEADS) {
-#pragma unroll
-            for (int v4 = 0; v4 < 4; ++v4)
-#pragma unroll
-                for (int half = 0; half < 2; ++half) {
-                    bf16x8 r;
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) r[i] = (bf16)acc[i & 3][4 * v4 + 2 * half + (i >> 2)];
-                    *(bf16x8*)(xb + (size_t)j31 * H + wave * 128 + 32 * v4 + 16 * g + 8 * half) = r;
-                }
+            for (int i = 0; i < 8; ++i) r[i] = (bf16)(acc[2 * gq + (i & 1)][i >> 1] * inv);
+            *(bf16x8*)(xb + (size_t)l16 * H + wave * FW + 32 * gq + 8 * kg) = r;
         }
     }
 }
@@ -866,22 +903,20 @@ hipError_t launch_attention_first_fold(const sp_model* M, const void* x, const v
 {
     const sp_config& c = M->cfg;
     if (!attention_first_fold_supported(c, max_seqlen) || cmrows < B || cmrows > crows) return hipErrorInvalidValue;
-    const int LP = ((max_seqlen + 3) & ~3) + 4;             // score row pitch (floats)
-    const int PP = ((max_seqlen + 15) & ~15) + 8;           // probability row pitch (bf16)
-    const size_t smem = kFoldPartBytes + (size_t)c.heads * LP * 4 + (size_t)c.heads * PP * 2;
     dim3 grid((unsigned)cmrows, (unsigned)k);
 #define SP_FOLD(HEADS)                                                                                              \
     do {                                                                                                            \
         auto kern = attention_first_fold_kernel<HEADS>;                                                             \
+        constexpr size_t smem = FoldLds<HEADS>::bytes;                                                              \
         static std::atomic<bool> raised{false}; /* the attribute is sticky for the process */                      \
         if (smem > 48 * 1024 && !raised) {                                                                          \
             hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,      \
-                                               (int)kFoldMaxSmem);                                                  \
+                                               (int)smem);                                                          \
             if (e != hipSuccess) return e;                                                                          \
             raised = true;                                                                                          \
         }                                                                                                           \
         hipLaunchKernelGGL(kern, grid, dim3(64 * kFoldWaves), smem, s, (const bf16*)x, (const bf16*)qt, (bf16*)xbar,  \
-                           cu, B, T, rows, crows, max_seqlen, LP, PP);                                              \
+                           cu, B, T, rows, crows, max_seqlen);                                                      \
     } while (0)
     switch (c.heads) {
         case 4: SP_FOLD(4); break;
