@@ -193,7 +193,7 @@ def power_leg(sp, torch, forward_burst):
 
 def first_only_runs(shape, tokens, max_len):
     """Whether sp_forward computes the last layer for the first-token rows only (sp_config.last_layer_all_tokens = 0)."""
-    return shape.dtype == "bf16" and tokens >= 1024 and shape.heads % 4 == 0 and shape.heads <= 16 and max_len <= 512
+    return shape.dtype == "bf16" and tokens >= 1024 and shape.heads % 4 == 0 and shape.heads <= 16   # (any length)
 
 
 def executed_flops(shape, lengths, k):

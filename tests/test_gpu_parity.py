@@ -169,9 +169,9 @@ def test_first_token_last_layer_matches_all_tokens(sp, oracle64):
 
 def test_sequences_longer_than_512_tokens(sp, oracle64):
     """Sequences beyond 512 tokens: three and four 256-query workgroups per (sequence, head) in the key/value-sharing
-    attention body, a dozen key tiles per query block; the folded first-token attention does not take them (its
-    score buffer is sized for 512), so the last layer runs on every token although the call is large enough.  Whole
-    forward against the oracle, every sequence, each k_active; and the attention stage by itself."""
+    attention body, a dozen key tiles per query block; up to 32 tiles of tokens under the running softmax of the folded
+    first-token attention in the last layer.  Whole forward against the oracle, every sequence, each k_active, with the
+    last layer on the first tokens and on every token; and the attention stage by itself."""
     shape = synth.StudentShape(K=2, layers=2, hidden=256, heads=4, ffn=512, vocab=200, max_pos=1024, classes=3,
                                dtype="bf16")
     rng = np.random.default_rng(29)
@@ -179,12 +179,15 @@ def test_sequences_longer_than_512_tokens(sp, oracle64):
     ids = synth.make_ids(rng, int(lengths.sum()), shape.vocab)
     blob = synth.make_weights(rng, shape, std=0.05, ln_random=True, qk_std=0.12)
     st = sp.Students(sp.config_from_shape(shape), blob)
+    st_all = sp.Students(sp.config_from_shape(shape, last_layer_all_tokens=True), blob)
     d_ids, d_cu, cu = gpu_inputs(lengths, ids, sp)
     ow = oracle_weights(blob, shape)
     for k in (1, 2):
-        got = st.sp_forward(d_ids, d_cu, int(lengths.max()), k).cpu().numpy().astype(np.float64)
         want = oracle64.forward(ocfg(shape), ow, ids, cu, k)
-        check_logits(got, want, shape, f"long sequences k_active={k}")
+        for name, students in (("first tokens", st), ("every token", st_all)):
+            got = students.sp_forward(d_ids, d_cu, int(lengths.max()), k).cpu().numpy().astype(np.float64)
+            check_logits(got, want, shape, f"long sequences, last layer on {name}, k_active={k}")
+    st_all.close()
     T, B = int(cu[-1]), len(lengths)
     ws = st.sp_forward_partial(d_ids, d_cu, int(lengths.max()), shape.K, 1)
     qkv, att = st.read_activation(ws, "qkv", T, B, shape.K), st.read_activation(ws, "att", T, B, shape.K)
