@@ -579,6 +579,67 @@ __global__ __launch_bounds__(256) void head_gemm_kernel(const bf16* __restrict__
         *(uint4*)(o + (size_t)(r0 + rr) * ldo) = *(const uint4*)(stg + (r0 + rr) * PITCH + cc * 16);
 }
 
+// The same products when the reduction is long and the outputs are few (the value projection of the weighted mean rows:
+// Kd = H, 64 outputs per head): one 32-row x 64-output item per workgroup, its four waves split the reduction range, and
+// the partial tiles are added through LDS (waves in a fixed order), so that a wave's chain of dependent loads is a quarter
+// as long and four times as many compute units take part.  Kd must be a multiple of 64.
+__global__ __launch_bounds__(256) void head_gemm_ksplit_kernel(const bf16* __restrict__ A, size_t a_ss, size_t a_hs,
+                                                               int lda, const char* __restrict__ arena,
+                                                               size_t student_stride, size_t w_off, size_t w_hs,
+                                                               int ldw, size_t b_off, size_t b_hs, int has_bias,
+                                                               bf16* __restrict__ out, size_t o_ss, size_t o_hs, int ldo,
+                                                               int mtiles, int nstrips, int Kd, int heads, int total)
+{
+    constexpr int NT = 2, SW = NT * 32, PP = 33;            // strip width; pitch of a feature's 32 rows (floats)
+    __shared__ float part[4 * SW * PP];
+    // XCD-aware order as in head_gemm_kernel: a head's weight slice is fetched into one L2
+    const int chunk = (total + 7) >> 3;
+    const int lin = (int)(blockIdx.x & 7) * chunk + (int)(blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= chunk || lin >= total) return;
+    const int per_head = mtiles * nstrips;
+    const int m = lin / (per_head * heads), h = (lin / per_head) % heads, item = lin % per_head;
+    const int ns = item % nstrips, mt = item / nstrips;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int j31 = lane & 31, g = lane >> 5;
+    const int kw = Kd / 4;                                  // this wave's share of the reduction range
+    const bf16* a = A + (size_t)m * a_ss + (size_t)h * a_hs + (size_t)(mt * 32 + j31) * lda + wave * kw + 8 * g;
+    const bf16* w = (const bf16*)(arena + (size_t)m * student_stride + w_off) + (size_t)h * w_hs +
+                    (size_t)(ns * SW + j31) * ldw + wave * kw + 8 * g;
+    f32x16 acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+#pragma unroll 12
+    for (int k0 = 0; k0 < kw; k0 += 16) {
+        const bf16x8 fa = *(const bf16x8*)(a + k0);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const bf16x8 fw = *(const bf16x8*)(w + (size_t)t * 32 * ldw + k0);
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw, fa, acc[t], 0, 0, 0);   // rows: output features, columns: r
+        }
+    }
+    // lane: row r = j31 of the strip; output features 32 t + 8 (v / 4) + 4 g + v % 4
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            part[(wave * SW + 32 * t + 8 * (v / 4) + 4 * g + v % 4) * PP + j31] = acc[t][v];
+    __syncthreads();
+    // thread: row r = tid % 32, eight neighbouring features: one 16-byte piece of the output row
+    const int r = tid & 31, f0 = (tid >> 5) * 8;
+    const float* bias = (const float*)(arena + (size_t)m * student_stride + b_off) + (size_t)h * b_hs + ns * SW + f0;
+    bf16x8 o8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        float sum = has_bias ? bias[i] : 0.f;
+#pragma unroll
+        for (int wv = 0; wv < 4; ++wv) sum += part[(wv * SW + f0 + i) * PP + r];
+        o8[i] = (bf16)sum;
+    }
+    *(bf16x8*)(out + (size_t)m * o_ss + (size_t)h * o_hs + (size_t)(mt * 32 + r) * ldo + ns * SW + f0) = o8;
+}
+
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 // Maximum / sum over the four lanes l % 16 + {0, 16, 32, 48} (every lane active).
@@ -874,6 +935,15 @@ hipError_t launch_head_gemm(const sp_model* M, const void* A, size_t a_ss, size_
         w_hs % 8 || o_hs % 8)
         return hipErrorInvalidValue;
     const int mtiles = mrows / 32;
+    if (N % 128 != 0 && N % 64 == 0 && Kd >= 256 && Kd % 64 == 0) {
+        const int nstrips = N / 64;
+        const int total = k * c.heads * mtiles * nstrips;
+        dim3 grid((unsigned)((total + 7) / 8 * 8));
+        hipLaunchKernelGGL(head_gemm_ksplit_kernel, grid, dim3(256), 0, s, (const bf16*)A, a_ss, a_hs, lda, M->arena,
+                           M->L.student_stride, w_off, w_hs, ldw, b_off, b_hs, has_bias ? 1 : 0, (bf16*)out, o_ss, o_hs,
+                           ldo, mtiles, nstrips, Kd, c.heads, total);
+        return hipGetLastError();
+    }
 #define SP_HEAD_GEMM(NT)                                                                                            \
     do {                                                                                                            \
         const int nstrips = N / (32 * NT);                                                                          \
