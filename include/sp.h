@@ -263,6 +263,11 @@ int sp_forward_profiled(const sp_model* model, const int32_t* token_ids, const i
  * Errors: SP_EINVAL, SP_ESHAPE, SP_EHIP. */
 int sp_probe_gelu(const float* x_device, float* y_device, int64_t n, void* hip_stream);
 
+/* The same for the GELU of the fp8 FFN up-projection (SP_DTYPE_FP8), whose result is stored as an e4m3 code: the
+ * erf form through a shorter fit, within 1e-4 of the definition (a thirtieth of the code's step where the function is
+ * smallest); y[i] is the value before the scaling and the rounding to e4m3.  Same arguments and errors. */
+int sp_probe_gelu_fp8(const float* x_device, float* y_device, int64_t n, void* hip_stream);
+
 /* codes_host[i] = the OCP e4m3 code (sign, 4 exponent bits with bias 7, 3 mantissa bits; no infinities, largest
  * finite value 448) the weight loader of SP_DTYPE_FP8 gives x_host[i]: round to nearest even, saturating; NaN -> 0x7f.
  * Host arrays of n elements; runs on the host.  For the test that pins the loader's rounding.

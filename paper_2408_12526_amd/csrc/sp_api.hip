@@ -712,6 +712,13 @@ int sp_probe_gelu(const float* x_device, float* y_device, int64_t n, void* hip_s
     return launch_gelu_probe(x_device, y_device, (long)n, (hipStream_t)hip_stream) == hipSuccess ? SP_OK : SP_EHIP;
 }
 
+int sp_probe_gelu_fp8(const float* x_device, float* y_device, int64_t n, void* hip_stream)
+{
+    if (!x_device || !y_device) return SP_EINVAL;
+    if (n < 1 || n > ((int64_t)1 << 31)) return SP_ESHAPE;
+    return launch_gelu_q8_probe(x_device, y_device, (long)n, (hipStream_t)hip_stream) == hipSuccess ? SP_OK : SP_EHIP;
+}
+
 void sp_free(sp_model* model)
 {
     if (!model) return;

@@ -262,7 +262,7 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_kernel(const unsigned char* _
                     const int f = i * 32 + 8 * v4 + 4 * g, t = jj * 32 + j31;
                     float r[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) r[e] = gelu_erf_fast(acc[i][jj][4 * v4 + e] * f4[i][v4][e]) * q_out;
+                    for (int e = 0; e < 4; ++e) r[e] = gelu_erf_q8(acc[i][jj][4 * v4 + e] * f4[i][v4][e]) * q_out;
                     int w = 0;
                     w = __builtin_amdgcn_cvt_pk_fp8_f32(r[0], r[1], w, false);
                     w = __builtin_amdgcn_cvt_pk_fp8_f32(r[2], r[3], w, true);
@@ -357,7 +357,21 @@ hipError_t launch_fp8_tile(const sp_model* M, const void* A8, int lda, size_t w_
     return hipGetLastError();
 }
 
+// y[i] = the GELU of the fp8 epilogue evaluated on x[i], before the scaling and the rounding to e4m3 (test aid)
+__global__ void gelu_q8_probe_kernel(const float* __restrict__ x, float* __restrict__ y, long n)
+{
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) y[i] = gelu_erf_q8(x[i]);
+}
+
 }  // namespace
+
+hipError_t launch_gelu_q8_probe(const float* x, float* y, long n, hipStream_t s)
+{
+    if (n < 1) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(gelu_q8_probe_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, x, y, n);
+    return hipGetLastError();
+}
 
 hipError_t launch_gemm_fp8(const sp_model* M, const void* A8, int lda, size_t w_off, size_t s_off, size_t b_off,
                            float a_qscale, void* out, int ldo, const void* residual, int ldr, int mrows, int N, int Kd,

@@ -52,6 +52,20 @@ __device__ inline float gelu_erf_fast(float x)
     return __builtin_fmaf(-a, e, __builtin_amdgcn_fmed3f(x, 0.0f, 3.402823466e+38f));
 }
 
+// The same function where the result is stored as an e4m3 code (three mantissa bits: steps of 2^-4 relative): the
+// exponent is a cubic, log2(erfc(a / sqrt 2) / 2) ~ -1 + a (c0 + a (c1 + a c2)), fitted (minimax in the error of
+// the function value) on [0, 4.5]; all three coefficients are negative, so it keeps falling beyond the fitted range and
+// needs no clamp.  Within 8.6e-5 of the erf form everywhere, a thirtieth of the e4m3 step at the function's minimum
+// (-0.17): four multiply-adds, one median and the exponential.
+__device__ inline float gelu_erf_q8(float x)
+{
+    const float a = __builtin_fabsf(x);
+    float q = __builtin_fmaf(-2.763128887e-02f, a, -4.882554528e-01f);
+    q = __builtin_fmaf(q, a, -1.140919014e+00f);
+    const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(q, a, -1.0f));
+    return __builtin_fmaf(-a, e, __builtin_amdgcn_fmed3f(x, 0.0f, 3.402823466e+38f));
+}
+
 // ---- reductions over the 64 lanes of a wave, result in every lane -------------------------------------------------
 // Inside a row of 16 lanes the second operand of each step comes through the data-parallel-primitive path of the
 // instruction itself (neighbour in the pair, other pair of the quad, mirror image in the half row, mirror image in the
@@ -216,6 +230,7 @@ hipError_t launch_gemm_fp8(const sp_model* M, const void* A8, int lda, size_t w_
 
 // y[i] = GELU as the bf16 FFN up-projection's epilogue evaluates it, in fp32 (i < n).  Test aid.
 hipError_t launch_gelu_probe(const float* x, float* y, long n, hipStream_t s);
+hipError_t launch_gelu_q8_probe(const float* x, float* y, long n, hipStream_t s);
 
 // Split reduction for calls of a few dozen tokens, where one workgroup per 64x64 output tile walking the whole
 // reduction range is a long serial chain: partials[m][s][row][0..N) = A[m][row][s*Kd/splits ..) . W^T (fp32, no bias),

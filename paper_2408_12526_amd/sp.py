@@ -55,6 +55,7 @@ def _load() -> C.CDLL:
     lib.sp_forward_profiled.restype = C.c_int
     lib.sp_forward_profiled.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, sz, vp, vp, vp]
     lib.sp_probe_gelu.restype = C.c_int; lib.sp_probe_gelu.argtypes = [vp, vp, C.c_int64, vp]
+    lib.sp_probe_gelu_fp8.restype = C.c_int; lib.sp_probe_gelu_fp8.argtypes = [vp, vp, C.c_int64, vp]
     lib.sp_probe_e4m3.restype = C.c_int; lib.sp_probe_e4m3.argtypes = [vp, C.c_int64, vp]
     lib.sp_probe_mfma_rate.restype = C.c_int
     lib.sp_probe_mfma_rate.argtypes = [i32, i32, vp, vp, C.POINTER(C.c_float)]
@@ -116,6 +117,14 @@ def sp_probe_gelu(x: torch.Tensor) -> torch.Tensor:
     assert x.dtype == torch.float32 and x.is_cuda and x.is_contiguous()
     y = torch.empty_like(x)
     _check(_lib.sp_probe_gelu(x.data_ptr(), y.data_ptr(), x.numel(), _stream_ptr(None)))
+    return y
+
+
+def sp_probe_gelu_fp8(x: torch.Tensor) -> torch.Tensor:
+    """The fp8 path's GELU evaluated in fp32 on a float32 device tensor, before scaling and rounding (test aid)."""
+    assert x.dtype == torch.float32 and x.is_cuda and x.is_contiguous()
+    y = torch.empty_like(x)
+    _check(_lib.sp_probe_gelu_fp8(x.data_ptr(), y.data_ptr(), x.numel(), _stream_ptr(None)))
     return y
 
 

@@ -122,6 +122,25 @@ def test_fp8_projections_stage_by_stage(sp, oracle64):
     st.close()
 
 
+def test_gelu_of_the_fp8_epilogue_is_the_erf_form_to_a_thirtieth_of_a_code_step(sp):
+    """The fp8 FFN up-projection stores GELU as e4m3 codes and evaluates it through a shorter fit than the bf16 path.
+    Before scaling and rounding it must stay within 1e-4 of x (1 + erf(x / sqrt 2)) / 2 everywhere, huge arguments
+    included (the fit has no clamp: its exponent keeps falling); the e4m3 step at the function's minimum, -0.17, is
+    2^-3 * 2^-3 = 1.6e-2 wide there, so the fit moves no code by more than a hundredth of a step."""
+    import math
+    grid = np.concatenate([np.linspace(-12, 12, 1_000_001), np.linspace(-1e-3, 1e-3, 2_001),
+                           [0.0, -0.0, 1.0, -1.0, 30.0, -30.0, 1e4, -1e4, 1e20, -1e20, 3e38, -3e38]]).astype(np.float32)
+    got = sp.sp_probe_gelu_fp8(torch.from_numpy(grid).cuda()).cpu().numpy().astype(np.float64)
+    x = grid.astype(np.float64)
+    want = 0.5 * x * (1.0 + np.vectorize(math.erf)(x / math.sqrt(2.0)))
+    assert np.isfinite(got).all()
+    err = np.abs(got - want)
+    rel_big = err[np.abs(x) > 12] / np.maximum(np.abs(want[np.abs(x) > 12]), 1.0)
+    assert err[np.abs(x) <= 12].max() <= 1e-4, f"max error {err[np.abs(x) <= 12].max():.3e} at x = {x[err.argmax()]}"
+    assert rel_big.max() <= 1e-6
+    assert got[np.flatnonzero(grid == 0.0)].max() == 0.0
+
+
 @pytest.mark.parametrize("all_tokens", [True, False])
 def test_fp8_forward_against_oracle_with_dequantised_weights(sp, oracle64, all_tokens):
     """Whole forward of quantised students, both last-layer variants (with the first-token last layer only the first
