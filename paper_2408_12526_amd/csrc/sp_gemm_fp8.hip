@@ -245,13 +245,17 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_kernel(const unsigned char* _
 #pragma unroll
     for (int i = 0; i < TN; ++i)
 #pragma unroll
-        for (int v4 = 0; v4 < 4; ++v4) f4[i][v4] = *(const f32x4*)(scl + i * 32 + 8 * v4) * inv_qa;
+        for (int v4 = 0; v4 < 4; ++v4)                     // (GELU: the output scale rides in the factors, see below)
+            f4[i][v4] = *(const f32x4*)(scl + i * 32 + 8 * v4) * (EPI == EPI_BIAS_GELU ? inv_qa * q_out : inv_qa);
 
     // ---- epilogue.  Accumulator element v of lane l in block (i, j): token = l % 32,
     // feature = 8 * (v / 4) + 4 * (l / 32) + v % 4 inside the 32x32 block.  After the barrier of the last
     // iteration nobody reads the ring: each wave stages its 128 x 128 sub-tile in its own slice of it.
     if (EPI == EPI_BIAS_GELU) {
-        // fp8 output, e4m3(gelu(.) * q_out): staged [128 tokens][128 bytes], chunk (feature / 16) ^ (token & 7)
+        // fp8 output, e4m3(gelu(.) * q_out): staged [128 tokens][128 bytes], chunk (feature / 16) ^ (token & 7).
+        // The values arrive scaled by q_out, and the fit's coefficients are scaled to match.
+        const float iq = 1.0f / q_out;
+        const float k0 = kGeluQ8C0 * iq, k1 = kGeluQ8C1 * iq * iq, k2 = kGeluQ8C2 * iq * iq * iq;
         char* slice8 = (char*)smem + (size_t)wave * (WT * WT);
 #pragma unroll
         for (int jj = 0; jj < TM; ++jj)
@@ -262,7 +266,7 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_kernel(const unsigned char* _
                     const int f = i * 32 + 8 * v4 + 4 * g, t = jj * 32 + j31;
                     float r[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) r[e] = gelu_erf_q8(acc[i][jj][4 * v4 + e] * f4[i][v4][e]) * q_out;
+                    for (int e = 0; e < 4; ++e) r[e] = gelu_erf_q8_scaled(acc[i][jj][4 * v4 + e] * f4[i][v4][e], k0, k1, k2);
                     int w = 0;
                     w = __builtin_amdgcn_cvt_pk_fp8_f32(r[0], r[1], w, false);
                     w = __builtin_amdgcn_cvt_pk_fp8_f32(r[2], r[3], w, true);

@@ -57,14 +57,18 @@ __device__ inline float gelu_erf_fast(float x)
 // the function value) on [0, 4.5]; all three coefficients are negative, so it keeps falling beyond the fitted range and
 // needs no clamp.  Within 8.6e-5 of the erf form everywhere, a thirtieth of the e4m3 step at the function's minimum
 // (-0.17): four multiply-adds, one median and the exponential.
-__device__ inline float gelu_erf_q8(float x)
+// The scaled form returns s gelu(y / s) for y = s x, with the coefficients divided by s, s^2, s^3 by the caller
+// (gelu_q8_coefficients): the scale of the quantised output then costs no instruction per value.
+constexpr float kGeluQ8C0 = -1.140919014e+00f, kGeluQ8C1 = -4.882554528e-01f, kGeluQ8C2 = -2.763128887e-02f;
+__device__ inline float gelu_erf_q8_scaled(float y, float k0, float k1, float k2)
 {
-    const float a = __builtin_fabsf(x);
-    float q = __builtin_fmaf(-2.763128887e-02f, a, -4.882554528e-01f);
-    q = __builtin_fmaf(q, a, -1.140919014e+00f);
+    const float a = __builtin_fabsf(y);
+    float q = __builtin_fmaf(k2, a, k1);
+    q = __builtin_fmaf(q, a, k0);
     const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(q, a, -1.0f));
-    return __builtin_fmaf(-a, e, __builtin_amdgcn_fmed3f(x, 0.0f, 3.402823466e+38f));
+    return __builtin_fmaf(-a, e, __builtin_amdgcn_fmed3f(y, 0.0f, 3.402823466e+38f));
 }
+__device__ inline float gelu_erf_q8(float x) { return gelu_erf_q8_scaled(x, kGeluQ8C0, kGeluQ8C1, kGeluQ8C2); }
 
 // ---- reductions over the 64 lanes of a wave, result in every lane -------------------------------------------------
 // Inside a row of 16 lanes the second operand of each step comes through the data-parallel-primitive path of the
