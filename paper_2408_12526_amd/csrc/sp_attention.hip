@@ -255,12 +255,11 @@ __device__ __forceinline__ void attention_long_body(char* lds, int bid, const bf
         __builtin_amdgcn_wave_barrier();
         const int orow = lane >> 3, oc = lane & 7;
         const size_t doff = ((size_t)m * rows + t0 + qs) * H + h * kD + oc * 8;
-        bf16* dst = att + doff;
 #pragma unroll
         for (int r0 = 0; r0 < 32; r0 += 8)
             if (qs + r0 + orow < L) {
                 const uint4 c = *(const uint4*)(stg + (r0 + orow) * kOutPitch + oc * 16);
-                *(uint4*)(dst + (size_t)(r0 + orow) * H) = c;
+                if (att) *(uint4*)(att + doff + (size_t)(r0 + orow) * H) = c;   // (null: the fp8 copy alone)
                 if (attq) *(uint2*)(attq + doff + (size_t)(r0 + orow) * H) = chunk_to_fp8(c, qscale);   // fp8 copy
             }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -454,12 +453,11 @@ __device__ __forceinline__ void attention_short_body(char* lds, int bid, const b
             __builtin_amdgcn_wave_barrier();
             const int orow = lane >> 3, oc = lane & 7;
             const size_t doff = ((size_t)m * rows + t0 + qs) * H + h * kD + oc * 8;
-            bf16* dst = att + doff;
 #pragma unroll
             for (int r0 = 0; r0 < 32; r0 += 8)
                 if (qs + r0 + orow < L) {
                     const uint4 c = *(const uint4*)(stg + (r0 + orow) * (kSVStride * 4) + oc * 16);
-                    *(uint4*)(dst + (size_t)(r0 + orow) * H) = c;
+                    if (att) *(uint4*)(att + doff + (size_t)(r0 + orow) * H) = c;   // (null: the fp8 copy alone)
                     if (attq) *(uint2*)(attq + doff + (size_t)(r0 + orow) * H) = chunk_to_fp8(c, qscale);   // fp8 copy
                 }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -892,6 +890,7 @@ hipError_t launch_attention(const sp_model* M, const void* qkv, const void* vt, 
 {
     const sp_config& c = M->cfg;
     if (c.hidden / c.heads != kD) return hipErrorInvalidValue;
+    if (!att && !(attq && bf16_path(c))) return hipErrorInvalidValue;   // (no bf16 output: the fp8 copy alone)
     if (bf16_path(c)) {
         // Sequences of up to 128 tokens: one wave per (sequence, head); longer ones: one workgroup per (sequence,
         // head, 128 queries) sharing the key/value tiles.  Each kernel skips the other's sequences.  (Giving the long
