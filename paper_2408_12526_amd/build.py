@@ -17,7 +17,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsp_mi355x.so")
-SOURCES = ["sp_api.hip", "sp_elementwise.hip", "sp_gemm.hip", "sp_attention.hip", "sp_dispatch.cpp", "sp_serve.hip", "sp_probe.hip", "sp_gemm_fp8.hip"]
+SOURCES = ["sp_api.hip", "sp_elementwise.hip", "sp_gemm.hip", "sp_attention.hip", "sp_dispatch.cpp", "sp_serve.hip", "sp_probe.hip", "sp_gemm_fp8.hip", "sp_gemv.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", INCLUDE, "-I", CSRC,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

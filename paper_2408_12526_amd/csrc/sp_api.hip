@@ -321,6 +321,7 @@ static int run_students(const sp_model* M0, const WsLayout& W, const int32_t* id
     char *cqt = w + W.cqt + m0 * cHH * ab, *cxb = w + W.cxb + m0 * cHH * ab;
     bool compact_final = false, small_head = false;
     size_t small_head_lo = 0;
+    int small_head_splits = 1;
     // Calls of a few dozen tokens: split the reduction range of the two projections that are followed by a LayerNorm
     // (largest slice count that leaves every slice at least two 64-wide k-tiles).
     const size_t slice = (size_t)kSplitRows * H;
@@ -404,6 +405,19 @@ static int run_students(const sp_model* M0, const WsLayout& W, const int32_t* id
         SP_TRY(launch_attention(M, qkv, vt, fp8 && with_head ? nullptr : att, cu, B, T, max_seqlen, rows, k, s, attq,
                                 kActQuantScale));
         SP_MARK(SP_PHASE_ATTENTION);
+        if (with_head && !c.last_layer_all_tokens && l == c.layers - 1 && m0 == 0 && split_o > 1 && split_d > 1 &&
+            first_rows_tail_supported(c, B)) {
+            // last layer of a whole forward of a few sequences: from here on only their first-token rows are needed,
+            // and those go through per-feature dot products instead of 64-row tiles; the head takes over from the
+            // raw down-projection (one slice)
+            float* ut = part + (size_t)k * slice;           // behind the slices the head reads
+            SP_TRY(launch_first_rows_tail(M, lo, att, x, x1, g, ut, part, slice, cu, B, T, rows, k, s));
+            SP_MARK(SP_PHASE_LAST_FIRST);
+            small_head = true;
+            small_head_lo = lo;
+            small_head_splits = 1;
+            continue;
+        }
         if (split_o > 1) {
             // few tokens: the reduction range is split over workgroups, and the slices are added together with the
             // bias, the residual and the LayerNorm
@@ -437,6 +451,7 @@ static int run_students(const sp_model* M0, const WsLayout& W, const int32_t* id
                 // slices itself
                 small_head = true;
                 small_head_lo = lo;
+                small_head_splits = split_d;
             } else {
                 SP_TRY(launch_ln_reduce(M, part, split_d, slice, lo + L.b2, x1, x, rows, mrows, k, lo + L.ln2g, lo + L.ln2b, s));
                 SP_MARK(SP_PHASE_LAYERNORM);
@@ -461,7 +476,7 @@ static int run_students(const sp_model* M0, const WsLayout& W, const int32_t* id
             SP_TRY(launch_gemm(M, cx, H, L.wp_t, L.bp, cu2, H, nullptr, 0, cmrows, H, H, k, EPI_BIAS_TANH, cH, cH, 0, s));
             SP_TRY(launch_head_classify(M, cu2, B, crows, k, z, logits, s));
         } else if (small_head)
-            SP_TRY(launch_head_small(M, part, split_d, slice, small_head_lo + L.b2, x1, small_head_lo + L.ln2g,
+            SP_TRY(launch_head_small(M, part, small_head_splits, slice, small_head_lo + L.b2, x1, small_head_lo + L.ln2g,
                                      small_head_lo + L.ln2b, cu, B, T, rows, k, z, zpart, logits, s));
         else
             SP_TRY(launch_head(M, x, cu, B, T, rows, k, z, zpart, logits, s));

@@ -233,6 +233,15 @@ hipError_t launch_gemm_fp8(const sp_model* M, const void* A8, int lda, size_t w_
                            size_t o2_student_stride, float out_qscale);
 
 // y[i] = GELU as the bf16 FFN up-projection's epilogue evaluates it, in fp32 (i < n).  Test aid.
+// Last layer after its attention for the first-token rows of a call of a few sequences (see sp_gemv.hip): u is fp32
+// scratch of first_rows_tail_scratch_floats elements, g the FFN activation buffer (its first rows are used), part the
+// split-reduction buffer whose slice 0 receives the raw down-projection at the first tokens' rows (student stride
+// part_ss elements), x1 the buffer whose first-token rows receive LN(u).
+bool first_rows_tail_supported(const sp_config& c, int B);
+size_t first_rows_tail_scratch_floats(const sp_config& c, int k);
+hipError_t launch_first_rows_tail(const sp_model* M, size_t lo, const void* att, const void* x, void* x1, void* g,
+                                  float* u, float* part, size_t part_ss, const int32_t* cu, int B, int T, int rows,
+                                  int k, hipStream_t s);
 hipError_t launch_gelu_probe(const float* x, float* y, long n, hipStream_t s);
 hipError_t launch_gelu_q8_probe(const float* x, float* y, long n, hipStream_t s);
 

@@ -375,6 +375,35 @@ def test_call_sizes_at_every_path_boundary(sp, oracle64, total):
         check_logits(got[pick], want, shape, f"{total} tokens, k_active={k}")
 
 
+@pytest.mark.parametrize("lengths", [(64,), (1,), (128,), (17, 3), (60, 1, 67), (30, 31, 32, 33), (1, 1, 1, 1),
+                                     (25, 25, 25, 25, 25)])
+def test_calls_of_a_few_sequences(sp, oracle64, lengths):
+    """Whole forwards of one to four sequences (up to 128 tokens) finish their last layer on the first-token rows by
+    per-feature dot products (attention-output projection, LayerNorm, FFN, the head on the raw down-projection); five
+    sequences take the tile path.  Random LayerNorm parameters and sharpened attention, every k_active, against the
+    oracle; and the same call with the last layer on every token (the tile path) must agree with it to rounding."""
+    shape = synth.StudentShape(K=3, layers=2, hidden=256, heads=4, ffn=1024, vocab=500, max_pos=160, classes=3,
+                               dtype="bf16")
+    rng = np.random.default_rng(500 + sum(lengths) + len(lengths))
+    lengths = np.array(lengths, dtype=np.int32)
+    ids = synth.make_ids(rng, int(lengths.sum()), shape.vocab)
+    blob = synth.make_weights(rng, shape, std=0.05, ln_random=True, qk_std=0.12)
+    st = sp.Students(sp.config_from_shape(shape), blob)
+    st_tiles = sp.Students(sp.config_from_shape(shape, last_layer_all_tokens=True), blob)
+    d_ids, d_cu, cu = gpu_inputs(lengths, ids, sp)
+    ow = oracle_weights(blob, shape)
+    for k in range(1, shape.K + 1):
+        got = st.sp_forward(d_ids, d_cu, int(lengths.max()), k).cpu().numpy().astype(np.float64)
+        tiles = st_tiles.sp_forward(d_ids, d_cu, int(lengths.max()), k).cpu().numpy().astype(np.float64)
+        want = oracle64.forward(ocfg(shape), ow, ids, cu, k)
+        assert np.abs(want).max() > 5e-2
+        check_logits(got, want, shape, f"{len(lengths)} sequences {tuple(lengths)}, k_active={k}")
+        check_logits(tiles, want, shape, f"{len(lengths)} sequences {tuple(lengths)}, tile path, k_active={k}")
+        assert rel_err(got, tiles) < 1e-2
+    st.close()
+    st_tiles.close()
+
+
 # ---- the five workloads ----------------------------------------------------------------------------
 
 _cache = {}
