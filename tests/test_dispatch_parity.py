@@ -98,6 +98,25 @@ def test_dispatcher_loop_bit_exact(kind, padded, variant):
     assert got.k_trace == want.k_trace and len(want.k_trace) > 1
 
 
+def test_native_dispatcher_on_the_hand_worked_traces():
+    """The two traces worked by hand in test_dispatch_pins.py (a burst with k_min = 2; students coming back after an idle
+    window), given to the native dispatcher directly: its result is pinned to the hand-worked numbers themselves, not only
+    to the oracle's."""
+    kw = dict(total_students=4, slots=4, k_min=2, window_us=10**9, base_us=[0, 100, 110, 120, 130],
+              per_token_ns=[0, 1000, 1000, 1000, 1000], bin_width=8, max_len=128, max_elem=4, capacity=64, padded=False)
+    r = D.simulate(np.zeros(6, dtype=np.int64), np.array([30, 30, 31, 52, 100, 30], dtype=np.int32), **kw)
+    assert r.dispatch_us.tolist() == [0, 0, 0, 160, 171, 322] and r.done_us.tolist() == [160, 171, 171, 322, 381, 462]
+    assert r.k_used.tolist() == [4, 2, 2, 2, 2, 2] and r.element.tolist() == [0, 1, 1, 2, 3, 4]
+    assert r.elem_size.tolist() == [1, 2, 1, 1, 1] and r.elem_tokens.tolist() == [30, 61, 52, 100, 30]
+    assert r.k_trace == [(0, 4), (0, 3), (0, 2)] and r.refused == 0
+    kw.update(k_min=1, window_us=50)
+    r = D.simulate(np.array([0, 0, 0, 1000, 1005], dtype=np.int64), np.array([10, 20, 40, 16, 8], dtype=np.int32), **kw)
+    assert r.dispatch_us.tolist() == [0, 0, 130, 1000, 1005] and r.done_us.tolist() == [140, 130, 280, 1136, 1123]
+    assert r.k_used.tolist() == [4, 2, 2, 3, 2] and r.element.tolist() == [0, 1, 2, 3, 4]
+    assert r.elem_size.tolist() == [1] * 5 and r.elem_tokens.tolist() == [10, 20, 40, 16, 8]
+    assert r.k_trace == [(0, 4), (0, 3), (0, 2), (280, 3), (1005, 2)] and r.refused == 0
+
+
 def test_dispatch_argument_errors():
     with pytest.raises(D.DispatchError):
         D.LengthAwareBuffer(bin_width=8, max_len=100)            # not a multiple of the bin width

@@ -161,6 +161,25 @@ def test_dispatcher_burst_hand_worked():
     assert r.k_trace == [(0, 4), (0, 3), (0, 2)] and r.refused == 0
 
 
+def test_dispatcher_idle_window_hand_worked():
+    """Students come back after an idle window, worked by hand (4 students, 4 slots, window 50 us, 1 us per token).
+    t = 0: sample 0 (10 tokens) goes out alone with k = 4 (done 0 + 130 + 10 = 140).  Sample 1 (20) finds the one group
+    busy: buffered, 1 element >= 1 group, k = 3 (still one group).  Sample 2 (40, another bin): second element,
+    2 >= 1, k = 2: two groups, the idle one takes [1] (done 0 + 110 + 20 = 130).  t = 130: that group finishes and
+    takes [2] (130 + 110 + 40 = 280); the buffer is empty from here on.  t = 140: sample 0 done, 10 us of empty buffer.
+    t = 280: last group done; 150 us >= the window, two idle groups x 2 students > 0 occupied: k = 3, window restarts.
+    t = 1000: sample 3 (16) goes out at once with k = 3 (1000 + 120 + 16 = 1136); the window has elapsed again but the
+    only group (4 // 3 = 1) is occupied: 0 x 3 > 1 is false.  t = 1005: sample 4 (8) finds it busy: buffered,
+    1 >= 1, k = 2, and the second group that now exists takes it (1005 + 110 + 8 = 1123)."""
+    kw = dict(KW, window_us=50)
+    r = O.simulate([0, 0, 0, 1000, 1005], [10, 20, 40, 16, 8], padded=False, **kw)
+    assert r.dispatch_us == [0, 0, 130, 1000, 1005]
+    assert r.done_us == [140, 130, 280, 1136, 1123]
+    assert r.k_used == [4, 2, 2, 3, 2]
+    assert r.element == [0, 1, 2, 3, 4] and r.elem_size == [1] * 5 and r.elem_tokens == [10, 20, 40, 16, 8]
+    assert r.k_trace == [(0, 4), (0, 3), (0, 2), (280, 3), (1005, 2)] and r.refused == 0
+
+
 @pytest.mark.parametrize("padded", [False, True])
 def test_dispatcher_conservation_and_bounds(padded):
     """Properties at any size: every sample is dispatched exactly once, not before it arrives; elements hold one bin
