@@ -319,7 +319,7 @@ static int run_students(const sp_model* M0, const WsLayout& W, const int32_t* id
     char *cx = w + W.cx + m0 * cH, *cq = w + W.cq + m0 * cH, *catt = w + W.catt + m0 * cH, *cu2 = w + W.cu_ + m0 * cH;
     char *cx1 = w + W.cx1 + m0 * cH, *cg = w + W.cg + m0 * cF;
     char *cqt = w + W.cqt + m0 * cHH * ab, *cxb = w + W.cxb + m0 * cHH * ab;
-    bool compact_final = false, small_head = false;
+    bool compact_final = false, small_head = false, first_tail = false;
     size_t small_head_lo = 0;
     int small_head_splits = 1;
     // Calls of a few dozen tokens: split the reduction range of the two projections that are followed by a LayerNorm
@@ -405,17 +405,23 @@ static int run_students(const sp_model* M0, const WsLayout& W, const int32_t* id
         SP_TRY(launch_attention(M, qkv, vt, fp8 && with_head ? nullptr : att, cu, B, T, max_seqlen, rows, k, s, attq,
                                 kActQuantScale));
         SP_MARK(SP_PHASE_ATTENTION);
-        if (with_head && !c.last_layer_all_tokens && l == c.layers - 1 && m0 == 0 && split_o > 1 && split_d > 1 &&
-            first_rows_tail_supported(c, B)) {
+        if (with_head && !c.last_layer_all_tokens && l == c.layers - 1 && m0 == 0 && first_rows_tail_supported(c, B)) {
             // last layer of a whole forward of a few sequences: from here on only their first-token rows are needed,
-            // and those go through per-feature dot products instead of 64-row tiles; the head takes over from the
-            // raw down-projection (one slice)
-            float* ut = part + (size_t)k * slice;           // behind the slices the head reads
-            SP_TRY(launch_first_rows_tail(M, lo, att, x, x1, g, ut, part, slice, cu, B, T, rows, k, s));
+            // and those go through per-feature dot products instead of 64-row tiles.  Calls of up to 128 tokens: the
+            // small-call head takes over from the raw down-projection (one slice); longer ones: pooler by dot
+            // products as well, then the classifier kernel (the pooled rows sit behind the scratch).
+            float* ut = part + (size_t)k * slice;           // behind the slice the head reads
+            if (split_o > 1 && split_d > 1) {
+                SP_TRY(launch_first_rows_tail(M, lo, att, x, x1, g, ut, part, slice, nullptr, cu, B, T, rows, k, s));
+                small_head = true;
+                small_head_lo = lo;
+                small_head_splits = 1;
+            } else {
+                SP_TRY(launch_first_rows_tail(M, lo, att, x, x1, g, ut, nullptr, 0, ut + first_rows_tail_scratch_floats(c, k),
+                                              cu, B, T, rows, k, s));
+                first_tail = true;
+            }
             SP_MARK(SP_PHASE_LAST_FIRST);
-            small_head = true;
-            small_head_lo = lo;
-            small_head_splits = 1;
             continue;
         }
         if (split_o > 1) {
@@ -475,7 +481,10 @@ static int run_students(const sp_model* M0, const WsLayout& W, const int32_t* id
             // first tokens stay readable after the call)
             SP_TRY(launch_gemm(M, cx, H, L.wp_t, L.bp, cu2, H, nullptr, 0, cmrows, H, H, k, EPI_BIAS_TANH, cH, cH, 0, s));
             SP_TRY(launch_head_classify(M, cu2, B, crows, k, z, logits, s));
-        } else if (small_head)
+        } else if (first_tail)
+            SP_TRY(launch_head_classify(M, part + (size_t)k * slice + first_rows_tail_scratch_floats(c, k), B,
+                                        first_rows_tail_pooled_rows(), k, z, logits, s, true));
+        else if (small_head)
             SP_TRY(launch_head_small(M, part, small_head_splits, slice, small_head_lo + L.b2, x1, small_head_lo + L.ln2g,
                                      small_head_lo + L.ln2b, cu, B, T, rows, k, z, zpart, logits, s));
         else

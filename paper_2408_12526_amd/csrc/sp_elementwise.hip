@@ -558,9 +558,10 @@ __global__ void sum_students_kernel(const float* __restrict__ z, int n, int k, f
 }
 
 // Classifier on pooled rows and the cross-student sum: one workgroup per sequence, wave w takes students w, w + 4, ...
-template <typename T>
+// (T: type of the classifier matrix in the arena, P: type of the pooled rows)
+template <typename T, typename P = T>
 __global__ __launch_bounds__(256) void head_classify_kernel(const char* arena, size_t student_stride, size_t wc_off,
-                                                            size_t bc_off, const T* __restrict__ pooled, int B, int crows,
+                                                            size_t bc_off, const P* __restrict__ pooled, int B, int crows,
                                                             int H, int C, int k, float* __restrict__ z,
                                                             float* __restrict__ logits)
 {
@@ -570,7 +571,7 @@ __global__ __launch_bounds__(256) void head_classify_kernel(const char* arena, s
         const char* sb = arena + (size_t)m * student_stride;
         const T* Wc = (const T*)(sb + wc_off);
         const float* bc = (const float*)(sb + bc_off);
-        const T* p = pooled + ((size_t)m * crows + b) * H;
+        const P* p = pooled + ((size_t)m * crows + b) * H;
         for (int c = 0; c < C; ++c) {
             float acc = 0.f;
             for (int n = lane; n < H; n += 64) acc += (float)p[n] * (float)Wc[(size_t)n * C + c];
@@ -589,10 +590,15 @@ __global__ __launch_bounds__(256) void head_classify_kernel(const char* arena, s
 }  // namespace
 
 hipError_t launch_head_classify(const sp_model* M, const void* pooled, int B, int crows, int k, float* z, float* logits,
-                                hipStream_t s)
+                                hipStream_t s, bool pooled_f32)
 {
     const sp_config& c = M->cfg;
     if (!bf16_path(c) || k > 64) return hipErrorInvalidValue;
+    if (pooled_f32) {
+        hipLaunchKernelGGL((head_classify_kernel<bf16, float>), dim3(B), dim3(256), 0, s, M->arena, M->L.student_stride, M->L.wc,
+                           M->L.bc, (const float*)pooled, B, crows, c.hidden, c.classes, k, z, logits);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(head_classify_kernel<bf16>, dim3(B), dim3(256), 0, s, M->arena, M->L.student_stride, M->L.wc,
                        M->L.bc, (const bf16*)pooled, B, crows, c.hidden, c.classes, k, z, logits);
     return hipGetLastError();

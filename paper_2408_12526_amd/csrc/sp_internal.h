@@ -233,15 +233,18 @@ hipError_t launch_gemm_fp8(const sp_model* M, const void* A8, int lda, size_t w_
                            size_t o2_student_stride, float out_qscale);
 
 // y[i] = GELU as the bf16 FFN up-projection's epilogue evaluates it, in fp32 (i < n).  Test aid.
-// Last layer after its attention for the first-token rows of a call of a few sequences (see sp_gemv.hip): u is fp32
-// scratch of first_rows_tail_scratch_floats elements, g the FFN activation buffer (its first rows are used), part the
-// split-reduction buffer whose slice 0 receives the raw down-projection at the first tokens' rows (student stride
-// part_ss elements), x1 the buffer whose first-token rows receive LN(u).
+// Last layer after its attention for the first-token rows of a call of a few sequences (see sp_gemv.hip): scratch is
+// fp32 memory of first_rows_tail_scratch_floats elements, g the FFN activation buffer (its first rows are used), x1 the
+// buffer whose first-token rows receive LN(u).  Exactly one of part and pooled is given: part, the split-reduction
+// buffer whose slice 0 receives the raw down-projection at the first tokens' rows (student stride part_ss elements;
+// launch_head_small with one slice finishes the call), or pooled, fp32 [k][first_rows_tail_pooled_rows][H], whose rows
+// b receive the pooled rows (launch_head_classify with pooled_f32 finishes the call).
 bool first_rows_tail_supported(const sp_config& c, int B);
 size_t first_rows_tail_scratch_floats(const sp_config& c, int k);
+int first_rows_tail_pooled_rows();
 hipError_t launch_first_rows_tail(const sp_model* M, size_t lo, const void* att, const void* x, void* x1, void* g,
-                                  float* u, float* part, size_t part_ss, const int32_t* cu, int B, int T, int rows,
-                                  int k, hipStream_t s);
+                                  float* scratch, float* part, size_t part_ss, float* pooled, const int32_t* cu, int B,
+                                  int T, int rows, int k, hipStream_t s);
 hipError_t launch_gelu_probe(const float* x, float* y, long n, hipStream_t s);
 hipError_t launch_gelu_q8_probe(const float* x, float* y, long n, hipStream_t s);
 
@@ -286,7 +289,7 @@ hipError_t launch_attention_first_fold(const sp_model* M, const void* x, const v
 
 // Head on pooled rows: z[m][b][c] = pooled[m][b] . Wc + bc; logits[b][c] = sum_{m<k} z[m][b][c] (m ascending).
 hipError_t launch_head_classify(const sp_model* M, const void* pooled, int B, int crows, int k, float* z, float* logits,
-                                hipStream_t s);
+                                hipStream_t s, bool pooled_f32 = false);   // pooled rows bf16, or fp32 if pooled_f32
 
 // flags[0] |= SP_BAD_* bits for the inputs of a forward (flags[0] is cleared first, on the same stream).
 hipError_t launch_check_inputs(const int32_t* ids, const int32_t* cu, int B, int T, int max_seqlen, int vocab,

@@ -118,9 +118,14 @@ def test_every_stage_against_oracle_pieces(sp, oracle64, dtype, lens):
                 e = rel_err(got[name][m], want[name])
                 assert e < tol, f"layer {layer} student {m} stage {name}: rel err {e:.3e}"
         x_in = got["x"]
+    # head in isolation: pooled first-token state through the oracle's linear pieces.  (A whole forward with the last
+    # layer on every token: that is the one whose head consumes the rows the partial forward above left in `x`; with the
+    # default setting a call of a few sequences recomputes the first-token rows of the last layer another way.)
+    st.close()
+    st = sp.Students(sp.config_from_shape(shape, last_layer_all_tokens=True), blob)
     logits = st.sp_forward(d_ids, d_cu, mx, k).cpu().numpy().astype(np.float64)
     z = st.read_activation(st.workspace(T, B), "z", T, B, k)
-    for m in range(k):     # head in isolation: pooled first-token state through the oracle's linear pieces
+    for m in range(k):
         v = synth.student_views(ow, shape, m)
         pooled = np.tanh(oracle64.linear(x_in[m][cu[:-1]], v["Wp"], v["bp"]))
         assert rel_err(z[m], oracle64.linear(pooled, v["Wc"], v["bc"])) < (2e-5 if dtype == "fp32" else 2e-3)
@@ -376,13 +381,16 @@ def test_call_sizes_at_every_path_boundary(sp, oracle64, total):
 
 
 @pytest.mark.parametrize("lengths", [(64,), (1,), (128,), (17, 3), (60, 1, 67), (30, 31, 32, 33), (1, 1, 1, 1),
-                                     (25, 25, 25, 25, 25)])
+                                     (25, 25, 25, 25, 25), (129,), (300,), (100, 90), (128, 128, 128, 128),
+                                     (5, 200, 7), (1, 640, 1, 381), (640, 640), (200, 200, 200, 200, 200)])
 def test_calls_of_a_few_sequences(sp, oracle64, lengths):
-    """Whole forwards of one to four sequences (up to 128 tokens) finish their last layer on the first-token rows by
-    per-feature dot products (attention-output projection, LayerNorm, FFN, the head on the raw down-projection); five
-    sequences take the tile path.  Random LayerNorm parameters and sharpened attention, every k_active, against the
-    oracle; and the same call with the last layer on every token (the tile path) must agree with it to rounding."""
-    shape = synth.StudentShape(K=3, layers=2, hidden=256, heads=4, ffn=1024, vocab=500, max_pos=160, classes=3,
+    """Whole forwards of one to four sequences finish their last layer on the first-token rows by per-feature dot
+    products: attention-output projection, LayerNorm, FFN, and then either the small-call head on the raw
+    down-projection (up to 128 tokens) or the pooler by dot products and the classifier kernel (up to 1023 tokens; from
+    1024 on the folded first-token layer takes over); five sequences take the tile path.  Random LayerNorm parameters
+    and sharpened attention, every k_active, against the oracle; and the same call with the last layer on every token
+    (the tile path) must agree with it to rounding."""
+    shape = synth.StudentShape(K=3, layers=2, hidden=256, heads=4, ffn=1024, vocab=500, max_pos=640, classes=3,
                                dtype="bf16")
     rng = np.random.default_rng(500 + sum(lengths) + len(lengths))
     lengths = np.array(lengths, dtype=np.int32)
@@ -399,7 +407,9 @@ def test_calls_of_a_few_sequences(sp, oracle64, lengths):
         assert np.abs(want).max() > 5e-2
         check_logits(got, want, shape, f"{len(lengths)} sequences {tuple(lengths)}, k_active={k}")
         check_logits(tiles, want, shape, f"{len(lengths)} sequences {tuple(lengths)}, tile path, k_active={k}")
-        assert rel_err(got, tiles) < 1e-2
+        # (beyond 128 tokens the tile path rounds the rows before each LayerNorm to bf16 and the dot-product path does
+        # not: the two differ by about as much as either differs from the oracle)
+        assert rel_err(got, tiles) < (1e-3 if lengths.sum() <= 128 else 3e-2)
     st.close()
     st_tiles.close()
 
