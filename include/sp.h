@@ -73,7 +73,7 @@ typedef struct {
                          their queries are folded through the key projection, the other tokens' keys and
                          values are never formed, and the output projection, FFN and LayerNorms run on
                          `batch` rows (same function; the rounding points of attention differ); bf16 calls
-                         of up to four sequences and 128 tokens compute the last layer's attention for every
+                         of up to four sequences (and fewer than 1024 tokens) compute the last layer's attention for every
                          token and everything after it for the first-token rows only.  1: every token goes
                          through the whole last layer (what a stock BERT does; the fp32 path always does). */
     int32_t single_stream;
