@@ -185,6 +185,10 @@ class Students:
             self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
         return self._ws
 
+    def release_workspace(self) -> None:
+        """Drop the cached workspace tensor (the next call that needs one allocates it again)."""
+        self._ws = None
+
     def sp_forward(self, token_ids: torch.Tensor, cu_seqlens: torch.Tensor, max_seqlen: int, k_active: int,
                    logits_out: torch.Tensor | None = None, workspace: torch.Tensor | None = None, stream=None):
         """token_ids int32 [T], cu_seqlens int32 [B+1] (device).  Returns logits_out (float32 [B, C])."""

@@ -522,6 +522,40 @@ def test_partial_last_block_of_the_token_tile_order(sp, oracle64):
         st.close()
 
 
+@pytest.mark.parametrize("all_tokens", [False, True])
+def test_call_whose_buffers_pass_four_gib(sp, oracle64, all_tokens):
+    """A call of about 132 thousand tokens on the burst workload's students (2304 sequences: the burst batch's lengths
+    nine times over, fresh ids): the q|k|v buffer (4.9 GB), the FFN activations (6.5 GB) and every student's share of
+    them lie beyond what 32-bit element or byte offsets reach, and the grids are nine times those of the burst batch.
+    The first, middle and last sequences and the longest one are compared with the oracle, which computes them as a
+    batch of their own (samples are independent: pinned by test_each_sample_is_independent_of_its_batch), for all
+    eight students and for five (two groups of unequal size); the logits of the whole call must be finite and a second
+    call must repeat them bit for bit."""
+    w, batch, ow, st = loaded(sp, 4, last_layer_all_tokens=all_tokens)
+    rng = np.random.default_rng(4096)
+    lengths = np.tile(batch.lengths, 9).astype(np.int32)
+    B, T = len(lengths), int(lengths.sum())
+    assert T * 3 * w.shape.hidden * 2 * w.shape.K > 4 * 2**30 and T * 3 * w.shape.hidden > 2**28
+    ids = synth.make_ids(rng, T, w.shape.vocab)
+    d_ids, d_cu, cu = gpu_inputs(lengths, ids, sp)
+    mx = int(lengths.max())
+    longest = int(np.argmax(lengths[B // 2:])) + B // 2
+    picks = sorted({0, 1, B // 2, B // 2 + 1, longest, B - 2, B - 1})
+    sub_ids = np.concatenate([ids[cu[b]:cu[b + 1]] for b in picks])
+    sub_cu = np.concatenate([[0], np.cumsum(lengths[picks])]).astype(np.int32)
+    _, terms = oracle64.forward(ocfg(w.shape), ow, sub_ids, sub_cu, w.shape.K, want_terms=True)
+    for k in (8, 5):
+        got = st.sp_forward(d_ids, d_cu, mx, k).cpu().numpy().astype(np.float64)
+        assert got.shape == (B, w.shape.classes) and np.isfinite(got).all()
+        want = np.zeros_like(terms[0])
+        for m in range(k):
+            want = want + terms[m]
+        check_logits(got[picks], want, w.shape, f"{T} tokens, k_active={k}, sequences {picks}")
+        again = st.sp_forward(d_ids, d_cu, mx, k).cpu().numpy().astype(np.float64)
+        assert np.array_equal(got, again)
+    st.release_workspace()
+
+
 # ---- properties that hold at any size ----------------------------------------------------------------
 
 def test_prefix_property_and_determinism_at_full_size(sp):
