@@ -213,6 +213,38 @@ def test_fp8_burst_workload_part(sp, oracle64):
     st.close()
 
 
+def test_fp8_call_whose_buffers_pass_four_gib(sp, oracle64):
+    """Quantised students on a call of about 177 thousand tokens (the burst batch's lengths twelve times over, fresh
+    ids): the one-byte FFN activations (4.3 GB) as well as the bf16 q|k|v buffer lie beyond what 32-bit offsets
+    reach.  First, middle and last sequences against the oracle (computed as a batch of their own), the whole call
+    finite and repeatable bit for bit."""
+    w = synth.WORKLOADS[4]
+    shape = synth.StudentShape(**{**w.shape.__dict__, "dtype": "fp8"})
+    batch, blob = synth.make_workload(w)
+    rng = np.random.default_rng(4097)
+    lengths = np.tile(batch.lengths, 12).astype(np.int32)
+    B, T = len(lengths), int(lengths.sum())
+    assert T * shape.ffn * shape.K > 4 * 2**30
+    ids = synth.make_ids(rng, T, shape.vocab)
+    cu = sp.sp_pack(lengths)
+    st = sp.Students(sp.config_from_shape(shape), blob)
+    d_ids, d_cu = torch.from_numpy(ids).cuda(), torch.from_numpy(cu).cuda()
+    ow = dequantised_weights(blob, shape, range(shape.layers - 1))
+    picks = [0, 1, B // 2, B // 2 + 1, B - 2, B - 1]
+    sub_ids = np.concatenate([ids[cu[b]:cu[b + 1]] for b in picks])
+    sub_cu = np.concatenate([[0], np.cumsum(lengths[picks])]).astype(np.int32)
+    _, terms = oracle64.forward(ocfg(shape), ow, sub_ids, sub_cu, shape.K, want_terms=True)
+    for k in (8, 3):
+        got = st.sp_forward(d_ids, d_cu, int(lengths.max()), k).cpu().numpy().astype(np.float64)
+        assert got.shape == (B, shape.classes) and np.isfinite(got).all()
+        e = rel_err(got[picks], terms[:k].sum(0))
+        print(f"fp8 {T} tokens k_active={k}: rel err {e:.3e}", flush=True)
+        assert e <= FP8_LOGITS_REL
+        again = st.sp_forward(d_ids, d_cu, int(lengths.max()), k).cpu().numpy().astype(np.float64)
+        assert np.array_equal(got, again)
+    st.close()
+
+
 def test_fp8_large_width(sp, oracle64):
     """Quantised students at the large width (hidden 1024, 16 heads, FFN 4096: reduction depths 1024 and 4096, four and
     sixteen 256-wide feature tiles), sequences of up to 300 tokens, every sequence against the oracle."""
