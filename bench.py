@@ -72,6 +72,39 @@ def tracked_traffic():
     return None
 
 
+def vendor_bmm(torch, dev, tokens, k, shape, layers, phases, calls=50, warm=20):
+    """Calibration point, not part of the path: the four projections of one all-token layer as plain batched products
+    of the vendor library (torch.bmm, bf16, one batch entry per student: no bias, no GELU, no residual, no transposed
+    value third), on operands distributed like the workload's, timed with events on torch's stream."""
+    H, F = shape.hidden, shape.ffn
+    out, total, flops = {}, 0.0, 0.0     # phases[...]["ms"] covers `layers` all-token layers: one layer's share is compared
+    for name, (kd, n) in (("qkv", (H, 3 * H)), ("oproj", (H, H)), ("ffn_up", (H, F)), ("ffn_down", (F, H))):
+        x = torch.randn(k, tokens, kd, device=dev, dtype=torch.bfloat16)
+        wt = (torch.randn(k, kd, n, device=dev, dtype=torch.float32) * 0.02).to(torch.bfloat16)
+        o = torch.empty(k, tokens, n, device=dev, dtype=torch.bfloat16)
+        for _ in range(warm):
+            torch.bmm(x, wt, out=o)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(calls):
+            torch.bmm(x, wt, out=o)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / calls
+        total += ms
+        fl = 2.0 * k * tokens * kd * n
+        flops += fl
+        out[name] = {"ms": ms, "tflops": fl / ms / 1e9, "this_library_ms": phases[name]["ms"] / layers}
+        del x, wt, o
+    out["total"] = {"ms": total, "tflops": flops / total / 1e9, "frac": flops / total / 1e9 / PEAK_BF16_TFLOPS,
+                    "this_library_ms": phases["gemm_phase_total"]["ms"] / layers}
+    out["what"] = ("torch.bmm (bf16, batch = students) on the same four products without their epilogues, weights "
+                   "N(0, 0.02) and activations N(0, 1); this_library_ms: the launch here that includes bias, GELU, "
+                   "residual or the transposed value third")
+    return out
+
+
 def gemm_flops(shape, tokens, k, layers):
     """Algorithmic flops of the four projections over `layers` all-token layers (real tokens, not padded tile rows)."""
     H, F = shape.hidden, shape.ffn
@@ -520,6 +553,9 @@ def main():
             ceiling, note="v_mfma_f32_32x32x16_bf16 on register operands, 16 accumulator blocks per wave, one wave per "
                           "SIMD, all compute units; random mantissas are what weights and activations look like",
             gemm_phase_frac_of_random_ceiling=phases["gemm_phase_total"]["tflops"] / ceiling["operands_random_tflops"])
+
+        if not args.single_stream:      # (the profiled runs leave the vendor's kernels out of their traces)
+            phases["vendor_library_same_products"] = vendor_bmm(torch, dev, T4, 8, w4.shape, full_layers, phases)
 
         def busy():
             for _ in range(20):
