@@ -254,8 +254,17 @@ def per_config_table(sp, synth, torch, dev, calls_small, calls_large, warm):
     paper_student = synth.Workload(
         "paper_2L256D_b256", synth.StudentShape(K=3, layers=2, hidden=256, heads=4, ffn=1024, vocab=30522, max_pos=512,
                                                 classes=2), 256, ("lognormal", 48.0, 0.6, 8, 256), (1, 3))
+    deeper = synth.Workload(
+        "6L768D_b256", synth.StudentShape(K=2, layers=6, hidden=768, heads=12, ffn=3072, vocab=30522, max_pos=512,
+                                          classes=2), 256, ("lognormal", 48.0, 0.6, 8, 256), (1, 2))
+    deepest = synth.Workload(
+        "12L1024D_b64", synth.StudentShape(K=1, layers=12, hidden=1024, heads=16, ffn=4096, vocab=30522, max_pos=512,
+                                           classes=2), 64, ("uniform", 64, 512), (1,))
     todo = [(synth.WORKLOADS[n], None) for n in (1, 2, 3, 4, 5)] + [(paper_student, "the paper's own student shape "
-            "(Table 2: 2 layers, 256 wide; 1 student and the 3-student ensemble), burst-like batch of 256")]
+            "(Table 2: 2 layers, 256 wide; 1 student and the 3-student ensemble), burst-like batch of 256"),
+            (deeper, "a deeper student shape (6 layers, 768 wide: five all-token layers, then the first-token one), "
+                     "burst-like batch of 256"),
+            (deepest, "the deepest shape the parity tests cover (12 layers, 1024 wide), batch of 64 long sequences")]
     for w, note in todo:
         batch, blob = synth.make_workload(w)
         cu = sp.sp_pack(batch.lengths)
