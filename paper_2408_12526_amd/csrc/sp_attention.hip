@@ -838,13 +838,17 @@ __global__ __launch_bounds__(512, HEADS == 16 ? 2 : 4) void attention_first_fold
 }
 
 // -------------------------------------------------------------------------------------
-// fp32 kernel: one thread per query, keys streamed from global memory (all threads of a
-// workgroup read the same key row), online softmax in registers, exact division.
+// fp32 kernel: one workgroup per (student, sequence, head, block of 64 queries); four neighbouring lanes share a query,
+// sixteen of the head's 64 dimensions each (the score is summed over the quad, every lane rescales and accumulates its
+// own sixteen output dimensions).  Keys and values come through LDS in chunks of 64 tokens; all lanes of a wave read
+// the same key row (a broadcast).  Online softmax in registers, exact exponentials and division.
 // -------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void attention_f32_kernel(const float* __restrict__ qkv, float* __restrict__ att,
-                                                           const int32_t* __restrict__ cu, int B, int Tn, int rows,
-                                                           int H, int heads, int max_seqlen, int nqc)
+__global__ __launch_bounds__(256) void attention_f32_kernel(const float* __restrict__ qkv, float* __restrict__ att,
+                                                            const int32_t* __restrict__ cu, int B, int Tn, int rows,
+                                                            int H, int heads, int max_seqlen, int nqc)
 {
+    constexpr int KC = 64, DP = kD / 4;                     // keys per chunk; dimensions per lane
+    __shared__ __attribute__((aligned(16))) float Ks[KC][kD], Vs[KC][kD];
     const int m = blockIdx.y;
     int idx = blockIdx.x;
     const int qc = idx % nqc; idx /= nqc;
@@ -856,31 +860,61 @@ __global__ __launch_bounds__(64) void attention_f32_kernel(const float* __restri
     L = L < 1 ? 1 : L;
     L = L > max_seqlen ? max_seqlen : L;
     L = L > Tn - t0 ? Tn - t0 : L;
-    const int q = qc * 64 + threadIdx.x;
-    if (q >= L) return;
+    if (qc * 64 >= L) return;                               // (uniform over the workgroup)
+    const int tid = threadIdx.x, part = tid & 3, q = qc * 64 + (tid >> 2);
+    const bool live = q < L;
     const size_t ld = (size_t)3 * H;
     const float* base = qkv + ((size_t)m * rows + t0) * ld + h * kD;
-    float qv[kD], o[kD];
+    float qv[DP], o[DP];
 #pragma unroll
-    for (int e = 0; e < kD; ++e) { qv[e] = base[(size_t)q * ld + e]; o[e] = 0.f; }
-    float mrun = -INFINITY, lrun = 0.f;
-    for (int key = 0; key < L; ++key) {
-        const float* kr = base + (size_t)key * ld + H;
-        const float* vr = kr + H;
-        float sdot = 0.f;
+    for (int e4 = 0; e4 < DP; e4 += 4) {
+        const f32x4 t = live ? *(const f32x4*)(base + (size_t)q * ld + DP * part + e4) : f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int e = 0; e < kD; ++e) sdot = fmaf(qv[e], kr[e], sdot);
-        sdot *= 0.125f;
-        const float mx = fmaxf(mrun, sdot);
-        const float alpha = expf(mrun - mx), p = expf(sdot - mx);
-        lrun = lrun * alpha + p;
-#pragma unroll
-        for (int e = 0; e < kD; ++e) o[e] = o[e] * alpha + p * vr[e];
-        mrun = mx;
+        for (int e = 0; e < 4; ++e) { qv[e4 + e] = t[e]; o[e4 + e] = 0.f; }
     }
-    float* dst = att + ((size_t)m * rows + t0 + q) * H + h * kD;
+    float mrun = -INFINITY, lrun = 0.f;
+    for (int kt0 = 0; kt0 < L; kt0 += KC) {
+        const int nk = L - kt0 < KC ? L - kt0 : KC;
+        __syncthreads();                                    // the previous chunk has been read by everybody
 #pragma unroll
-    for (int e = 0; e < kD; ++e) dst[e] = o[e] / lrun;
+        for (int i = 0; i < KC * kD / 4 / 256; ++i) {
+            const int c = tid + 256 * i, key = c >> 4, d = (c & 15) * 4;
+            if (key < nk) {
+                const float* kr = base + (size_t)(kt0 + key) * ld + H + d;
+                *(f32x4*)&Ks[key][d] = *(const f32x4*)kr;
+                *(f32x4*)&Vs[key][d] = *(const f32x4*)(kr + H);
+            }
+        }
+        __syncthreads();
+        for (int key = 0; key < nk; ++key) {
+            float sdot = 0.f;
+#pragma unroll
+            for (int e4 = 0; e4 < DP; e4 += 4) {
+                const f32x4 kv = *(const f32x4*)&Ks[key][DP * part + e4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) sdot = fmaf(qv[e4 + e], kv[e], sdot);
+            }
+            sdot += dpp_moved<kDppPair>(sdot);              // the four lanes of a query: every one ends with the whole sum
+            sdot += dpp_moved<kDppQuad>(sdot);
+            sdot *= 0.125f;
+            const float mx = fmaxf(mrun, sdot);
+            const float alpha = expf(mrun - mx), p = expf(sdot - mx);
+            lrun = lrun * alpha + p;
+#pragma unroll
+            for (int e4 = 0; e4 < DP; e4 += 4) {
+                const f32x4 vv = *(const f32x4*)&Vs[key][DP * part + e4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e4 + e] = o[e4 + e] * alpha + p * vv[e];
+            }
+            mrun = mx;
+        }
+    }
+    if (live) {
+        float* dst = att + ((size_t)m * rows + t0 + q) * H + h * kD + DP * part;
+#pragma unroll
+        for (int e4 = 0; e4 < DP; e4 += 4)
+            *(f32x4*)(dst + e4) = f32x4{o[e4] / lrun, o[e4 + 1] / lrun, o[e4 + 2] / lrun, o[e4 + 3] / lrun};
+    }
 }
 
 }  // namespace
@@ -919,7 +953,7 @@ hipError_t launch_attention(const sp_model* M, const void* qkv, const void* vt, 
     } else {
         const int nqc = (max_seqlen + 63) / 64;
         dim3 grid((unsigned)(B * c.heads * nqc), k);
-        hipLaunchKernelGGL(attention_f32_kernel, grid, dim3(64), 0, s, (const float*)qkv, (float*)att, cu, B, T, rows,
+        hipLaunchKernelGGL(attention_f32_kernel, grid, dim3(256), 0, s, (const float*)qkv, (float*)att, cu, B, T, rows,
                            c.hidden, c.heads, max_seqlen, nqc);
     }
     return hipGetLastError();

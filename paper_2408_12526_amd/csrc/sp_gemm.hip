@@ -485,56 +485,69 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
 }
 
 // -------------------------------------------------------------------------------------
-// fp32 kernel: 64x64 tile, 16x16 threads, 4x4 outputs per thread, FMA only.
+// fp32 kernel: square tile of 16 TS rows x 16 TS features (TS = 4: 64 x 64, TS = 2: 32 x 32 for calls whose larger
+// tiles would leave most compute units idle), 16 x 16 threads with TS x TS outputs each, FMA only, the reduction index
+// ascending for every output.  Slabs of 64 along the reduction: the next slab's rows are requested (into registers)
+// before the current one is multiplied, so a slab costs one memory round trip or its arithmetic, whichever is longer.
 // -------------------------------------------------------------------------------------
-template <int EPI>
+template <int EPI, int TS>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__ A, int lda, size_t a_ss,
                                                        const char* __restrict__ arena, size_t student_stride,
                                                        size_t w_off, size_t b_off, float* __restrict__ out, int ldo,
                                                        size_t o_ss, const float* __restrict__ res, int ldr,
                                                        size_t r_ss, int Kd)
 {
-    __shared__ float As[16][68], Ws[16][68];
-    const int m = blockIdx.z, m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+    constexpr int BT = 16 * TS, BK = 64, PITCH = BT + 4;
+    constexpr int LPT = BT * BK / 4 / 256;                  // 16-byte loads per thread and operand: 16 rows apart
+    typedef float fts __attribute__((ext_vector_type(TS)));
+    __shared__ float As[BK][PITCH], Ws[BK][PITCH];
+    const int m = blockIdx.z, m0 = blockIdx.y * BT, n0 = blockIdx.x * BT;
     const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
     const float* Ag = A + (size_t)m * a_ss + (size_t)m0 * lda;
     const float* Wg = (const float*)(arena + (size_t)m * student_stride + w_off) + (size_t)n0 * Kd;
-    const int lr = tid >> 2, lk = (tid & 3) * 4;
-    float acc[4][4] = {};
-    for (int k0 = 0; k0 < Kd; k0 += 16) {
-        const f32x4 a = *(const f32x4*)(Ag + (size_t)lr * lda + k0 + lk);
-        const f32x4 w = *(const f32x4*)(Wg + (size_t)lr * Kd + k0 + lk);
+    const int lr = tid >> 4, lk = (tid & 15) * 4;           // loader: row lr + 16 i of the tile, reduction elements lk .. lk + 3
+    f32x4 pa[LPT], pw[LPT];
+    auto request = [&](int k0) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) { As[lk + e][lr] = a[e]; Ws[lk + e][lr] = w[e]; }
+        for (int i = 0; i < LPT; ++i) {
+            pa[i] = *(const f32x4*)(Ag + (size_t)(lr + 16 * i) * lda + k0 + lk);
+            pw[i] = *(const f32x4*)(Wg + (size_t)(lr + 16 * i) * Kd + k0 + lk);
+        }
+    };
+    float acc[TS][TS] = {};
+    request(0);
+    for (int k0 = 0; k0 < Kd; k0 += BK) {
+#pragma unroll
+        for (int i = 0; i < LPT; ++i)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { As[lk + e][lr + 16 * i] = pa[i][e]; Ws[lk + e][lr + 16 * i] = pw[i][e]; }
         __syncthreads();
+        if (k0 + BK < Kd) request(k0 + BK);
+#pragma unroll 16
+        for (int kk = 0; kk < BK; ++kk) {
+            const fts a = *(const fts*)&As[kk][ty * TS];
+            const fts w = *(const fts*)&Ws[kk][tx * TS];
 #pragma unroll
-        for (int kk = 0; kk < 16; ++kk) {
-            const f32x4 a4 = *(const f32x4*)&As[kk][ty * 4];
-            const f32x4 w4 = *(const f32x4*)&Ws[kk][tx * 4];
+            for (int i = 0; i < TS; ++i)
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a4[i], w4[j], acc[i][j]);
+                for (int j = 0; j < TS; ++j) acc[i][j] = fmaf(a[i], w[j], acc[i][j]);
         }
         __syncthreads();
     }
     const float* bias = (const float*)(arena + (size_t)m * student_stride + b_off);
-    const f32x4 b4 = *(const f32x4*)(bias + n0 + tx * 4);
+    const fts bv = *(const fts*)(bias + n0 + tx * TS);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const size_t row = (size_t)(m0 + ty * 4 + i);
-        f32x4 r;
+    for (int i = 0; i < TS; ++i) {
+        const size_t row = (size_t)(m0 + ty * TS + i);
+        fts r;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) r[j] = acc[i][j] + b4[j];
+        for (int j = 0; j < TS; ++j) r[j] = acc[i][j] + bv[j];
         if (EPI == EPI_BIAS_GELU) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) r[j] = gelu_erf(r[j]);
+            for (int j = 0; j < TS; ++j) r[j] = gelu_erf(r[j]);
         }
-        if (EPI == EPI_BIAS_RESIDUAL) {
-            const f32x4 x4 = *(const f32x4*)(res + (size_t)m * r_ss + row * ldr + n0 + tx * 4);
-            r += x4;
-        }
-        *(f32x4*)(out + (size_t)m * o_ss + row * ldo + n0 + tx * 4) = r;
+        if (EPI == EPI_BIAS_RESIDUAL) r += *(const fts*)(res + (size_t)m * r_ss + row * ldr + n0 + tx * TS);
+        *(fts*)(out + (size_t)m * o_ss + row * ldo + n0 + tx * TS) = r;
     }
 }
 
@@ -599,10 +612,18 @@ hipError_t launch_f32(const sp_model* M, const void* A, int lda, size_t w_off, s
                       const void* residual, int ldr, int mrows, int N, int Kd, int k, size_t a_ss, size_t o_ss,
                       size_t r_ss, hipStream_t s)
 {
-    dim3 grid(N / 64, mrows / 64, k);
-    hipLaunchKernelGGL(gemm_f32_kernel<EPI>, grid, dim3(256), 0, s, (const float*)A, lda, a_ss / 4, M->arena,
-                       M->L.student_stride, w_off, b_off, (float*)out, ldo, o_ss / 4, (const float*)residual, ldr,
-                       r_ss / 4, Kd);
+    // (rows and widths are multiples of 64 and the reduction depth of 128: the launcher's callers see to that)
+    if (mrows % 64 || N % 64 || Kd % 64) return hipErrorInvalidValue;
+    // 64 x 64 tiles when they give every compute unit a few workgroups; else 32 x 32 tiles, four times as many
+    if ((long)(N / 64) * (mrows / 64) * k >= 1024) {
+        hipLaunchKernelGGL((gemm_f32_kernel<EPI, 4>), dim3(N / 64, mrows / 64, k), dim3(256), 0, s, (const float*)A, lda,
+                           a_ss / 4, M->arena, M->L.student_stride, w_off, b_off, (float*)out, ldo, o_ss / 4,
+                           (const float*)residual, ldr, r_ss / 4, Kd);
+    } else {
+        hipLaunchKernelGGL((gemm_f32_kernel<EPI, 2>), dim3(N / 32, mrows / 32, k), dim3(256), 0, s, (const float*)A, lda,
+                           a_ss / 4, M->arena, M->L.student_stride, w_off, b_off, (float*)out, ldo, o_ss / 4,
+                           (const float*)residual, ldr, r_ss / 4, Kd);
+    }
     return hipGetLastError();
 }
 
