@@ -346,6 +346,31 @@ def test_large_calls_on_other_widths(sp, oracle64, name):
     check_logits(got2[pick], want, shape, name + " all-token last layer")
 
 
+def test_fp32_large_call(sp, oracle64):
+    """The fp32 path on a call large enough for its 64 x 64 projection tile (a grid of at least 1024 such tiles: the
+    q|k|v and FFN up-projections here; the two residual projections stay on the 32 x 32 tile), sequences of up to 300
+    tokens (several key chunks and query blocks in the fp32 attention kernel), every sequence against the oracle to the
+    fp32 bound."""
+    shape = synth.StudentShape(K=2, layers=2, hidden=128, heads=2, ffn=512, vocab=1000, max_pos=320, classes=3,
+                               dtype="fp32")
+    rng = np.random.default_rng(43)
+    lengths = rng.integers(1, 301, size=40).astype(np.int32)
+    lengths[:3] = (300, 1, 65)
+    total = int(lengths.sum())
+    assert (shape.ffn // 64) * ((total + 255) // 256 * 4) * shape.K >= 1024, total
+    ids = synth.make_ids(rng, total, shape.vocab)
+    blob = synth.make_weights(rng, shape, std=0.02, ln_random=True, qk_std=float(np.sqrt(1.5 / shape.hidden)))
+    st = sp.Students(sp.config_from_shape(shape), blob)
+    d_ids, d_cu, cu = gpu_inputs(lengths, ids, sp)
+    want = oracle64.forward(ocfg(shape), blob, ids, cu, shape.K)
+    for k in (2, 1):
+        got = st.sp_forward(d_ids, d_cu, int(lengths.max()), k).cpu().numpy().astype(np.float64)
+        ref = want if k == 2 else oracle64.forward(ocfg(shape), blob, ids, cu, 1)
+        err = check_logits(got, ref, shape, f"fp32, {total} tokens, k_active={k}")
+        assert err < 1e-4
+    st.close()
+
+
 BOUNDARY_TOKENS = [63, 64, 65, 127, 128, 129, 255, 256, 257, 1023, 1024, 1025, 2047, 2048, 2049]
 
 
