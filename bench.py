@@ -463,6 +463,9 @@ def main():
                     help="load the students with sp_config.single_stream = 1: every call stays on one stream instead of "
                          "running two groups of students side by side (the configuration the per-kernel profiles use: "
                          "one launch of each kernel per layer, all active students in it)")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="with the burst leg: also time the vendor library's batched products (torch.bmm) on the four "
+                         "projections of the burst workload, as a calibration point beside phases_k8")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device-to-device copy a few times (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -563,7 +566,7 @@ def main():
                           "SIMD, all compute units; random mantissas are what weights and activations look like",
             gemm_phase_frac_of_random_ceiling=phases["gemm_phase_total"]["tflops"] / ceiling["operands_random_tflops"])
 
-        if not args.single_stream:      # (the profiled runs leave the vendor's kernels out of their traces)
+        if args.vendor_gemm:
             phases["vendor_library_same_products"] = vendor_bmm(torch, dev, T4, 8, w4.shape, full_layers, phases)
 
         def busy():
