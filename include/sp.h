@@ -133,7 +133,8 @@ int sp_load_students(const sp_config* cfg, const float* host_weights, size_t nfl
  *   workspace    device, 256-byte aligned, >= sp_workspace_bytes(cfg,
  *                total_tokens, batch); contents undefined afterwards; calls
  *                that may overlap in time need separate workspaces
- *   logits_out   device float32 [batch][classes] row-major, overwritten
+ *   logits_out   device float32 [batch][classes] row-major, overwritten (written once, never read: pinned host memory
+ *                that the device can address will do as well, through its device pointer)
  *   hip_stream   hipStream_t (or NULL); kernels are enqueued there
  * Contents of token_ids / cu_seqlens are not inspected on the host (that
  * would need a synchronisation): ids outside the vocabulary or inconsistent
