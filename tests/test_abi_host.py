@@ -104,3 +104,15 @@ def test_e4m3_encoder_matches_the_library_conversion_bit_for_bit(sp):
     # (-0.0 and +0.0: both conversions keep the sign bit)
     assert bad.size == 0, f"{bad.size} codes differ, first at x = {x[bad[0]]!r}: {got[bad[0]]:#x} vs {want[bad[0]]:#x}"
     assert sp.sp_probe_e4m3(np.array([1e9, -1e9, 464.0], np.float32)).tolist() == [0x7e, 0xfe, 0x7e]   # saturating
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asked for more it says so and exits (before anything touches a GPU)."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stdout + r.stderr)
