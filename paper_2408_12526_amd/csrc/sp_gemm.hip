@@ -551,6 +551,96 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
     }
 }
 
+// The same product for deep reductions on small grids (the FFN down-projection of a call of a few dozen tokens): one
+// 32 x 32 tile per workgroup, the reduction range split over its four waves (a quarter each, ascending inside it, 4 x 4
+// outputs per lane, wave-private slabs of 32 along the reduction), the four partial tiles added in wave order through
+// LDS.  A single chain over the whole depth costs one memory round trip per slab; here a wave has four slabs in flight
+// at once and a quarter of the depth to walk.  Kd must be a multiple of 512 (a wave's quarter: whole groups of four slabs).
+template <int EPI, int TS>
+__global__ __launch_bounds__(256) void gemm_f32_ksplit_kernel(const float* __restrict__ A, int lda, size_t a_ss,
+                                                              const char* __restrict__ arena, size_t student_stride,
+                                                              size_t w_off, size_t b_off, float* __restrict__ out,
+                                                              int ldo, size_t o_ss, const float* __restrict__ res,
+                                                              int ldr, size_t r_ss, int Kd)
+{
+    // tile of 8 TS x 8 TS outputs (TS = 4: 32 x 32; TS = 2: 16 x 16, four times the workgroups, when even the 32 x 32
+    // tiles would leave most of the chip idle); a lane owns TS x TS of them
+    constexpr int BT = 8 * TS, BK = 32, PITCH = BT + 4, SLAB = BK * PITCH;
+    typedef float fts __attribute__((ext_vector_type(TS)));
+    __shared__ __attribute__((aligned(16))) float lds[4 * 2 * SLAB];   // per wave: activation slab, weight slab
+    const int m = blockIdx.z, m0 = blockIdx.y * BT, n0 = blockIdx.x * BT;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tx = lane & 7, ty = lane >> 3;                // this lane's outputs: rows TS ty .., features TS tx ..
+    const int kw = Kd / 4, kb = wave * kw;
+    const float* Ag = A + (size_t)m * a_ss + (size_t)m0 * lda + kb;
+    const float* Wg = (const float*)(arena + (size_t)m * student_stride + w_off) + (size_t)n0 * Kd + kb;
+    float* As = lds + wave * 2 * SLAB;
+    float* Ws = As + SLAB;
+    // A wave requests four slabs (128 of its reduction range: all of it at a depth of 512) before it uses the first, so
+    // their memory round trips overlap; then slab after slab goes through the wave's LDS and is multiplied.
+    constexpr int NSL = 4, LPT = BT * BK / 4 / 64;          // 16-byte loads per lane, slab and operand
+    f32x4 pa[NSL][LPT], pw[NSL][LPT];
+    float acc[TS][TS] = {};
+    for (int kc0 = 0; kc0 < kw; kc0 += NSL * BK) {
+#pragma unroll
+        for (int sl = 0; sl < NSL; ++sl)
+#pragma unroll
+            for (int i = 0; i < LPT; ++i) {
+                const int idx = lane + 64 * i, row = idx >> 3, kc = (idx & 7) * 4;
+                pa[sl][i] = *(const f32x4*)(Ag + (size_t)row * lda + kc0 + sl * BK + kc);
+                pw[sl][i] = *(const f32x4*)(Wg + (size_t)row * Kd + kc0 + sl * BK + kc);
+            }
+#pragma unroll
+        for (int sl = 0; sl < NSL; ++sl) {
+#pragma unroll
+            for (int i = 0; i < LPT; ++i) {
+                const int idx = lane + 64 * i, row = idx >> 3, kc = (idx & 7) * 4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    As[(kc + e) * PITCH + row] = pa[sl][i][e];
+                    Ws[(kc + e) * PITCH + row] = pw[sl][i][e];
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll 8
+            for (int kk = 0; kk < BK; ++kk) {
+                const fts a = *(const fts*)&As[kk * PITCH + ty * TS];
+                const fts w = *(const fts*)&Ws[kk * PITCH + tx * TS];
+#pragma unroll
+                for (int i = 0; i < TS; ++i)
+#pragma unroll
+                    for (int j = 0; j < TS; ++j) acc[i][j] = fmaf(a[i], w[j], acc[i][j]);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();                // the slab is rewritten only after every lane has read it
+        }
+    }
+    // partial tiles -> LDS (over the slabs, which nobody reads any more), then summed in wave order
+    __syncthreads();
+    float* red = lds;                                       // [wave][row][PITCH]
+#pragma unroll
+    for (int i = 0; i < TS; ++i)
+#pragma unroll
+        for (int jj = 0; jj < TS; ++jj) red[(wave * BT + ty * TS + i) * PITCH + tx * TS + jj] = acc[i][jj];
+    __syncthreads();
+    constexpr int OUTS = BT * BT / 256, TPR = BT / OUTS;    // outputs per thread (neighbours in a row); threads per row
+    const int r = tid / TPR, c0 = (tid % TPR) * OUTS;
+    const float* bias = (const float*)(arena + (size_t)m * student_stride + b_off);
+    const size_t row = (size_t)(m0 + r);
+#pragma unroll
+    for (int o = 0; o < OUTS; ++o) {
+        const int c = c0 + o;
+        float v = red[r * PITCH + c];
+#pragma unroll
+        for (int wv = 1; wv < 4; ++wv) v += red[(wv * BT + r) * PITCH + c];
+        v += bias[n0 + c];
+        if (EPI == EPI_BIAS_GELU) v = gelu_erf(v);
+        if (EPI == EPI_BIAS_RESIDUAL) v += res[(size_t)m * r_ss + row * ldr + n0 + c];
+        out[(size_t)m * o_ss + row * ldo + n0 + c] = v;
+    }
+}
+
 template <int BM, int BN, int EPI>
 hipError_t launch_bf16_tile(const sp_model* M, const void* A, int lda, size_t w_off, size_t b_off, void* out, int ldo,
                             const void* residual, int ldr, int mrows, int N, int Kd, int k, size_t a_ss, size_t o_ss,
@@ -619,6 +709,16 @@ hipError_t launch_f32(const sp_model* M, const void* A, int lda, size_t w_off, s
         hipLaunchKernelGGL((gemm_f32_kernel<EPI, 4>), dim3(N / 64, mrows / 64, k), dim3(256), 0, s, (const float*)A, lda,
                            a_ss / 4, M->arena, M->L.student_stride, w_off, b_off, (float*)out, ldo, o_ss / 4,
                            (const float*)residual, ldr, r_ss / 4, Kd);
+    } else if (Kd >= 512 && Kd % 512 == 0 && (long)(N / 32) * (mrows / 32) * k <= 256) {
+        // few tiles and a deep reduction: the reduction range over the four waves of a workgroup
+        if ((long)(N / 32) * (mrows / 32) * k < 128)
+            hipLaunchKernelGGL((gemm_f32_ksplit_kernel<EPI, 2>), dim3(N / 16, mrows / 16, k), dim3(256), 0, s,
+                               (const float*)A, lda, a_ss / 4, M->arena, M->L.student_stride, w_off, b_off, (float*)out,
+                               ldo, o_ss / 4, (const float*)residual, ldr, r_ss / 4, Kd);
+        else
+            hipLaunchKernelGGL((gemm_f32_ksplit_kernel<EPI, 4>), dim3(N / 32, mrows / 32, k), dim3(256), 0, s,
+                               (const float*)A, lda, a_ss / 4, M->arena, M->L.student_stride, w_off, b_off, (float*)out,
+                               ldo, o_ss / 4, (const float*)residual, ldr, r_ss / 4, Kd);
     } else {
         hipLaunchKernelGGL((gemm_f32_kernel<EPI, 2>), dim3(N / 32, mrows / 32, k), dim3(256), 0, s, (const float*)A, lda,
                            a_ss / 4, M->arena, M->L.student_stride, w_off, b_off, (float*)out, ldo, o_ss / 4,

@@ -371,6 +371,31 @@ def test_fp32_large_call(sp, oracle64):
     st.close()
 
 
+@pytest.mark.parametrize("nseq", [3, 24])
+def test_fp32_deep_reduction_on_small_grids(sp, oracle64, nseq):
+    """The fp32 FFN down-projection (reduction depth 512) on calls too small to fill the chip with tiles: the reduction
+    range is split over the waves of a workgroup, with 16 x 16 tiles for the smallest calls (3 sequences, about a
+    hundred tokens) and 32 x 32 tiles for the next size (24 sequences, about 800 tokens).  Every sequence against the
+    oracle."""
+    shape = synth.StudentShape(K=2, layers=2, hidden=128, heads=2, ffn=512, vocab=1000, max_pos=64, classes=3,
+                               dtype="fp32")
+    rng = np.random.default_rng(47 + nseq)
+    lengths = rng.integers(20, 49, size=nseq).astype(np.int32)
+    total = int(lengths.sum())
+    mtile = 256 if total > 256 else (128 if total > 64 else 64)
+    tiles = (shape.hidden // 32) * ((total + mtile - 1) // mtile * mtile // 32) * shape.K
+    assert (tiles < 128) if nseq == 3 else (128 <= tiles <= 256), (total, tiles)
+    ids = synth.make_ids(rng, total, shape.vocab)
+    blob = synth.make_weights(rng, shape, std=0.05, ln_random=True, qk_std=0.12)
+    st = sp.Students(sp.config_from_shape(shape), blob)
+    d_ids, d_cu, cu = gpu_inputs(lengths, ids, sp)
+    got = st.sp_forward(d_ids, d_cu, int(lengths.max()), shape.K).cpu().numpy().astype(np.float64)
+    want = oracle64.forward(ocfg(shape), blob, ids, cu, shape.K)
+    assert np.abs(want).max() > 5e-2
+    assert check_logits(got, want, shape, f"fp32, {total} tokens") < 1e-4
+    st.close()
+
+
 BOUNDARY_TOKENS = [63, 64, 65, 127, 128, 129, 255, 256, 257, 1023, 1024, 1025, 2047, 2048, 2049]
 
 
