@@ -670,6 +670,37 @@ def test_forward_can_be_captured_in_a_graph(sp):
         torch.cuda.synchronize()
 
 
+def test_small_call_can_be_captured_in_a_graph(sp):
+    """The same for the path of a single short sequence (split reductions, per-feature dot products, the small-call
+    head: a dozen and a half launches on one stream), at two student numbers."""
+    w, batch, _, st = loaded(sp, 3)
+    d_ids, d_cu, cu = gpu_inputs(batch.lengths, batch.ids, sp)
+    mx, B = int(batch.lengths.max()), len(batch.lengths)
+    ws = st.workspace(int(cu[-1]), B)
+    side = torch.cuda.Stream()
+    for k in (8, 3):
+        out = torch.empty(B, w.shape.classes, dtype=torch.float32, device="cuda")
+        st.sp_forward(d_ids, d_cu, mx, k, out, ws)
+        torch.cuda.synchronize()
+        ref = out.clone()
+        with torch.cuda.stream(side):
+            st.sp_forward(d_ids, d_cu, mx, k, out, ws, stream=side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            st.sp_forward(d_ids, d_cu, mx, k, out, ws, stream=side)
+        torch.cuda.synchronize()
+        for i in range(3):
+            out.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out, ref), f"k_active={k}, replay {i}"
+            st.sp_forward(d_ids, d_cu, mx, 1, out, ws)     # eager work between the replays
+            torch.cuda.synchronize()
+        del graph
+
+
 def test_sample_is_independent_of_batch_mates(sp):
     """A sequence's logits do not depend on where it sits in the packed batch (bitwise in the fp32 path)."""
     w = synth.WORKLOADS[1]
